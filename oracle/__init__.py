@@ -1,0 +1,175 @@
+"""CPU oracle for lossless sparse weight synchronisation -- TEST INFRASTRUCTURE.
+
+Thin numpy/ctypes front end of ``srs_oracle.c`` (a plain single-threaded C
+statement of Alg. 1's changed-index set, Alg. 2's ``V = W[I]`` and Alg. 3's
+scatter, with bit-pattern comparison as goal G1 requires).  Only the tests,
+the smoke check and the benchmark's CPU-baseline leg may import this package;
+it shares nothing with the GPU library and never imports it.
+
+All weights are numpy ``uint16`` arrays (BF16 bit patterns); indices are
+``int32``; counts are ``uint32``.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+import subprocess
+from typing import List, Sequence, Tuple
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "srs_oracle.c")
+_LIB = os.path.join(_HERE, "libsrs_oracle.so")
+
+OK = 0
+BAD_ARG = -1
+BAD_INDEX = -2
+
+
+def build(force: bool = False) -> str:
+    """Compile ``srs_oracle.c`` with gcc (plain -O2, no OpenMP, no tuning)."""
+    stale = (not os.path.exists(_LIB)) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC)
+    if force or stale:
+        subprocess.check_call(["gcc", "-O2", "-Wall", "-Wextra", "-shared", "-fPIC", "-o", _LIB, _SRC])
+    return _LIB
+
+
+_lib = None
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        lib = C.CDLL(build())
+        u16p, i32p, u32p, u64p = (C.POINTER(C.c_uint16), C.POINTER(C.c_int32),
+                                  C.POINTER(C.c_uint32), C.POINTER(C.c_uint64))
+        lib.srs_oracle_extract.restype = C.c_int
+        lib.srs_oracle_extract.argtypes = [u16p, u16p, C.c_uint64, C.c_uint64, i32p, u16p, u32p, C.c_uint64, C.c_int]
+        lib.srs_oracle_apply.restype = C.c_int
+        lib.srs_oracle_apply.argtypes = [u16p, C.c_uint64, C.c_uint64, i32p, u16p, u32p, C.c_uint64]
+        pp = C.POINTER(u16p)
+        lib.srs_oracle_extract_multi.restype = C.c_int
+        lib.srs_oracle_extract_multi.argtypes = [pp, pp, u64p, C.c_uint32, C.c_uint64, C.c_uint64, C.c_uint64,
+                                                 i32p, u16p, u32p, C.c_uint64, C.c_int]
+        lib.srs_oracle_apply_multi.restype = C.c_int
+        lib.srs_oracle_apply_multi.argtypes = [pp, u64p, C.c_uint32, C.c_uint64, C.c_uint64, C.c_uint64,
+                                               i32p, u16p, u32p, C.c_uint64]
+        lib.srs_oracle_num_buckets.restype = C.c_uint64
+        lib.srs_oracle_num_buckets.argtypes = [u64p, C.c_uint32, C.c_uint64]
+        _lib = lib
+    return _lib
+
+
+def _u16(a: np.ndarray, writable: bool = False) -> np.ndarray:
+    if not isinstance(a, np.ndarray) or a.dtype != np.uint16 or a.ndim != 1 or not a.flags.c_contiguous:
+        raise TypeError("oracle expects 1-D contiguous numpy uint16 arrays")
+    if writable and not a.flags.writeable:
+        raise TypeError("array must be writable")
+    return a
+
+
+def _p(a: np.ndarray, ct):
+    return a.ctypes.data_as(C.POINTER(ct))
+
+
+def num_buckets(n: int, be: int) -> int:
+    return (n + be - 1) // be
+
+
+def extract(old: np.ndarray, new: np.ndarray, be: int, cap: int | None = None, refresh: bool = True
+            ) -> Tuple[np.ndarray, np.ndarray, np.ndarray, int]:
+    """Single tensor.  Returns (I[nb, cap] int32, V[nb, cap] uint16, counts[nb] uint32, n_overflowed).
+
+    ``old`` is refreshed in place to ``new`` when ``refresh`` is true.  Unused payload slots hold
+    I = -1, V = 0xFFFF (fill values chosen by this wrapper, never by the C code)."""
+    lib = _load()
+    _u16(old, True), _u16(new)
+    n = old.size
+    if new.size != n:
+        raise ValueError("size mismatch")
+    cap = be if cap is None else cap
+    nb = num_buckets(n, be) if be else 0
+    I = np.full((nb, max(cap, 0)), -1, np.int32)
+    V = np.full((nb, max(cap, 0)), 0xFFFF, np.uint16)
+    counts = np.zeros(nb, np.uint32)
+    rc = lib.srs_oracle_extract(_p(old, C.c_uint16), _p(new, C.c_uint16), n, be,
+                                _p(I, C.c_int32), _p(V, C.c_uint16), _p(counts, C.c_uint32), cap, int(refresh))
+    if rc < 0:
+        raise ValueError(f"srs_oracle_extract: bad argument ({rc})")
+    return I, V, counts, rc
+
+
+def apply(w: np.ndarray, be: int, I: np.ndarray, V: np.ndarray, counts: np.ndarray) -> int:
+    """Single tensor scatter, in place.  Returns OK or BAD_INDEX."""
+    lib = _load()
+    _u16(w, True)
+    I = np.ascontiguousarray(I, np.int32)
+    V = np.ascontiguousarray(V, np.uint16)
+    counts = np.ascontiguousarray(counts, np.uint32)
+    cap = I.shape[1] if I.ndim == 2 else (I.size // max(counts.size, 1))
+    rc = lib.srs_oracle_apply(_p(w, C.c_uint16), w.size, be, _p(I, C.c_int32), _p(V, C.c_uint16),
+                              _p(counts, C.c_uint32), cap)
+    if rc == BAD_ARG:
+        raise ValueError("srs_oracle_apply: bad argument")
+    return rc
+
+
+def _ptr_array(arrs: Sequence[np.ndarray | None]):
+    T = C.POINTER(C.c_uint16)
+    out = (T * max(len(arrs), 1))()
+    for k, a in enumerate(arrs):
+        out[k] = _p(a, C.c_uint16) if a is not None else T()
+    return out
+
+
+def extract_multi(old: Sequence[np.ndarray | None], new: Sequence[np.ndarray | None], numel: Sequence[int],
+                  be: int, cap: int | None = None, b_lo: int = 0, b_hi: int | None = None, refresh: bool = True
+                  ) -> Tuple[np.ndarray, np.ndarray, np.ndarray, int]:
+    """Tensor list laid end to end; buckets b_lo <= b < b_hi.  Index = position inside the bucket.
+
+    Tensors wholly outside the bucket range may be None."""
+    lib = _load()
+    nt = len(numel)
+    for a in old:
+        if a is not None:
+            _u16(a, True)
+    for a in new:
+        if a is not None:
+            _u16(a)
+    ne = np.asarray(list(numel), np.uint64)
+    for k in range(nt):
+        if old[k] is not None and (old[k].size != ne[k] or new[k].size != ne[k]):
+            raise ValueError("numel mismatch")
+    nb = num_buckets(int(ne.sum()), be) if be else 0
+    b_hi = nb if b_hi is None else b_hi
+    cap = be if cap is None else cap
+    m = max(b_hi - b_lo, 0)
+    I = np.full((m, max(cap, 0)), -1, np.int32)
+    V = np.full((m, max(cap, 0)), 0xFFFF, np.uint16)
+    counts = np.zeros(m, np.uint32)
+    rc = lib.srs_oracle_extract_multi(_ptr_array(old), _ptr_array(new), _p(ne, C.c_uint64), nt, be, b_lo, b_hi,
+                                      _p(I, C.c_int32), _p(V, C.c_uint16), _p(counts, C.c_uint32), cap, int(refresh))
+    if rc < 0:
+        raise ValueError(f"srs_oracle_extract_multi: bad argument ({rc})")
+    return I, V, counts, rc
+
+
+def apply_multi(w: Sequence[np.ndarray | None], numel: Sequence[int], be: int,
+                I: np.ndarray, V: np.ndarray, counts: np.ndarray, b_lo: int = 0, b_hi: int | None = None) -> int:
+    lib = _load()
+    for a in w:
+        if a is not None:
+            _u16(a, True)
+    ne = np.asarray(list(numel), np.uint64)
+    nb = num_buckets(int(ne.sum()), be) if be else 0
+    b_hi = nb if b_hi is None else b_hi
+    I = np.ascontiguousarray(I, np.int32)
+    V = np.ascontiguousarray(V, np.uint16)
+    counts = np.ascontiguousarray(counts, np.uint32)
+    cap = I.shape[1] if I.ndim == 2 else (I.size // max(counts.size, 1))
+    rc = lib.srs_oracle_apply_multi(_ptr_array(w), _p(ne, C.c_uint64), len(numel), be, b_lo, b_hi,
+                                    _p(I, C.c_int32), _p(V, C.c_uint16), _p(counts, C.c_uint32), cap)
+    if rc == BAD_ARG:
+        raise ValueError("srs_oracle_apply_multi: bad argument")
+    return rc

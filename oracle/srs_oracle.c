@@ -1,0 +1,190 @@
+/*
+ * srs_oracle.c -- TEST INFRASTRUCTURE, NOT PRODUCT CODE.
+ *
+ * A plain, slow, single-threaded CPU statement of what lossless sparse weight
+ * synchronisation computes.  It exists so that the GPU library can be checked
+ * against something written independently of it: it shares no code, header,
+ * table or helper with the HIP path, and only the tests, the smoke check and
+ * the benchmark's CPU-baseline leg may call it.
+ *
+ * What is computed (every value is handled as an opaque 16-bit pattern; no
+ * arithmetic is ever done on a weight):
+ *
+ *   extract  -- the changed-index set  I = { i : W[i] != W_prev[i] }  of the
+ *               Trainer (Alg. 1, the line that forms I_t; Sec. 3.1 step
+ *               "Compute indices"), with "!=" read as inequality of the bit
+ *               patterns so that reconstruction is bit-for-bit (goal G1), and
+ *               the values  V = W[I]  with I as int32 and V as BF16
+ *               (Alg. 2, the line that forms V).  Indices are emitted in
+ *               ascending order (Sec. 3.3 relies on sorted indices).  The
+ *               weights are cut into fixed-size buckets, the unit that is
+ *               sent (Fig. 2 caption; Sec. 2 on bucketing); each bucket gets
+ *               its own (I, V) slot and its own count.  The snapshot W_prev is
+ *               then brought up to date, W_prev <- W (Alg. 1 clones W before
+ *               every cast; here the clone is kept and refreshed).
+ *
+ *   apply    -- the Rollout side's in-place scatter  W[I] <- V  (Alg. 3, the
+ *               scatter line), bucket by bucket, in payload order.
+ *
+ * Index conventions.  Single tensor: I holds the tensor-flat index i, exactly
+ * the per-tensor int32 index of Alg. 2.  Tensor list: the tensors are laid end
+ * to end in list order with no padding ("packed position" g); bucket b covers
+ * packed positions [b*be, (b+1)*be); I holds g - b*be, the position inside the
+ * bucket, because g itself does not fit int32 for a 30 B-element model.
+ *
+ * Capacity.  Each bucket's slot holds `cap` pairs.  counts[b] is always the
+ * true number of changed elements; if it exceeds cap only the first cap pairs
+ * (ascending) are stored.
+ *
+ * Parity pins (tests/test_oracle_*.py): round trip apply(extract) == new,
+ * identical inputs -> empty payload, all-changed -> dense payload, brute force
+ * over every change mask of tiny tensors, the generator's own change mask, the
+ * payload-size closed form of Eq. (1)/(2), and numpy's flatnonzero / fancy
+ * indexing as an independent library statement of the same definition.
+ */
+#include <stdint.h>
+#include <stddef.h>
+
+#define SRS_ORACLE_OK 0
+#define SRS_ORACLE_BAD_ARG (-1)
+#define SRS_ORACLE_BAD_INDEX (-2)
+
+/* Single tensor.  old_w (in/out) and new_w are n 16-bit patterns.
+ * I: int32[nb*cap], V: u16[nb*cap], counts: u32[nb], nb = ceil(n/be).
+ * refresh != 0 also performs old_w <- new_w.  Returns the number of buckets
+ * whose count exceeded cap (>= 0) or a negative error. */
+int srs_oracle_extract(uint16_t *old_w, const uint16_t *new_w, uint64_t n, uint64_t be,
+                       int32_t *I, uint16_t *V, uint32_t *counts, uint64_t cap, int refresh)
+{
+    if (be == 0 || cap == 0 || n > 0x7fffffffULL || be > 0x7fffffffULL) return SRS_ORACLE_BAD_ARG;
+    uint64_t nb = (n + be - 1) / be;
+    int overflowed = 0;
+    for (uint64_t b = 0; b < nb; ++b) {
+        uint64_t lo = b * be;
+        uint64_t hi = lo + be < n ? lo + be : n;
+        uint64_t c = 0;
+        for (uint64_t i = lo; i < hi; ++i) {
+            if (old_w[i] != new_w[i]) {
+                if (c < cap) {
+                    I[b * cap + c] = (int32_t)i;
+                    V[b * cap + c] = new_w[i];
+                }
+                c += 1;
+            }
+        }
+        counts[b] = (uint32_t)c;
+        if (c > cap) overflowed += 1;
+    }
+    if (refresh)
+        for (uint64_t i = 0; i < n; ++i) old_w[i] = new_w[i];
+    return overflowed;
+}
+
+/* Single tensor scatter.  A count above cap is read as cap (only cap pairs
+ * were stored).  An index outside its bucket's span is an error: nothing is
+ * written for it and SRS_ORACLE_BAD_INDEX is returned at the end. */
+int srs_oracle_apply(uint16_t *w, uint64_t n, uint64_t be,
+                     const int32_t *I, const uint16_t *V, const uint32_t *counts, uint64_t cap)
+{
+    if (be == 0 || cap == 0 || n > 0x7fffffffULL || be > 0x7fffffffULL) return SRS_ORACLE_BAD_ARG;
+    uint64_t nb = (n + be - 1) / be;
+    int rc = SRS_ORACLE_OK;
+    for (uint64_t b = 0; b < nb; ++b) {
+        uint64_t lo = b * be;
+        uint64_t hi = lo + be < n ? lo + be : n;
+        uint64_t c = counts[b] < cap ? counts[b] : cap;
+        for (uint64_t r = 0; r < c; ++r) {
+            int64_t i = I[b * cap + r];
+            if (i < (int64_t)lo || i >= (int64_t)hi) { rc = SRS_ORACLE_BAD_INDEX; continue; }
+            w[i] = V[b * cap + r];
+        }
+    }
+    return rc;
+}
+
+/* Tensor list.  old_w[k] (in/out) and new_w[k] are numel[k] patterns; the list
+ * is laid end to end.  Only buckets b_lo <= b < b_hi are produced, into
+ * I/V/counts indexed from b_lo (I + (b-b_lo)*cap ...); tensors that lie wholly
+ * outside that range are never touched and may be NULL.  The walk below visits
+ * every packed position g in order, carrying (k, j) = (tensor, offset). */
+int srs_oracle_extract_multi(uint16_t *const *old_w, const uint16_t *const *new_w,
+                             const uint64_t *numel, uint32_t ntensors, uint64_t be,
+                             uint64_t b_lo, uint64_t b_hi,
+                             int32_t *I, uint16_t *V, uint32_t *counts, uint64_t cap, int refresh)
+{
+    if (be == 0 || cap == 0 || be > 0x7fffffffULL || b_hi < b_lo) return SRS_ORACLE_BAD_ARG;
+    for (uint32_t k = 0; k < ntensors; ++k)
+        if (numel[k] > 0x7fffffffULL) return SRS_ORACLE_BAD_ARG;
+    for (uint64_t b = b_lo; b < b_hi; ++b) counts[b - b_lo] = 0;
+    uint64_t g_lo = b_lo * be, g_hi = b_hi * be;
+    uint64_t g = 0; /* packed position of element 0 of tensor k */
+    int overflowed = 0;
+    for (uint32_t k = 0; k < ntensors; ++k) {
+        uint64_t len = numel[k];
+        if (g + len <= g_lo || g >= g_hi) { g += len; continue; } /* wholly outside */
+        for (uint64_t j = 0; j < len; ++j) {
+            uint64_t p = g + j;
+            if (p < g_lo || p >= g_hi) continue;
+            uint64_t b = p / be;
+            uint64_t local = p - b * be;
+            if (old_w[k][j] != new_w[k][j]) {
+                uint64_t c = counts[b - b_lo];
+                if (c < cap) {
+                    I[(b - b_lo) * cap + c] = (int32_t)local;
+                    V[(b - b_lo) * cap + c] = new_w[k][j];
+                }
+                counts[b - b_lo] = (uint32_t)(c + 1);
+                if (refresh) old_w[k][j] = new_w[k][j];
+            }
+        }
+        g += len;
+    }
+    for (uint64_t b = b_lo; b < b_hi; ++b)
+        if (counts[b - b_lo] > cap) overflowed += 1;
+    return overflowed;
+}
+
+/* Tensor list scatter for buckets b_lo <= b < b_hi (I/V/counts indexed from
+ * b_lo).  Each stored position inside bucket b is turned back into a packed
+ * position and then, by walking the list, into (tensor, offset). */
+int srs_oracle_apply_multi(uint16_t *const *w, const uint64_t *numel, uint32_t ntensors, uint64_t be,
+                           uint64_t b_lo, uint64_t b_hi,
+                           const int32_t *I, const uint16_t *V, const uint32_t *counts, uint64_t cap)
+{
+    if (be == 0 || cap == 0 || be > 0x7fffffffULL || b_hi < b_lo) return SRS_ORACLE_BAD_ARG;
+    uint64_t total = 0;
+    for (uint32_t k = 0; k < ntensors; ++k) {
+        if (numel[k] > 0x7fffffffULL) return SRS_ORACLE_BAD_ARG;
+        total += numel[k];
+    }
+    int rc = SRS_ORACLE_OK;
+    for (uint64_t b = b_lo; b < b_hi; ++b) {
+        uint64_t lo = b * be;
+        if (lo >= total) break;
+        uint64_t span = lo + be < total ? be : total - lo;
+        uint64_t c = counts[b - b_lo] < cap ? counts[b - b_lo] : cap;
+        /* (k0, start0): the tensor that holds the bucket's first packed position */
+        uint32_t k0 = 0;
+        uint64_t start0 = 0;
+        while (lo >= start0 + numel[k0]) { start0 += numel[k0]; k0 += 1; }
+        /* the payload is not required to be sorted here: find the tensor afresh for each pair */
+        for (uint64_t r = 0; r < c; ++r) {
+            int64_t local = I[(b - b_lo) * cap + r];
+            if (local < 0 || (uint64_t)local >= span) { rc = SRS_ORACLE_BAD_INDEX; continue; }
+            uint64_t p = lo + (uint64_t)local;
+            uint32_t k = k0;
+            uint64_t start = start0;
+            while (p >= start + numel[k]) { start += numel[k]; k += 1; }
+            w[k][p - start] = V[(b - b_lo) * cap + r];
+        }
+    }
+    return rc;
+}
+
+/* Number of buckets of a packed tensor list: ceil(sum numel / be). */
+uint64_t srs_oracle_num_buckets(const uint64_t *numel, uint32_t ntensors, uint64_t be)
+{
+    uint64_t total = 0;
+    for (uint32_t k = 0; k < ntensors; ++k) total += numel[k];
+    return be ? (total + be - 1) / be : 0;
+}
