@@ -1,0 +1,135 @@
+/*
+ * srs.h -- C ABI of the MI355X (gfx950) hot path of lossless sparse weight synchronisation.
+ *
+ * Two operations, as the paper states the problem:
+ *
+ *   extract (Trainer side)  -- the changed-index set I = { i : W[i] != W_prev[i] } (Alg. 1, the
+ *       line that forms I_t; Sec. 3.1 "Compute indices"), with "!=" taken on the 16-bit pattern so
+ *       that the receiver can be bit-identical (goal G1), together with the values V = W[I], I as
+ *       int32 and V as BF16 (Alg. 2, the line that forms V), in ascending index order (Sec. 3.3
+ *       relies on sorted indices), one (I, V) payload per fixed-size bucket (the unit that is sent:
+ *       Fig. 2 caption, Sec. 2 on bucketing).  The same pass brings the snapshot W_prev up to date.
+ *
+ *   apply (Rollout side)    -- the in-place scatter W[I] <- V (Alg. 3, the scatter line; Sec. 3.2
+ *       calls it a fused kernel), after which W equals the Trainer's weights bit for bit.
+ *
+ * General conventions
+ *   - Every data pointer is a DEVICE pointer owned by the caller (the library never frees or keeps
+ *     it past the call's completion on the stream).  Arrays of descriptors (srs_tensor_pair[],
+ *     srs_tensor[], numel[]) are HOST arrays, read before the call returns.
+ *   - Weights are 16-bit patterns (BF16; FP16 works unchanged).  No arithmetic is done on them.
+ *     Base pointers need 2-byte alignment only; 16-byte alignment takes the fast path.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Every call is
+ *     asynchronous on it and does no host synchronisation, except where stated.
+ *   - Payload layout: bucket b owns the slots I[b*cap .. b*cap+cap) and V[b*cap .. b*cap+cap).
+ *     counts[b] is always the TRUE number of changed elements of bucket b.  If it exceeds cap only
+ *     the first cap pairs (ascending) are stored and the SRS_FLAG_OVERFLOW device flag is raised;
+ *     the snapshot is refreshed all the same, and the caller sends that bucket as a dense copy of
+ *     the new weights (the full-copy route of Sec. 3.4 for dense parameters).  Slots at and beyond
+ *     counts[b] are left untouched.
+ *   - Return value: SRS_OK (0) or a negative srs_error.  Nothing is launched when an error is
+ *     returned.  Device-side conditions (overflow, bad index, look-back time-out) are reported
+ *     through srs_status().
+ *   - A context serialises its own scratch memory: use one context per stream, and do not run
+ *     two calls on the same context concurrently.
+ */
+#ifndef SRS_H
+#define SRS_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    SRS_OK = 0,
+    SRS_ERR_INVALID = -1,     /* null pointer, zero bucket size or capacity, size beyond int32 indexing */
+    SRS_ERR_HIP = -2,         /* a HIP runtime call failed (allocation, copy, launch) */
+    SRS_ERR_NOMEM = -3,       /* host allocation failed */
+    SRS_ERR_NO_DEVICE = -4    /* no usable GPU / wrong architecture */
+} srs_error;
+
+/* device flags reported by srs_status() */
+#define SRS_FLAG_OVERFLOW  1u  /* extract: some bucket had more than cap changed elements */
+#define SRS_FLAG_BAD_INDEX 2u  /* apply: an index lay outside its bucket's span and was skipped */
+#define SRS_FLAG_TIMEOUT   4u  /* extract: a tile gave up waiting for its predecessors (payload invalid) */
+
+/* options for srs_set_option() */
+#define SRS_OPT_SPIN_LIMIT 1   /* max polls of a predecessor tile before SRS_FLAG_TIMEOUT (default 1<<24) */
+#define SRS_OPT_TILE_ELEMS 2   /* elements per extract tile: 4096, 8192, 16384 or 32768 (tuning; affects
+                                  plans created afterwards) */
+#define SRS_OPT_NONTEMPORAL 3  /* 1: stream weights with non-temporal loads */
+
+typedef struct srs_ctx srs_ctx;    /* per-stream scratch: tile status words, ticket counters, flag word */
+typedef struct srs_plan srs_plan;  /* immutable bucket / segment / tile tables of one tensor list */
+
+/* Context.  srs_create selects `device`, allocates a few KiB of device scratch and synchronises.
+ * The tile-status array grows on demand inside srs_extract* (that one call then allocates and
+ * synchronises the device; later calls of the same or smaller size do not). */
+int srs_create(srs_ctx **out, int device);
+int srs_destroy(srs_ctx *ctx);                       /* synchronises the device, frees scratch */
+int srs_set_option(srs_ctx *ctx, int option, uint64_t value);
+const char *srs_strerror(int err);
+int srs_version(void);
+
+/* Waits for `stream`, copies the device flag word to *flags (host pointer) and clears it. */
+int srs_status(srs_ctx *ctx, uint32_t *flags, void *stream);
+
+/*
+ * Single tensor (Alg. 1 / Alg. 2 for one parameter).  old_snapshot (in/out) and new_w are n 16-bit
+ * elements.  Bucket b covers the flat range [b*bucket_elems, min(n, (b+1)*bucket_elems)).
+ * I[nb*cap] receives tensor-flat indices i (the per-tensor int32 index of Alg. 2), V[nb*cap] the
+ * patterns new_w[i], counts[nb] the per-bucket counts; nb = ceil(n / bucket_elems).  On completion
+ * old_snapshot equals new_w bitwise.  n and bucket_elems must be below 2^31 (int32 indices,
+ * Sec. 3.2); n == 0 is SRS_OK and writes nothing.
+ */
+int srs_extract(srs_ctx *ctx, void *old_snapshot, const void *new_w, uint64_t n, uint64_t bucket_elems,
+                int32_t *I, uint16_t *V, uint32_t *counts, uint64_t cap, void *stream);
+
+/*
+ * Single tensor scatter (Alg. 3): weights[I[b*cap+r]] <- V[b*cap+r] for r < min(counts[b], cap).
+ * counts is read on the device.  An index outside bucket b's span is skipped and raises
+ * SRS_FLAG_BAD_INDEX; nothing is ever written out of bounds.  Duplicate indices are a caller
+ * error (extract never produces them): one of the values wins.
+ */
+int srs_apply(srs_ctx *ctx, void *weights, uint64_t n, uint64_t bucket_elems,
+              const int32_t *I, const uint16_t *V, const uint32_t *counts, uint64_t cap, void *stream);
+
+/*
+ * Tensor lists.  The tensors are laid end to end in list order, without padding, and that packed
+ * space is cut into buckets of bucket_elems (the last one short); a tensor may straddle buckets and
+ * a bucket may hold many tensors.  Indices are positions INSIDE the bucket (packed position minus
+ * b*bucket_elems), because packed positions of a 30 B-element model do not fit int32; with the
+ * plan's segment table they map one-to-one to Alg. 2's per-tensor flat indices.
+ */
+typedef struct { void *old_snapshot; const void *new_w; } srs_tensor_pair;   /* extract side */
+typedef struct { void *weights; } srs_tensor;                                 /* apply side   */
+
+/* Builds the tables on the host and uploads them (allocates; synchronises).  numel[k] < 2^31. */
+int srs_plan_create(srs_ctx *ctx, const uint64_t *numel, uint32_t ntensors, uint64_t bucket_elems,
+                    srs_plan **out);
+int srs_plan_info(const srs_plan *plan, uint64_t *total_elems, uint32_t *nbuckets, uint32_t *nsegments,
+                  uint32_t *ntiles);
+int srs_plan_destroy(srs_plan *plan);
+
+/* t[ntensors] (host array) gives the device pointers of each tensor, in plan order.  The library
+ * keeps a device copy and re-uploads it (hipMemcpyAsync on `stream`) only when a pointer changed. */
+int srs_extract_multi(srs_ctx *ctx, srs_plan *plan, const srs_tensor_pair *t,
+                      int32_t *I, uint16_t *V, uint32_t *counts, uint64_t cap, void *stream);
+int srs_apply_multi(srs_ctx *ctx, srs_plan *plan, const srs_tensor *t,
+                    const int32_t *I, const uint16_t *V, const uint32_t *counts, uint64_t cap, void *stream);
+
+/*
+ * Measurement aid (not part of the method): reads `bytes` bytes from each of a and b with the same
+ * 16-byte streaming loads and launch shape as extract and writes one word per workgroup to `sink`
+ * (at least srs_stream_probe_sink_words(bytes) uint32).  Gives the box's achievable two-stream read
+ * bandwidth, the practical ceiling for extract.  a, b 16-byte aligned; bytes a multiple of 16.
+ */
+int srs_stream_probe(srs_ctx *ctx, const void *a, const void *b, uint64_t bytes, uint32_t *sink, void *stream);
+uint64_t srs_stream_probe_sink_words(uint64_t bytes);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SRS_H */

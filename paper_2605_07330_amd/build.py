@@ -1,0 +1,41 @@
+"""Builds libsrs.so (HIP, gfx950 only) in-tree, next to this file."""
+from __future__ import annotations
+
+import os
+import subprocess
+import sys
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+ROOT = os.path.dirname(HERE)
+LIB = os.path.join(HERE, "libsrs.so")
+SOURCES = [os.path.join(HERE, "csrc", "srs.hip")]
+HEADERS = [os.path.join(HERE, "csrc", "srs_kernels.hpp"), os.path.join(ROOT, "include", "srs.h")]
+
+
+def hipcc_command(out: str = LIB, extra=()) -> list:
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    return [hipcc, "--offload-arch=gfx950", "-O3", "-std=c++17", "-shared", "-fPIC",
+            "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+            "-Wall", "-Wno-unused-command-line-argument",
+            "-I", os.path.join(ROOT, "include"), "-I", os.path.join(HERE, "csrc"),
+            "-Wl,-rpath,/opt/rocm/lib", *extra, *SOURCES, "-o", out]
+
+
+def build_lib(verbose: bool = False) -> str:
+    cmd = hipcc_command()
+    if verbose:
+        print(" ".join(cmd), flush=True)
+    subprocess.check_call(cmd)
+    return LIB
+
+
+def is_stale() -> bool:
+    if not os.path.exists(LIB):
+        return True
+    t = os.path.getmtime(LIB)
+    return any(os.path.getmtime(f) > t for f in SOURCES + HEADERS)
+
+
+if __name__ == "__main__":
+    build_lib(verbose=True)
+    print(LIB)

@@ -1,0 +1,439 @@
+// Host side of libsrs.so: argument checks, bucket / segment / tile tables, launches.
+// The operations and their conventions are documented in include/srs.h.
+#include "srs.h"
+#include "srs_kernels.hpp"
+
+#include <hip/hip_runtime.h>
+
+#include <cstdlib>
+#include <cstring>
+#include <new>
+#include <vector>
+
+using namespace srs;
+
+namespace {
+
+constexpr uint64_t kMaxIndexable = 0x7fffffffull;   // int32 indices (Sec. 3.2: tensors below 2^31 elements)
+constexpr uint32_t kEpochMax = (1u << 30) - 1u;
+
+#define SRS_HIP(expr)                                   \
+    do {                                                \
+        hipError_t e_ = (expr);                         \
+        if (e_ != hipSuccess) { (void)hipGetLastError(); return SRS_ERR_HIP; } \
+    } while (0)
+
+}  // namespace
+
+struct srs_ctx {
+    int device = 0;
+    unsigned long long *status = nullptr;   // tile status words
+    uint64_t status_cap = 0;
+    uint32_t *counters = nullptr;           // [0] ticket, [32] finished, [64] flags
+    uint32_t epoch = 1;
+    uint32_t spin_limit = 1u << 24;
+    uint32_t tile_elems = 16384;
+    bool nontemporal = false;
+};
+
+struct srs_plan {
+    int device = 0;
+    uint64_t total = 0, be = 0;
+    uint32_t ntensors = 0, nbuckets = 0, nsegments = 0, ntiles = 0, tile_elems = 0;
+    TileDesc *d_tiles = nullptr;
+    SegDesc *d_segs = nullptr;
+    uint32_t *d_seg_begin = nullptr;
+    PtrPair *d_pairs = nullptr;             // extract-side pointer table
+    uint16_t **d_wptrs = nullptr;           // apply-side pointer table
+    std::vector<PtrPair> h_pairs;           // what d_pairs currently holds
+    std::vector<uint16_t *> h_wptrs;
+    bool pairs_valid = false, wptrs_valid = false;
+};
+
+namespace {
+
+int fill_status(srs_ctx *ctx, hipStream_t st) {
+    if (ctx->status_cap == 0) return SRS_OK;
+    const uint32_t threads = 256;
+    const uint64_t blocks = (ctx->status_cap + threads - 1) / threads;
+    hipLaunchKernelGGL(fill_u64_kernel, dim3((uint32_t)blocks), dim3(threads), 0, st, ctx->status, ctx->status_cap, 0ull);
+    SRS_HIP(hipGetLastError());
+    return SRS_OK;
+}
+
+// make room for ntiles status words and hand out this launch's epoch
+int prepare_extract(srs_ctx *ctx, uint64_t ntiles, hipStream_t st, uint32_t *epoch) {
+    if (ntiles > ctx->status_cap) {
+        SRS_HIP(hipDeviceSynchronize());
+        if (ctx->status) SRS_HIP(hipFree(ctx->status));
+        ctx->status = nullptr; ctx->status_cap = 0;
+        uint64_t cap = ntiles + ntiles / 4 + 1024;
+        SRS_HIP(hipMalloc((void **)&ctx->status, cap * sizeof(unsigned long long)));
+        ctx->status_cap = cap;
+        int rc = fill_status(ctx, st);
+        if (rc != SRS_OK) return rc;
+        ctx->epoch = 1;
+    }
+    if (ctx->epoch >= kEpochMax) {          // epoch field is 30 bits: start over with cleared words
+        int rc = fill_status(ctx, st);
+        if (rc != SRS_OK) return rc;
+        ctx->epoch = 1;
+    }
+    *epoch = ctx->epoch++;
+    return SRS_OK;
+}
+
+template <bool MULTI>
+int launch_extract(const srs_ctx *ctx, uint32_t tile_elems, const ExtractArgs &a, hipStream_t st) {
+    const dim3 grid(a.ntiles), block(kThreads);
+#define SRS_LAUNCH(VV)                                                                              \
+    do {                                                                                            \
+        if (ctx->nontemporal) hipLaunchKernelGGL((extract_kernel<VV, MULTI, true>), grid, block, 0, st, a);  \
+        else hipLaunchKernelGGL((extract_kernel<VV, MULTI, false>), grid, block, 0, st, a);         \
+    } while (0)
+    switch (tile_elems) {
+        case 4096: SRS_LAUNCH(2); break;
+        case 8192: SRS_LAUNCH(4); break;
+        case 16384: SRS_LAUNCH(8); break;
+        case 32768: SRS_LAUNCH(16); break;
+        default: return SRS_ERR_INVALID;
+    }
+#undef SRS_LAUNCH
+    SRS_HIP(hipGetLastError());
+    return SRS_OK;
+}
+
+bool valid_tile_elems(uint64_t v) { return v == 4096 || v == 8192 || v == 16384 || v == 32768; }
+
+}  // namespace
+
+extern "C" {
+
+int srs_version(void) { return 100; }
+
+const char *srs_strerror(int err) {
+    switch (err) {
+        case SRS_OK: return "ok";
+        case SRS_ERR_INVALID: return "invalid argument";
+        case SRS_ERR_HIP: return "HIP runtime call failed";
+        case SRS_ERR_NOMEM: return "out of host memory";
+        case SRS_ERR_NO_DEVICE: return "no usable GPU";
+        default: return "unknown error";
+    }
+}
+
+int srs_create(srs_ctx **out, int device) {
+    if (!out) return SRS_ERR_INVALID;
+    *out = nullptr;
+    int ndev = 0;
+    if (hipGetDeviceCount(&ndev) != hipSuccess || ndev <= 0) { (void)hipGetLastError(); return SRS_ERR_NO_DEVICE; }
+    if (device < 0 || device >= ndev) return SRS_ERR_INVALID;
+    SRS_HIP(hipSetDevice(device));
+    srs_ctx *ctx = new (std::nothrow) srs_ctx();
+    if (!ctx) return SRS_ERR_NOMEM;
+    ctx->device = device;
+    if (hipMalloc((void **)&ctx->counters, 96 * sizeof(uint32_t)) != hipSuccess) {
+        (void)hipGetLastError(); delete ctx; return SRS_ERR_HIP;
+    }
+    if (hipMemset(ctx->counters, 0, 96 * sizeof(uint32_t)) != hipSuccess || hipDeviceSynchronize() != hipSuccess) {
+        (void)hipGetLastError(); (void)hipFree(ctx->counters); delete ctx; return SRS_ERR_HIP;
+    }
+    *out = ctx;
+    return SRS_OK;
+}
+
+int srs_destroy(srs_ctx *ctx) {
+    if (!ctx) return SRS_ERR_INVALID;
+    (void)hipSetDevice(ctx->device);
+    (void)hipDeviceSynchronize();
+    if (ctx->status) (void)hipFree(ctx->status);
+    if (ctx->counters) (void)hipFree(ctx->counters);
+    delete ctx;
+    return SRS_OK;
+}
+
+int srs_set_option(srs_ctx *ctx, int option, uint64_t value) {
+    if (!ctx) return SRS_ERR_INVALID;
+    switch (option) {
+        case SRS_OPT_SPIN_LIMIT:
+            if (value == 0 || value > 0xffffffffull) return SRS_ERR_INVALID;
+            ctx->spin_limit = (uint32_t)value; return SRS_OK;
+        case SRS_OPT_TILE_ELEMS:
+            if (!valid_tile_elems(value)) return SRS_ERR_INVALID;
+            ctx->tile_elems = (uint32_t)value; return SRS_OK;
+        case SRS_OPT_NONTEMPORAL:
+            ctx->nontemporal = value != 0; return SRS_OK;
+        default: return SRS_ERR_INVALID;
+    }
+}
+
+int srs_status(srs_ctx *ctx, uint32_t *flags, void *stream) {
+    if (!ctx || !flags) return SRS_ERR_INVALID;
+    hipStream_t st = (hipStream_t)stream;
+    SRS_HIP(hipSetDevice(ctx->device));
+    SRS_HIP(hipMemcpyAsync(flags, ctx->counters + 64, sizeof(uint32_t), hipMemcpyDeviceToHost, st));
+    SRS_HIP(hipStreamSynchronize(st));
+    hipLaunchKernelGGL(fill_u64_kernel, dim3(1), dim3(64), 0, st, (unsigned long long *)(ctx->counters + 64), (uint64_t)1, 0ull);
+    SRS_HIP(hipGetLastError());
+    return SRS_OK;
+}
+
+// ---------------------------------------------------------------------------------------------
+// single tensor
+// ---------------------------------------------------------------------------------------------
+
+int srs_extract(srs_ctx *ctx, void *old_snapshot, const void *new_w, uint64_t n, uint64_t bucket_elems,
+                int32_t *I, uint16_t *V, uint32_t *counts, uint64_t cap, void *stream) {
+    if (!ctx || bucket_elems == 0 || cap == 0 || n > kMaxIndexable || bucket_elems > kMaxIndexable) return SRS_ERR_INVALID;
+    if (n == 0) return SRS_OK;
+    if (!old_snapshot || !new_w || !I || !V || !counts) return SRS_ERR_INVALID;
+    if (((uintptr_t)old_snapshot | (uintptr_t)new_w | (uintptr_t)V) & 1u) return SRS_ERR_INVALID;
+    if (((uintptr_t)I | (uintptr_t)counts) & 3u) return SRS_ERR_INVALID;
+    hipStream_t st = (hipStream_t)stream;
+    SRS_HIP(hipSetDevice(ctx->device));
+
+    const uint64_t T = ctx->tile_elems;
+    const uint64_t nb = (n + bucket_elems - 1) / bucket_elems;
+    const uint64_t tpb = (bucket_elems + T - 1) / T;
+    const uint64_t last_len = n - (nb - 1) * bucket_elems;
+    const uint64_t ntiles = (nb - 1) * tpb + (last_len + T - 1) / T;
+    if (ntiles > 0x7fffffffull) return SRS_ERR_INVALID;
+
+    ExtractArgs a;
+    std::memset(&a, 0, sizeof(a));
+    int rc = prepare_extract(ctx, ntiles, st, &a.epoch);
+    if (rc != SRS_OK) return rc;
+    a.old_w = (uint16_t *)old_snapshot; a.new_w = (const uint16_t *)new_w; a.n = n;
+    a.be = (uint32_t)bucket_elems; a.tiles_per_bucket = (uint32_t)tpb;
+    a.ntiles = (uint32_t)ntiles;
+    a.I = I; a.V = V; a.counts = counts; a.cap = cap;
+    a.status = ctx->status; a.ticket = ctx->counters; a.flags = ctx->counters + 64;
+    a.spin_limit = ctx->spin_limit;
+    return launch_extract<false>(ctx, ctx->tile_elems, a, st);
+}
+
+int srs_apply(srs_ctx *ctx, void *weights, uint64_t n, uint64_t bucket_elems,
+              const int32_t *I, const uint16_t *V, const uint32_t *counts, uint64_t cap, void *stream) {
+    if (!ctx || bucket_elems == 0 || cap == 0 || n > kMaxIndexable || bucket_elems > kMaxIndexable) return SRS_ERR_INVALID;
+    if (n == 0) return SRS_OK;
+    if (!weights || !I || !V || !counts) return SRS_ERR_INVALID;
+    if (((uintptr_t)weights | (uintptr_t)V) & 1u) return SRS_ERR_INVALID;
+    if (((uintptr_t)I | (uintptr_t)counts) & 3u) return SRS_ERR_INVALID;
+    hipStream_t st = (hipStream_t)stream;
+    SRS_HIP(hipSetDevice(ctx->device));
+
+    const uint64_t nb = (n + bucket_elems - 1) / bucket_elems;
+    const uint64_t slots = cap < bucket_elems ? cap : bucket_elems;       // a bucket never holds more pairs than elements
+    const uint64_t cpb = (slots + kApplyChunk - 1) / kApplyChunk;
+    if (nb * cpb > 0x7fffffffull) return SRS_ERR_INVALID;
+    ApplyArgs a;
+    std::memset(&a, 0, sizeof(a));
+    a.w = (uint16_t *)weights; a.n = n; a.be = (uint32_t)bucket_elems; a.nb = (uint32_t)nb;
+    a.chunks_per_bucket = (uint32_t)cpb;
+    a.I = I; a.V = V; a.counts = counts; a.cap = cap; a.flags = ctx->counters + 64;
+    hipLaunchKernelGGL((apply_kernel<false>), dim3((uint32_t)(nb * cpb)), dim3(kThreads), 0, st, a);
+    SRS_HIP(hipGetLastError());
+    return SRS_OK;
+}
+
+// ---------------------------------------------------------------------------------------------
+// tensor lists
+// ---------------------------------------------------------------------------------------------
+
+int srs_plan_create(srs_ctx *ctx, const uint64_t *numel, uint32_t ntensors, uint64_t bucket_elems, srs_plan **out) {
+    if (!ctx || !out || (!numel && ntensors) || bucket_elems == 0 || bucket_elems > kMaxIndexable) return SRS_ERR_INVALID;
+    *out = nullptr;
+    uint64_t total = 0;
+    for (uint32_t k = 0; k < ntensors; ++k) {
+        if (numel[k] > kMaxIndexable) return SRS_ERR_INVALID;
+        total += numel[k];
+    }
+    const uint64_t nb64 = (total + bucket_elems - 1) / bucket_elems;
+    if (nb64 > 0x7fffffffull) return SRS_ERR_INVALID;
+    SRS_HIP(hipSetDevice(ctx->device));
+
+    srs_plan *p = new (std::nothrow) srs_plan();
+    if (!p) return SRS_ERR_NOMEM;
+    p->device = ctx->device; p->total = total; p->be = bucket_elems; p->ntensors = ntensors;
+    p->nbuckets = (uint32_t)nb64; p->tile_elems = ctx->tile_elems;
+
+    // Walk the packed space: a segment is a maximal run of one tensor inside one bucket; a tile is a
+    // run of at most tile_elems elements inside one segment.
+    std::vector<SegDesc> segs;
+    std::vector<uint32_t> seg_begin;
+    std::vector<TileDesc> tiles;
+    try {
+        seg_begin.assign((size_t)p->nbuckets + 1, 0);
+        uint64_t g = 0;                       // packed position of the current tensor's element 0
+        uint32_t cur_bucket = 0xffffffffu, first_tile = 0;
+        for (uint32_t k = 0; k < ntensors; ++k) {
+            uint64_t off = 0;
+            while (off < numel[k]) {
+                const uint64_t pos = g + off;
+                const uint64_t b = pos / bucket_elems;
+                const uint64_t boff = pos - b * bucket_elems;
+                uint64_t len = numel[k] - off;
+                if (len > bucket_elems - boff) len = bucket_elems - boff;
+                if ((uint32_t)b != cur_bucket) {
+                    if (!tiles.empty()) tiles.back().last = 1;
+                    cur_bucket = (uint32_t)b;
+                    first_tile = (uint32_t)tiles.size();
+                    seg_begin[b] = (uint32_t)segs.size();
+                }
+                segs.push_back(SegDesc{(uint32_t)boff, (uint32_t)len, k, (uint32_t)off});
+                for (uint64_t t = 0; t < len; t += p->tile_elems) {
+                    const uint64_t tl = (len - t < p->tile_elems) ? (len - t) : p->tile_elems;
+                    tiles.push_back(TileDesc{k, (uint32_t)(off + t), (uint32_t)b, (uint32_t)(boff + t), (uint32_t)tl,
+                                             first_tile, 0u, 0u});
+                }
+                off += len;
+            }
+            g += numel[k];
+        }
+        if (!tiles.empty()) tiles.back().last = 1;
+        seg_begin[p->nbuckets] = (uint32_t)segs.size();
+        p->h_pairs.assign(ntensors, PtrPair{nullptr, nullptr});
+        p->h_wptrs.assign(ntensors, nullptr);
+    } catch (const std::bad_alloc &) {
+        delete p; return SRS_ERR_NOMEM;
+    }
+    if (tiles.size() > 0x7fffffffull) { delete p; return SRS_ERR_INVALID; }
+    p->nsegments = (uint32_t)segs.size();
+    p->ntiles = (uint32_t)tiles.size();
+
+    auto upload = [](void **dst, const void *src, size_t bytes) -> bool {
+        if (bytes == 0) bytes = 16;
+        if (hipMalloc(dst, bytes) != hipSuccess) return false;
+        if (src && hipMemcpy(*dst, src, bytes, hipMemcpyHostToDevice) != hipSuccess) return false;
+        return true;
+    };
+    bool ok = true;
+    ok = ok && upload((void **)&p->d_tiles, tiles.empty() ? nullptr : tiles.data(), tiles.size() * sizeof(TileDesc));
+    ok = ok && upload((void **)&p->d_segs, segs.empty() ? nullptr : segs.data(), segs.size() * sizeof(SegDesc));
+    ok = ok && upload((void **)&p->d_seg_begin, seg_begin.data(), seg_begin.size() * sizeof(uint32_t));
+    ok = ok && upload((void **)&p->d_pairs, nullptr, (size_t)ntensors * sizeof(PtrPair));
+    ok = ok && upload((void **)&p->d_wptrs, nullptr, (size_t)ntensors * sizeof(uint16_t *));
+    ok = ok && hipDeviceSynchronize() == hipSuccess;
+    if (!ok) { (void)hipGetLastError(); srs_plan_destroy(p); return SRS_ERR_HIP; }
+    *out = p;
+    return SRS_OK;
+}
+
+int srs_plan_info(const srs_plan *plan, uint64_t *total_elems, uint32_t *nbuckets, uint32_t *nsegments, uint32_t *ntiles) {
+    if (!plan) return SRS_ERR_INVALID;
+    if (total_elems) *total_elems = plan->total;
+    if (nbuckets) *nbuckets = plan->nbuckets;
+    if (nsegments) *nsegments = plan->nsegments;
+    if (ntiles) *ntiles = plan->ntiles;
+    return SRS_OK;
+}
+
+int srs_plan_destroy(srs_plan *p) {
+    if (!p) return SRS_ERR_INVALID;
+    (void)hipSetDevice(p->device);
+    (void)hipDeviceSynchronize();
+    if (p->d_tiles) (void)hipFree(p->d_tiles);
+    if (p->d_segs) (void)hipFree(p->d_segs);
+    if (p->d_seg_begin) (void)hipFree(p->d_seg_begin);
+    if (p->d_pairs) (void)hipFree(p->d_pairs);
+    if (p->d_wptrs) (void)hipFree(p->d_wptrs);
+    delete p;
+    return SRS_OK;
+}
+
+int srs_extract_multi(srs_ctx *ctx, srs_plan *plan, const srs_tensor_pair *t,
+                      int32_t *I, uint16_t *V, uint32_t *counts, uint64_t cap, void *stream) {
+    if (!ctx || !plan || cap == 0 || plan->device != ctx->device) return SRS_ERR_INVALID;
+    if (plan->total == 0) return SRS_OK;
+    if (!t || !I || !V || !counts) return SRS_ERR_INVALID;
+    if (((uintptr_t)V & 1u) || (((uintptr_t)I | (uintptr_t)counts) & 3u)) return SRS_ERR_INVALID;
+    // numel is not known here any more, but a tensor with elements has at least one segment
+    for (uint32_t k = 0; k < plan->ntensors; ++k)
+        if (((uintptr_t)t[k].old_snapshot | (uintptr_t)t[k].new_w) & 1u) return SRS_ERR_INVALID;
+    hipStream_t st = (hipStream_t)stream;
+    SRS_HIP(hipSetDevice(ctx->device));
+
+    bool same = plan->pairs_valid;
+    for (uint32_t k = 0; same && k < plan->ntensors; ++k)
+        same = plan->h_pairs[k].old_w == (uint16_t *)t[k].old_snapshot && plan->h_pairs[k].new_w == (const uint16_t *)t[k].new_w;
+    if (!same) {
+        for (uint32_t k = 0; k < plan->ntensors; ++k)
+            plan->h_pairs[k] = PtrPair{(uint16_t *)t[k].old_snapshot, (const uint16_t *)t[k].new_w};
+        plan->pairs_valid = false;
+        SRS_HIP(hipMemcpyAsync(plan->d_pairs, plan->h_pairs.data(), plan->ntensors * sizeof(PtrPair), hipMemcpyHostToDevice, st));
+        plan->pairs_valid = true;
+    }
+
+    ExtractArgs a;
+    std::memset(&a, 0, sizeof(a));
+    int rc = prepare_extract(ctx, plan->ntiles, st, &a.epoch);
+    if (rc != SRS_OK) return rc;
+    a.tiles = plan->d_tiles; a.ptrs = plan->d_pairs; a.ntiles = plan->ntiles;
+    a.I = I; a.V = V; a.counts = counts; a.cap = cap;
+    a.status = ctx->status; a.ticket = ctx->counters; a.flags = ctx->counters + 64;
+    a.spin_limit = ctx->spin_limit;
+    return launch_extract<true>(ctx, plan->tile_elems, a, st);
+}
+
+int srs_apply_multi(srs_ctx *ctx, srs_plan *plan, const srs_tensor *t,
+                    const int32_t *I, const uint16_t *V, const uint32_t *counts, uint64_t cap, void *stream) {
+    if (!ctx || !plan || cap == 0 || plan->device != ctx->device) return SRS_ERR_INVALID;
+    if (plan->total == 0) return SRS_OK;
+    if (!t || !I || !V || !counts) return SRS_ERR_INVALID;
+    if (((uintptr_t)V & 1u) || (((uintptr_t)I | (uintptr_t)counts) & 3u)) return SRS_ERR_INVALID;
+    for (uint32_t k = 0; k < plan->ntensors; ++k)
+        if ((uintptr_t)t[k].weights & 1u) return SRS_ERR_INVALID;
+    hipStream_t st = (hipStream_t)stream;
+    SRS_HIP(hipSetDevice(ctx->device));
+
+    bool same = plan->wptrs_valid;
+    for (uint32_t k = 0; same && k < plan->ntensors; ++k) same = plan->h_wptrs[k] == (uint16_t *)t[k].weights;
+    if (!same) {
+        for (uint32_t k = 0; k < plan->ntensors; ++k) plan->h_wptrs[k] = (uint16_t *)t[k].weights;
+        plan->wptrs_valid = false;
+        SRS_HIP(hipMemcpyAsync(plan->d_wptrs, plan->h_wptrs.data(), plan->ntensors * sizeof(uint16_t *), hipMemcpyHostToDevice, st));
+        plan->wptrs_valid = true;
+    }
+
+    const uint64_t slots = cap < plan->be ? cap : plan->be;
+    const uint64_t cpb = (slots + kApplyChunk - 1) / kApplyChunk;
+    if ((uint64_t)plan->nbuckets * cpb > 0x7fffffffull) return SRS_ERR_INVALID;
+    ApplyArgs a;
+    std::memset(&a, 0, sizeof(a));
+    a.segs = plan->d_segs; a.seg_begin = plan->d_seg_begin; a.wptrs = plan->d_wptrs; a.total = plan->total;
+    a.be = (uint32_t)plan->be; a.nb = plan->nbuckets; a.chunks_per_bucket = (uint32_t)cpb;
+    a.I = I; a.V = V; a.counts = counts; a.cap = cap; a.flags = ctx->counters + 64;
+    hipLaunchKernelGGL((apply_kernel<true>), dim3((uint32_t)((uint64_t)plan->nbuckets * cpb)), dim3(kThreads), 0, st, a);
+    SRS_HIP(hipGetLastError());
+    return SRS_OK;
+}
+
+// ---------------------------------------------------------------------------------------------
+// measurement aid
+// ---------------------------------------------------------------------------------------------
+
+uint64_t srs_stream_probe_sink_words(uint64_t bytes) {
+    const uint64_t tile_bytes = 16384ull * 2ull;
+    return (bytes + tile_bytes - 1) / tile_bytes + 1;
+}
+
+int srs_stream_probe(srs_ctx *ctx, const void *a, const void *b, uint64_t bytes, uint32_t *sink, void *stream) {
+    if (!ctx || !a || !b || !sink || (bytes & 15u) || (((uintptr_t)a | (uintptr_t)b) & 15u)) return SRS_ERR_INVALID;
+    if (bytes == 0) return SRS_OK;
+    hipStream_t st = (hipStream_t)stream;
+    SRS_HIP(hipSetDevice(ctx->device));
+    const uint64_t nvec = bytes / 16;
+    const uint64_t tile_bytes = 16384ull * 2ull;
+    const uint64_t blocks = (bytes + tile_bytes - 1) / tile_bytes;
+    if (blocks > 0x7fffffffull) return SRS_ERR_INVALID;
+    if (ctx->nontemporal)
+        hipLaunchKernelGGL((stream_probe_kernel<8, true>), dim3((uint32_t)blocks), dim3(kThreads), 0, st,
+                           (const uint16_t *)a, (const uint16_t *)b, nvec, sink);
+    else
+        hipLaunchKernelGGL((stream_probe_kernel<8, false>), dim3((uint32_t)blocks), dim3(kThreads), 0, st,
+                           (const uint16_t *)a, (const uint16_t *)b, nvec, sink);
+    SRS_HIP(hipGetLastError());
+    return SRS_OK;
+}
+
+}  // extern "C"

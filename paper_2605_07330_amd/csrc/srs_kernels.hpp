@@ -1,0 +1,441 @@
+// Device code of the sparse-weight-sync hot path for gfx950 (wave64, 256 CUs in 8 XCDs).
+//
+// extract_kernel: one pass over old/new.  Each workgroup takes one tile (a run of up to
+//   TILE = 2048*V elements that lies inside one tensor and one bucket) in ticket order, streams
+//   both inputs with 16-byte loads, forms per-lane change masks by XOR of the 16-bit patterns
+//   (Alg. 1: I = { i : W[i] != W_prev[i] }), ranks the changed elements with a packed DPP wave
+//   scan + an LDS combine across the four waves, chains tiles of the same bucket with a
+//   decoupled look-back on one 64-bit {epoch|flag, value} status word per tile, stages the
+//   (index, value) pairs of the tile in LDS in rank order and writes them out coalesced
+//   (Alg. 2: V = W[I], I int32 ascending), refreshing the snapshot at the same positions.
+// apply_kernel: the scatter of Alg. 3, W[I] <- V, one workgroup per (bucket, payload chunk).
+//
+// No arithmetic is done on weight values anywhere; the path is HBM-bandwidth bound.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace srs {
+
+constexpr int kThreads = 256;          // 4 waves of 64
+constexpr int kWaves = kThreads / 64;
+constexpr int kVecElems = 8;           // 16-byte vector = 8 patterns
+constexpr int kUnit = kThreads * kVecElems;   // 2048 elements per "V" step of a tile
+constexpr uint32_t kStage = 2048;      // (index,value) pairs staged in LDS per round
+constexpr uint32_t kApplyChunk = 2048; // payload pairs per apply workgroup
+
+constexpr uint32_t kFlagOverflow = 1u, kFlagBadIndex = 2u, kFlagTimeout = 4u;
+constexpr uint32_t kStAgg = 1u, kStPrefix = 2u;   // tile status: aggregate only / inclusive prefix
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+struct TileDesc {          // one extract tile of a tensor list (32 bytes)
+    uint32_t tensor;       // index into the pointer table
+    uint32_t tensor_off;   // first element inside the tensor
+    uint32_t bucket;
+    uint32_t bucket_off;   // first element inside the bucket
+    uint32_t len;          // 1 .. TILE
+    uint32_t first_tile;   // id of the first tile of this bucket
+    uint32_t last;         // 1 if this is the last tile of its bucket
+    uint32_t pad;
+};
+
+struct SegDesc {           // a run of one tensor inside one bucket (16 bytes)
+    uint32_t bucket_off;
+    uint32_t len;
+    uint32_t tensor;
+    uint32_t tensor_off;
+};
+
+struct PtrPair { uint16_t *old_w; const uint16_t *new_w; };
+
+struct ExtractArgs {
+    // single tensor
+    uint16_t *old_w; const uint16_t *new_w; uint64_t n; uint32_t be; uint32_t tiles_per_bucket;
+    // tensor list
+    const TileDesc *tiles; const PtrPair *ptrs;
+    uint32_t ntiles;
+    int32_t *I; uint16_t *V; uint32_t *counts; uint64_t cap;
+    unsigned long long *status;    // [>= ntiles] {(epoch<<2|flag) : value}
+    uint32_t *ticket;              // [0] next tile id, [32] tiles finished (separate 128-byte lines)
+    uint32_t *flags;
+    uint32_t epoch; uint32_t spin_limit;
+};
+
+struct ApplyArgs {
+    // single tensor
+    uint16_t *w; uint64_t n;
+    // tensor list
+    const SegDesc *segs; const uint32_t *seg_begin; uint16_t *const *wptrs; uint64_t total;
+    uint32_t be; uint32_t nb; uint32_t chunks_per_bucket;
+    const int32_t *I; const uint16_t *V; const uint32_t *counts; uint64_t cap;
+    uint32_t *flags;
+};
+
+// ---------------------------------------------------------------------------------------------
+// wave64 helpers
+// ---------------------------------------------------------------------------------------------
+
+template <int CTRL, int ROW_MASK, int BANK_MASK>
+__device__ __forceinline__ uint32_t dpp_get(uint32_t x) {
+    // lanes whose source is outside the row, or whose row is masked off, receive 0
+    return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, CTRL, ROW_MASK, BANK_MASK, false);
+}
+
+// inclusive prefix sum over the 64 lanes of a wave (also valid on two packed 16-bit fields as long
+// as neither field overflows)
+__device__ __forceinline__ uint32_t wave_inclusive_scan(uint32_t x) {
+    x += dpp_get<0x111, 0xF, 0xF>(x);   // row_shr:1
+    x += dpp_get<0x112, 0xF, 0xF>(x);   // row_shr:2
+    x += dpp_get<0x114, 0xF, 0xF>(x);   // row_shr:4
+    x += dpp_get<0x118, 0xF, 0xF>(x);   // row_shr:8
+    x += dpp_get<0x142, 0xA, 0xF>(x);   // row_bcast:15 -> rows 1 and 3
+    x += dpp_get<0x143, 0xC, 0xF>(x);   // row_bcast:31 -> rows 2 and 3
+    return x;
+}
+
+__device__ __forceinline__ uint32_t lane63(uint32_t x) {
+    return (uint32_t)__builtin_amdgcn_readlane((int)x, 63);
+}
+
+__device__ __forceinline__ uint32_t uniform(uint32_t x) {
+    return (uint32_t)__builtin_amdgcn_readfirstlane((int)x);
+}
+
+template <bool NT>
+__device__ __forceinline__ u32x4 load16(const uint16_t *p) {
+    const u32x4 *q = reinterpret_cast<const u32x4 *>(p);
+    if (NT) return __builtin_nontemporal_load(q);
+    return *q;
+}
+
+// 8 patterns starting at element e of a run of len elements, as 4 dwords; elements at or beyond
+// len read as 0 (for both inputs, hence "unchanged").  Any alignment.
+__device__ __forceinline__ u32x4 load8_guarded(const uint16_t *p, uint32_t e, uint32_t len) {
+    uint32_t h[8];
+#pragma unroll
+    for (int k = 0; k < 8; ++k) h[k] = (e + k < len) ? (uint32_t)p[e + k] : 0u;
+    u32x4 r;
+    r.x = h[0] | (h[1] << 16); r.y = h[2] | (h[3] << 16);
+    r.z = h[4] | (h[5] << 16); r.w = h[6] | (h[7] << 16);
+    return r;
+}
+
+// bit k of the result is set iff the k-th 16-bit pattern of a and b differ (k = 0..7, memory order)
+__device__ __forceinline__ uint32_t diff_mask8(u32x4 a, u32x4 b) {
+    uint32_t m = 0;
+    const uint32_t d0 = a.x ^ b.x, d1 = a.y ^ b.y, d2 = a.z ^ b.z, d3 = a.w ^ b.w;
+    m |= (d0 & 0xFFFFu) ? 1u : 0u;   m |= (d0 >> 16) ? 2u : 0u;
+    m |= (d1 & 0xFFFFu) ? 4u : 0u;   m |= (d1 >> 16) ? 8u : 0u;
+    m |= (d2 & 0xFFFFu) ? 16u : 0u;  m |= (d2 >> 16) ? 32u : 0u;
+    m |= (d3 & 0xFFFFu) ? 64u : 0u;  m |= (d3 >> 16) ? 128u : 0u;
+    return m;
+}
+
+__device__ __forceinline__ uint32_t pattern_at(u32x4 v, uint32_t e) {
+    const uint32_t lo = (e & 2u) ? v.y : v.x;
+    const uint32_t hi = (e & 2u) ? v.w : v.z;
+    const uint32_t w = (e & 4u) ? hi : lo;
+    return (e & 1u) ? (w >> 16) : (w & 0xFFFFu);
+}
+
+__device__ __forceinline__ unsigned long long status_load(const unsigned long long *p) {
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void status_store(unsigned long long *p, unsigned long long v) {
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ unsigned long long status_word(uint32_t epoch, uint32_t flag, uint32_t value) {
+    return ((unsigned long long)((epoch << 2) | flag) << 32) | value;
+}
+
+// ---------------------------------------------------------------------------------------------
+// decoupled look-back, run by all 64 lanes of wave 0.  Returns the number of changed elements in
+// the tiles first_tile .. tile-1 of the same bucket.  Lane l inspects tile (pos - l); the window
+// slides back by 64 until a tile with an inclusive prefix, or the bucket's first tile, is reached.
+// Bounded: after spin_limit polls of one window the wave gives up, raises kFlagTimeout and
+// returns what it has (ranks are clamped by the caller, so memory safety does not depend on it).
+// ---------------------------------------------------------------------------------------------
+__device__ __forceinline__ uint32_t look_back(const ExtractArgs &a, uint32_t tile, uint32_t first_tile, int lane) {
+    uint32_t excl = 0;
+    int64_t pos = (int64_t)tile - 1;
+    while (pos >= (int64_t)first_tile) {
+        const int64_t idx = pos - lane;
+        const bool in_bucket = idx >= (int64_t)first_tile;
+        uint32_t flag = 0, value = 0;
+        unsigned long long need = 0;
+        bool found_prefix = false;
+        uint32_t polls = 0;
+        for (;;) {
+            if (in_bucket) {
+                const unsigned long long w = status_load(a.status + idx);
+                const uint32_t hi = (uint32_t)(w >> 32);
+                flag = ((hi >> 2) == a.epoch) ? (hi & 3u) : 0u;
+                value = (uint32_t)w;
+            }
+            const unsigned long long valid = __ballot(in_bucket);            // a low run of lanes
+            const unsigned long long pending = __ballot(in_bucket && flag == 0);
+            const unsigned long long prefixed = __ballot(in_bucket && flag == kStPrefix);
+            found_prefix = prefixed != 0;
+            if (found_prefix) {
+                const int first = __builtin_ctzll(prefixed);                 // nearest tile that has a prefix
+                need = (first == 63) ? ~0ull : ((1ull << (first + 1)) - 1ull);
+            } else {
+                need = valid;
+            }
+            if ((pending & need) == 0) break;
+            if (++polls > a.spin_limit) {
+                if (lane == 0) atomicOr(a.flags, kFlagTimeout);
+                need &= ~pending;
+                found_prefix = true;                                         // stop walking back
+                break;
+            }
+            __builtin_amdgcn_s_sleep(2);
+        }
+        const uint32_t mine = ((need >> lane) & 1ull) ? value : 0u;
+        excl += lane63(wave_inclusive_scan(mine));
+        if (found_prefix) break;
+        pos -= 64;
+    }
+    return excl;
+}
+
+// ---------------------------------------------------------------------------------------------
+// extract
+// ---------------------------------------------------------------------------------------------
+template <int V, bool MULTI, bool NT>
+__global__ __launch_bounds__(kThreads) void extract_kernel(const ExtractArgs a) {
+    static_assert(V % 2 == 0, "counts are scanned in packed pairs");
+    constexpr uint32_t TILE = (uint32_t)V * kUnit;
+    __shared__ uint32_t s_ticket;
+    __shared__ uint32_t s_wave_total[kWaves];
+    __shared__ uint32_t s_excl;
+    __shared__ uint32_t s_stage[kStage];
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    if (tid == 0) s_ticket = __hip_atomic_fetch_add(a.ticket, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __syncthreads();
+    const uint32_t tile = uniform(s_ticket);
+    if (tile >= a.ntiles) return;          // cannot happen while the counters are consistent
+
+    // ---- where this tile lives
+    uint32_t bucket, bucket_off, len, first_tile, idx_base;
+    bool last;
+    uint16_t *po; const uint16_t *pn;
+    if (MULTI) {
+        const TileDesc d = a.tiles[tile];
+        const PtrPair p = a.ptrs[d.tensor];
+        po = p.old_w + d.tensor_off; pn = p.new_w + d.tensor_off;
+        bucket = d.bucket; bucket_off = d.bucket_off; len = d.len; first_tile = d.first_tile; last = d.last != 0;
+        idx_base = bucket_off;                          // index = position inside the bucket
+    } else {
+        bucket = tile / a.tiles_per_bucket;
+        const uint32_t k = tile - bucket * a.tiles_per_bucket;
+        const uint64_t b0 = (uint64_t)bucket * a.be;
+        const uint32_t blen = (uint32_t)((a.n - b0 < a.be) ? (a.n - b0) : a.be);
+        bucket_off = k * TILE;
+        len = (blen - bucket_off < TILE) ? (blen - bucket_off) : TILE;
+        first_tile = bucket * a.tiles_per_bucket;
+        last = (bucket_off + len == blen);
+        po = a.old_w + b0 + bucket_off; pn = a.new_w + b0 + bucket_off;
+        idx_base = (uint32_t)(b0 + bucket_off);         // index = tensor-flat position
+    }
+
+    // ---- stream the tile.  Layout: wave w owns elements [w*V*512, (w+1)*V*512); inside it vector j
+    // of lane l holds elements (j*64 + l)*8 .. +8, so ascending order is (wave, j, lane, element).
+    u32x4 xo[V], xn[V];
+    const uint32_t e0 = (uint32_t)wave * (V * 512u) + (uint32_t)lane * 8u;
+    const bool aligned = ((((uintptr_t)po) | ((uintptr_t)pn)) & 15u) == 0;
+    if (aligned && len == TILE) {
+#pragma unroll
+        for (int j = 0; j < V; ++j) xn[j] = load16<NT>(pn + e0 + j * 512);
+#pragma unroll
+        for (int j = 0; j < V; ++j) xo[j] = load16<NT>(po + e0 + j * 512);
+    } else {
+#pragma unroll
+        for (int j = 0; j < V; ++j) {
+            const uint32_t e = e0 + j * 512;
+            if (aligned && e + 8 <= len) {
+                xn[j] = load16<false>(pn + e); xo[j] = load16<false>(po + e);
+            } else {
+                xn[j] = load8_guarded(pn, e, len); xo[j] = load8_guarded(po, e, len);
+            }
+        }
+    }
+
+    // ---- change masks and their counts
+    uint32_t m[V];
+    uint32_t pk[V / 2];
+#pragma unroll
+    for (int j = 0; j < V; ++j) m[j] = diff_mask8(xo[j], xn[j]);
+#pragma unroll
+    for (int q = 0; q < V / 2; ++q) pk[q] = __popc(m[2 * q]) | (__popc(m[2 * q + 1]) << 16);
+
+    // ---- wave scan (two vectors per register), then offsets of each vector inside the wave
+    uint32_t ex[V];       // rank of this lane's first changed element of vector j inside the wave
+    uint32_t wave_total = 0;
+#pragma unroll
+    for (int q = 0; q < V / 2; ++q) {
+        const uint32_t inc = wave_inclusive_scan(pk[q]);
+        const uint32_t tot = lane63(inc);
+        const uint32_t exc = inc - pk[q];
+        ex[2 * q] = wave_total + (exc & 0xFFFFu);
+        wave_total += tot & 0xFFFFu;
+        ex[2 * q + 1] = wave_total + (exc >> 16);
+        wave_total += tot >> 16;
+    }
+    if (lane == 0) s_wave_total[wave] = wave_total;
+    __syncthreads();
+    uint32_t wave_base = 0, tile_total = 0;
+#pragma unroll
+    for (int w = 0; w < kWaves; ++w) {
+        const uint32_t t = s_wave_total[w];
+        wave_base += (w < wave) ? t : 0u;
+        tile_total += t;
+    }
+    tile_total = uniform(tile_total);
+
+    // ---- chain with the earlier tiles of the bucket (wave 0), while the other waves start staging
+    if (wave == 0) {
+        uint32_t excl = 0;
+        if (tile == first_tile) {
+            if (lane == 0) status_store(a.status + tile, status_word(a.epoch, kStPrefix, tile_total));
+        } else {
+            if (lane == 0) status_store(a.status + tile, status_word(a.epoch, kStAgg, tile_total));
+            excl = look_back(a, tile, first_tile, lane);
+            if (lane == 0) status_store(a.status + tile, status_word(a.epoch, kStPrefix, excl + tile_total));
+        }
+        if (lane == 0) {
+            s_excl = excl;
+            if (last) {
+                const uint32_t c = excl + tile_total;
+                a.counts[bucket] = c;
+                if ((uint64_t)c > a.cap) atomicOr(a.flags, kFlagOverflow);
+            }
+        }
+    }
+
+    // ---- stage (index, value) pairs in LDS in rank order, write out coalesced; kStage per round
+    int32_t *const Ib = a.I + (uint64_t)bucket * a.cap;
+    uint16_t *const Vb = a.V + (uint64_t)bucket * a.cap;
+    for (uint32_t r0 = 0; r0 < tile_total; r0 += kStage) {
+#pragma unroll
+        for (int j = 0; j < V; ++j) {
+            uint32_t mm = m[j];
+            if (mm) {
+                uint32_t rank = wave_base + ex[j] - r0;
+                const uint32_t local = e0 + j * 512;
+                while (mm) {
+                    const uint32_t e = (uint32_t)__builtin_ctz(mm);
+                    mm &= mm - 1u;
+                    if (rank < kStage) s_stage[rank] = ((local + e) << 16) | pattern_at(xn[j], e);
+                    ++rank;
+                }
+            }
+        }
+        __syncthreads();
+        const uint32_t excl = s_excl;
+        const uint32_t nst = (tile_total - r0 < kStage) ? (tile_total - r0) : kStage;
+        for (uint32_t k = tid; k < nst; k += kThreads) {
+            const uint32_t ent = s_stage[k];
+            const uint32_t local = ent >> 16;
+            const uint16_t val = (uint16_t)(ent & 0xFFFFu);
+            const uint64_t r = (uint64_t)excl + r0 + k;
+            if (local < len) {                      // always true for a correct scan; keeps stores in bounds
+                if (r < a.cap) { Ib[r] = (int32_t)(idx_base + local); Vb[r] = val; }
+                po[local] = val;                    // snapshot refresh: W_prev <- W at changed positions
+            }
+        }
+        __syncthreads();
+    }
+
+    // ---- the last workgroup to finish rewinds the counters for the next launch
+    if (tid == 0) {
+        const uint32_t d = __hip_atomic_fetch_add(a.ticket + 32, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (d == a.ntiles - 1) {
+            __hip_atomic_store(a.ticket, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __hip_atomic_store(a.ticket + 32, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// apply: W[I] <- V
+// ---------------------------------------------------------------------------------------------
+template <bool MULTI>
+__global__ __launch_bounds__(kThreads) void apply_kernel(const ApplyArgs a) {
+    const uint32_t b = blockIdx.x / a.chunks_per_bucket;
+    const uint32_t c = blockIdx.x - b * a.chunks_per_bucket;
+    if (b >= a.nb) return;
+    const uint32_t cnt_true = a.counts[b];
+    const uint64_t cnt = ((uint64_t)cnt_true < a.cap) ? cnt_true : a.cap;
+    const uint64_t start = (uint64_t)c * kApplyChunk;
+    if (start >= cnt) return;
+    const uint64_t end = (start + kApplyChunk < cnt) ? (start + kApplyChunk) : cnt;
+    const int32_t *const Ib = a.I + (uint64_t)b * a.cap;
+    const uint16_t *const Vb = a.V + (uint64_t)b * a.cap;
+    bool bad = false;
+    if (MULTI) {
+        const uint64_t b0 = (uint64_t)b * a.be;
+        const uint32_t blen = (uint32_t)((a.total - b0 < a.be) ? (a.total - b0) : a.be);
+        const uint32_t s_lo = a.seg_begin[b], s_hi = a.seg_begin[b + 1];
+        for (uint64_t k = start + threadIdx.x; k < end; k += kThreads) {
+            const uint32_t idx = (uint32_t)Ib[k];
+            const uint16_t val = Vb[k];
+            if (idx >= blen) { bad = true; continue; }
+            // last segment of the bucket whose bucket_off <= idx
+            uint32_t lo = s_lo, hi = s_hi;          // invariant: segs[lo].bucket_off <= idx < segs[hi].bucket_off
+            while (hi - lo > 1) {
+                const uint32_t mid = (lo + hi) >> 1;
+                if (a.segs[mid].bucket_off <= idx) lo = mid; else hi = mid;
+            }
+            const SegDesc s = a.segs[lo];
+            const uint32_t off = idx - s.bucket_off;
+            if (off >= s.len) { bad = true; continue; }   // cannot happen for a well-formed plan
+            a.wptrs[s.tensor][(uint64_t)s.tensor_off + off] = val;
+        }
+    } else {
+        const uint64_t lo = (uint64_t)b * a.be;
+        const uint64_t hi = (lo + a.be < a.n) ? (lo + a.be) : a.n;
+        for (uint64_t k = start + threadIdx.x; k < end; k += kThreads) {
+            const int64_t idx = Ib[k];
+            const uint16_t val = Vb[k];
+            if (idx < (int64_t)lo || idx >= (int64_t)hi) { bad = true; continue; }
+            a.w[idx] = val;
+        }
+    }
+    if (bad) atomicOr(a.flags, kFlagBadIndex);
+}
+
+// ---------------------------------------------------------------------------------------------
+// small utilities
+// ---------------------------------------------------------------------------------------------
+__global__ void fill_u64_kernel(unsigned long long *p, uint64_t n, unsigned long long v) {
+    const uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = v;
+}
+
+// two-stream read probe with extract's load shape; the XOR-reduction keeps the loads alive
+template <int V, bool NT>
+__global__ __launch_bounds__(kThreads) void stream_probe_kernel(const uint16_t *pa, const uint16_t *pb, uint64_t nvec,
+                                                                 uint32_t *sink) {
+    constexpr uint32_t TILE = (uint32_t)V * kUnit;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const uint64_t base = (uint64_t)blockIdx.x * TILE + (uint32_t)wave * (V * 512u) + (uint32_t)lane * 8u;
+    u32x4 acc = {0, 0, 0, 0};
+    u32x4 xa[V], xb[V];
+#pragma unroll
+    for (int j = 0; j < V; ++j) {
+        const uint64_t e = base + j * 512;
+        const bool ok = e / 8 < nvec;
+        xa[j] = ok ? load16<NT>(pa + e) : acc;
+        xb[j] = ok ? load16<NT>(pb + e) : acc;
+    }
+#pragma unroll
+    for (int j = 0; j < V; ++j) acc ^= xa[j] ^ xb[j];
+    uint32_t r = acc.x ^ acc.y ^ acc.z ^ acc.w;
+    r = lane63(wave_inclusive_scan(r & 0xFFu));
+    if (lane == 0 && wave == 0) sink[blockIdx.x] = r;
+}
+
+}  // namespace srs

@@ -1,0 +1,243 @@
+"""ctypes binding of libsrs.so -- argument marshalling only; every step runs in the HIP kernels.
+
+The names follow include/srs.h: ``Context.extract / apply / extract_multi / apply_multi`` call
+``srs_extract / srs_apply / srs_extract_multi / srs_apply_multi``.  Tensors are torch CUDA
+(ROCm) tensors used purely as device memory; the current torch stream is passed through.
+
+Importing this module fails loudly when the library has not been built
+(``python -m paper_2605_07330_amd.build``): there is no CPU fallback.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import List, Optional, Sequence
+
+import torch  # loads the HIP runtime that libsrs.so binds to
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libsrs.so")
+
+if not os.path.exists(LIB_PATH):
+    raise ImportError(f"{LIB_PATH} is missing: build it with `python -m paper_2605_07330_amd.build` "
+                      "(hipcc --offload-arch=gfx950); there is no fallback path")
+
+_lib = C.CDLL(LIB_PATH)
+
+OK, ERR_INVALID, ERR_HIP, ERR_NOMEM, ERR_NO_DEVICE = 0, -1, -2, -3, -4
+FLAG_OVERFLOW, FLAG_BAD_INDEX, FLAG_TIMEOUT = 1, 2, 4
+OPT_SPIN_LIMIT, OPT_TILE_ELEMS, OPT_NONTEMPORAL = 1, 2, 3
+
+EXPORTS = [
+    "srs_create", "srs_destroy", "srs_set_option", "srs_strerror", "srs_version", "srs_status",
+    "srs_extract", "srs_apply", "srs_plan_create", "srs_plan_info", "srs_plan_destroy",
+    "srs_extract_multi", "srs_apply_multi", "srs_stream_probe", "srs_stream_probe_sink_words",
+]
+
+
+class TensorPair(C.Structure):
+    _fields_ = [("old_snapshot", C.c_void_p), ("new_w", C.c_void_p)]
+
+
+class Tensor(C.Structure):
+    _fields_ = [("weights", C.c_void_p)]
+
+
+_vp, _u64, _u32p = C.c_void_p, C.c_uint64, C.POINTER(C.c_uint32)
+_lib.srs_create.argtypes = [C.POINTER(_vp), C.c_int]
+_lib.srs_destroy.argtypes = [_vp]
+_lib.srs_set_option.argtypes = [_vp, C.c_int, _u64]
+_lib.srs_strerror.argtypes = [C.c_int]
+_lib.srs_strerror.restype = C.c_char_p
+_lib.srs_version.argtypes = []
+_lib.srs_status.argtypes = [_vp, _u32p, _vp]
+_lib.srs_extract.argtypes = [_vp, _vp, _vp, _u64, _u64, _vp, _vp, _vp, _u64, _vp]
+_lib.srs_apply.argtypes = [_vp, _vp, _u64, _u64, _vp, _vp, _vp, _u64, _vp]
+_lib.srs_plan_create.argtypes = [_vp, C.POINTER(_u64), C.c_uint32, _u64, C.POINTER(_vp)]
+_lib.srs_plan_info.argtypes = [_vp, C.POINTER(_u64), _u32p, _u32p, _u32p]
+_lib.srs_plan_destroy.argtypes = [_vp]
+_lib.srs_extract_multi.argtypes = [_vp, _vp, C.POINTER(TensorPair), _vp, _vp, _vp, _u64, _vp]
+_lib.srs_apply_multi.argtypes = [_vp, _vp, C.POINTER(Tensor), _vp, _vp, _vp, _u64, _vp]
+_lib.srs_stream_probe.argtypes = [_vp, _vp, _vp, _u64, _vp, _vp]
+_lib.srs_stream_probe_sink_words.argtypes = [_u64]
+_lib.srs_stream_probe_sink_words.restype = _u64
+for _n in EXPORTS:
+    if _n not in ("srs_strerror", "srs_stream_probe_sink_words"):
+        getattr(_lib, _n).restype = C.c_int
+
+
+class SrsError(RuntimeError):
+    def __init__(self, code: int, where: str):
+        self.code = code
+        super().__init__(f"{where}: {_lib.srs_strerror(code).decode()} ({code})")
+
+
+def _check(rc: int, where: str) -> None:
+    if rc != OK:
+        raise SrsError(rc, where)
+
+
+def version() -> int:
+    return _lib.srs_version()
+
+
+def _stream_ptr(stream: Optional[torch.cuda.Stream]) -> int:
+    s = stream if stream is not None else torch.cuda.current_stream()
+    return int(s.cuda_stream)
+
+
+def _dev16(t: torch.Tensor, what: str) -> None:
+    if not (isinstance(t, torch.Tensor) and t.is_cuda and t.element_size() == 2 and t.is_contiguous()):
+        raise TypeError(f"{what}: expected a contiguous 16-bit tensor on the GPU")
+
+
+def _payload_ok(I: torch.Tensor, V: torch.Tensor, counts: torch.Tensor, nb: int, cap: int) -> None:
+    if not (I.is_cuda and I.dtype == torch.int32 and I.is_contiguous() and I.numel() >= nb * cap):
+        raise TypeError("I: expected contiguous int32 GPU tensor of at least nb*cap elements")
+    if not (V.is_cuda and V.element_size() == 2 and V.is_contiguous() and V.numel() >= nb * cap):
+        raise TypeError("V: expected contiguous 16-bit GPU tensor of at least nb*cap elements")
+    if not (counts.is_cuda and counts.element_size() == 4 and counts.is_contiguous() and counts.numel() >= nb):
+        raise TypeError("counts: expected contiguous 32-bit GPU tensor of at least nb elements")
+
+
+class Plan:
+    """Bucket / segment / tile tables of one tensor list (srs_plan_*)."""
+
+    def __init__(self, ctx: "Context", numel: Sequence[int], bucket_elems: int):
+        self._h = _vp()
+        self.numel = [int(x) for x in numel]
+        self.bucket_elems = int(bucket_elems)
+        arr = (_u64 * max(len(self.numel), 1))(*self.numel)
+        _check(_lib.srs_plan_create(ctx._h, arr, len(self.numel), self.bucket_elems, C.byref(self._h)), "srs_plan_create")
+        tot, nb, ns, nt = _u64(), C.c_uint32(), C.c_uint32(), C.c_uint32()
+        _check(_lib.srs_plan_info(self._h, C.byref(tot), C.byref(nb), C.byref(ns), C.byref(nt)), "srs_plan_info")
+        self.total, self.nbuckets, self.nsegments, self.ntiles = tot.value, nb.value, ns.value, nt.value
+        self._pairs = None
+        self._pairs_key = None
+        self._tens = None
+        self._tens_key = None
+
+    def close(self) -> None:
+        if self._h:
+            _lib.srs_plan_destroy(self._h)
+            self._h = _vp()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+class Context:
+    """Per-stream scratch of the library (srs_create / srs_destroy)."""
+
+    def __init__(self, device: int = 0):
+        if not torch.cuda.is_available():
+            raise RuntimeError("no GPU visible: the sparse-sync hot path has no CPU fallback")
+        self._h = _vp()
+        self.device = int(device)
+        _check(_lib.srs_create(C.byref(self._h), self.device), "srs_create")
+
+    def close(self) -> None:
+        if self._h:
+            _lib.srs_destroy(self._h)
+            self._h = _vp()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def set_option(self, option: int, value: int) -> None:
+        _check(_lib.srs_set_option(self._h, option, int(value)), "srs_set_option")
+
+    def status(self, stream: Optional[torch.cuda.Stream] = None) -> int:
+        """Synchronises the stream; returns and clears the device flag word."""
+        f = C.c_uint32(0)
+        _check(_lib.srs_status(self._h, C.byref(f), _stream_ptr(stream)), "srs_status")
+        return f.value
+
+    # ---- single tensor --------------------------------------------------------------------
+    def extract(self, old: torch.Tensor, new: torch.Tensor, bucket_elems: int, I: torch.Tensor, V: torch.Tensor,
+                counts: torch.Tensor, cap: int, stream: Optional[torch.cuda.Stream] = None) -> None:
+        _dev16(old, "old"), _dev16(new, "new")
+        n = old.numel()
+        if new.numel() != n:
+            raise ValueError("old/new size mismatch")
+        if bucket_elems > 0 and cap > 0:
+            _payload_ok(I, V, counts, (n + bucket_elems - 1) // bucket_elems, cap)
+        _check(_lib.srs_extract(self._h, old.data_ptr(), new.data_ptr(), n, bucket_elems, I.data_ptr(), V.data_ptr(),
+                                counts.data_ptr(), cap, _stream_ptr(stream)), "srs_extract")
+
+    def apply(self, weights: torch.Tensor, bucket_elems: int, I: torch.Tensor, V: torch.Tensor, counts: torch.Tensor,
+              cap: int, stream: Optional[torch.cuda.Stream] = None) -> None:
+        _dev16(weights, "weights")
+        n = weights.numel()
+        if bucket_elems > 0 and cap > 0:
+            _payload_ok(I, V, counts, (n + bucket_elems - 1) // bucket_elems, cap)
+        _check(_lib.srs_apply(self._h, weights.data_ptr(), n, bucket_elems, I.data_ptr(), V.data_ptr(),
+                              counts.data_ptr(), cap, _stream_ptr(stream)), "srs_apply")
+
+    # ---- tensor lists ---------------------------------------------------------------------
+    def plan(self, numel: Sequence[int], bucket_elems: int) -> Plan:
+        return Plan(self, numel, bucket_elems)
+
+    def extract_multi(self, plan: Plan, old: Sequence[torch.Tensor], new: Sequence[torch.Tensor], I: torch.Tensor,
+                      V: torch.Tensor, counts: torch.Tensor, cap: int, stream: Optional[torch.cuda.Stream] = None) -> None:
+        if len(old) != len(plan.numel) or len(new) != len(plan.numel):
+            raise ValueError("tensor list does not match the plan")
+        key = (tuple(t.data_ptr() for t in old), tuple(t.data_ptr() for t in new))
+        if plan._pairs_key != key:
+            for k, (o, w) in enumerate(zip(old, new)):
+                _dev16(o, f"old[{k}]"), _dev16(w, f"new[{k}]")
+                if o.numel() != plan.numel[k] or w.numel() != plan.numel[k]:
+                    raise ValueError(f"tensor {k}: numel differs from the plan")
+            arr = (TensorPair * max(len(old), 1))()
+            for k, (o, w) in enumerate(zip(old, new)):
+                arr[k].old_snapshot, arr[k].new_w = o.data_ptr(), w.data_ptr()
+            plan._pairs, plan._pairs_key = arr, key
+        if cap > 0:
+            _payload_ok(I, V, counts, plan.nbuckets, cap)
+        _check(_lib.srs_extract_multi(self._h, plan._h, plan._pairs, I.data_ptr(), V.data_ptr(), counts.data_ptr(), cap,
+                                      _stream_ptr(stream)), "srs_extract_multi")
+
+    def apply_multi(self, plan: Plan, weights: Sequence[torch.Tensor], I: torch.Tensor, V: torch.Tensor,
+                    counts: torch.Tensor, cap: int, stream: Optional[torch.cuda.Stream] = None) -> None:
+        if len(weights) != len(plan.numel):
+            raise ValueError("tensor list does not match the plan")
+        key = tuple(t.data_ptr() for t in weights)
+        if plan._tens_key != key:
+            for k, w in enumerate(weights):
+                _dev16(w, f"weights[{k}]")
+                if w.numel() != plan.numel[k]:
+                    raise ValueError(f"tensor {k}: numel differs from the plan")
+            arr = (Tensor * max(len(weights), 1))()
+            for k, w in enumerate(weights):
+                arr[k].weights = w.data_ptr()
+            plan._tens, plan._tens_key = arr, key
+        if cap > 0:
+            _payload_ok(I, V, counts, plan.nbuckets, cap)
+        _check(_lib.srs_apply_multi(self._h, plan._h, plan._tens, I.data_ptr(), V.data_ptr(), counts.data_ptr(), cap,
+                                    _stream_ptr(stream)), "srs_apply_multi")
+
+    # ---- measurement aid ------------------------------------------------------------------
+    def stream_probe(self, a: torch.Tensor, b: torch.Tensor, sink: torch.Tensor,
+                     stream: Optional[torch.cuda.Stream] = None) -> None:
+        nbytes = a.numel() * a.element_size()
+        if b.numel() * b.element_size() != nbytes:
+            raise ValueError("size mismatch")
+        if sink.numel() * sink.element_size() < 4 * _lib.srs_stream_probe_sink_words(nbytes):
+            raise ValueError("sink too small")
+        _check(_lib.srs_stream_probe(self._h, a.data_ptr(), b.data_ptr(), nbytes, sink.data_ptr(), _stream_ptr(stream)),
+               "srs_stream_probe")
+
+
+def alloc_payload(nbuckets: int, cap: int, device) -> tuple:
+    """(I, V, counts) device buffers of the layout srs.h describes.  I is filled with -1 and V with
+    0xFFFF so that tests can see that slots beyond counts[b] are left untouched."""
+    I = torch.full((nbuckets, cap), -1, dtype=torch.int32, device=device)
+    V = torch.full((nbuckets, cap), -1, dtype=torch.int16, device=device)
+    counts = torch.zeros(nbuckets, dtype=torch.int32, device=device)
+    return I, V, counts
