@@ -1,0 +1,262 @@
+#!/usr/bin/env python3
+"""Benchmark of the sparse-weight-sync hot path on one MI355X.
+
+One "step" = one pass of the whole hot path over one synthetic update of the workload:
+    srs_extract_multi(snapshot, new)  ->  (I, V, counts)      (Trainer side, Alg. 1 + Alg. 2)
+    srs_apply_multi(rollout weights, I, V, counts)             (Rollout side, Alg. 3)
+with every input resident in HBM before the timed region.  Default workload: the
+Qwen3-30B-A3B-shaped set (30.5 G BF16 elements, 910 buckets of 64 MiB) at 1 % changed elements.
+
+Two full weight versions W0 and W1 (W1 = W0 with an iid 1 % update) stay resident; step i
+extracts against W1 when i is even and against W0 when i is odd, so every step sees exactly the
+same 1 % change mask while the snapshot and the rollout copy keep being refreshed for real.
+
+Prints ONE JSON line (see the keys at the bottom).  `value` = dense bytes scanned (old + new,
+4 B per element) per second of extract + apply wall time.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+
+# HBM traffic per extract launch measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE), scaled by a
+# copy kernel of known size; filled in from profiles/ once measured for the named workload, else None.
+MEASURED_TRAFFIC_BYTES = {}
+
+
+def log(msg: str) -> None:
+    print(f"[bench] {msg}", file=sys.stderr, flush=True)
+
+
+def overlapping_tensors(numels, be, b_lo, b_hi):
+    lo, hi, out, g = b_lo * be, b_hi * be, [], 0
+    for k, m in enumerate(numels):
+        if g + m > lo and g < hi and m:
+            out.append(k)
+        g += m
+    return out
+
+
+def cpu_baseline_and_check(torch, np, oracle, wl, old_ws, new_ws, payload, buckets_per_group, ngroups):
+    """Times the oracle (as it stands, one thread) on a sample of the workload's buckets and checks
+    the GPU payload of those buckets against it.  old_ws/new_ws are the weight sets the last GPU
+    extract compared (old_ws untouched by it)."""
+    I, V, counts = payload
+    be, numels = wl.bucket_elems, [t.numel for t in wl.tensors]
+    nb = wl.num_buckets
+    stride = max(1, (nb - buckets_per_group) // max(1, ngroups - 1)) if ngroups > 1 else 1
+    starts = sorted({min(max(0, nb - buckets_per_group), g * stride) for g in range(ngroups)})
+    t_extract = t_apply = 0.0
+    elems = 0
+    cap = I.shape[1]
+    for b_lo in starts:
+        b_hi = min(nb, b_lo + buckets_per_group)
+        ks = overlapping_tensors(numels, be, b_lo, b_hi)
+        olds = [None] * len(numels); news = [None] * len(numels); rolls = [None] * len(numels)
+        for k in ks:
+            olds[k] = old_ws.tensors[k].view(torch.int16).cpu().numpy().view(np.uint16)
+            news[k] = new_ws.tensors[k].view(torch.int16).cpu().numpy().view(np.uint16)
+            rolls[k] = olds[k].copy()
+        t0 = time.perf_counter()
+        oI, oV, oc, _ = oracle.extract_multi(olds, news, numels, be, cap=cap, b_lo=b_lo, b_hi=b_hi)
+        t1 = time.perf_counter()
+        oracle.apply_multi(rolls, numels, be, oI, oV, oc, b_lo=b_lo, b_hi=b_hi)
+        t2 = time.perf_counter()
+        t_extract += t1 - t0; t_apply += t2 - t1
+        elems += min(wl.numel, b_hi * be) - b_lo * be
+        gI = I[b_lo:b_hi].cpu().numpy(); gV = V[b_lo:b_hi].cpu().numpy().view(np.uint16)
+        gc = counts[b_lo:b_hi].cpu().numpy().view(np.uint32)
+        if not np.array_equal(gc, oc):
+            raise SystemExit(f"bench self-check failed: counts differ in buckets {b_lo}..{b_hi}")
+        for j in range(b_hi - b_lo):
+            c = int(oc[j])
+            if not (np.array_equal(gI[j, :c], oI[j, :c]) and np.array_equal(gV[j, :c], oV[j, :c])):
+                raise SystemExit(f"bench self-check failed: payload differs in bucket {b_lo + j}")
+        log(f"oracle sample buckets [{b_lo},{b_hi}): extract {t1 - t0:.2f}s apply {t2 - t1:.2f}s, GPU payload matches")
+    return t_extract, t_apply, elems, len(starts) * buckets_per_group
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=4)
+    ap.add_argument("--config", type=int, default=2, help="workload id (BASELINE configs); 2 = Qwen3-30B-A3B-shaped")
+    ap.add_argument("--density", type=float, default=None)
+    ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--tile", type=int, default=0, help="extract tile elements (0 = library default)")
+    ap.add_argument("--nontemporal", type=int, default=-1)
+    ap.add_argument("--tiny", action="store_true", help="structure-preserving tiny workload (debugging only)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-groups", type=int, default=10, help="oracle sample: groups of 16 buckets")
+    ap.add_argument("--probe", action="store_true", help="also time the two-stream read probe")
+    args = ap.parse_args()
+
+    if args.gpus != 1:
+        print("bench.py: this build measures one GPU only (the path has no cross-GPU step); run with --gpus 1",
+              file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+
+    from paper_2605_07330_amd import srs, synth
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; the hot path has no CPU fallback", file=sys.stderr)
+        return 3
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+
+    wl = synth.workload(args.config, density=args.density, tiny=args.tiny)
+    N = wl.numel
+    log(f"workload {wl.name}: {len(wl.tensors)} tensors, {N} elements ({2 * N / 1e9:.2f} GB), "
+        f"{wl.num_buckets} buckets of {wl.bucket_elems} elements")
+
+    t0 = time.perf_counter()
+    W0 = synth.WeightSet(wl, dev); W1 = synth.WeightSet(wl, dev)
+    S = synth.WeightSet(wl, dev); R = synth.WeightSet(wl, dev)
+    synth.fill_base(W0, args.seed)
+    nchanged, _ = synth.make_update(W1, W0, args.seed)
+    S.copy_from(W0); R.copy_from(W0)
+    torch.cuda.synchronize()
+    rho = nchanged / N
+    log(f"generated in {time.perf_counter() - t0:.1f}s: {nchanged} changed elements (rho = {rho:.5f})")
+
+    ctx = srs.Context(0)
+    if args.tile:
+        ctx.set_option(srs.OPT_TILE_ELEMS, args.tile)
+    if args.nontemporal >= 0:
+        ctx.set_option(srs.OPT_NONTEMPORAL, args.nontemporal)
+    plan = ctx.plan(S.numels, wl.bucket_elems)
+    cap = synth.payload_capacity(wl)
+    cap = (cap + 7) // 8 * 8
+    I = torch.empty((plan.nbuckets, cap), dtype=torch.int32, device=dev)
+    V = torch.empty((plan.nbuckets, cap), dtype=torch.int16, device=dev)
+    counts = torch.zeros(plan.nbuckets, dtype=torch.int32, device=dev)
+    log(f"plan: {plan.nbuckets} buckets, {plan.nsegments} segments, {plan.ntiles} tiles; cap {cap} pairs per bucket "
+        f"({plan.nbuckets * cap * 6 / 1e9:.2f} GB payload buffers)")
+
+    versions = [W1, W0]
+
+    def step(i, ev=None):
+        new = versions[i % 2]
+        if ev:
+            ev[0].record()
+        ctx.extract_multi(plan, S.tensors, new.tensors, I, V, counts, cap)
+        if ev:
+            ev[1].record()
+        ctx.apply_multi(plan, R.tensors, I, V, counts, cap)
+        if ev:
+            ev[2].record()
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    flags = ctx.status()
+    if flags:
+        raise SystemExit(f"device flags {flags} after warm-up")
+
+    events = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t_start = time.perf_counter()
+    for k in range(args.steps):
+        step(args.warmup + k, events[k])
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t_start
+
+    flags = ctx.status()
+    last_new = versions[(args.warmup + args.steps - 1) % 2] if args.warmup + args.steps else W0
+    total_counts = int(counts.to(torch.int64).sum().item())
+    ok = flags == 0 and total_counts == nchanged and torch.equal(S.flat.view(torch.int16), last_new.flat.view(torch.int16)) \
+        and torch.equal(R.flat.view(torch.int16), last_new.flat.view(torch.int16))
+    if not ok:
+        raise SystemExit(f"bench self-check failed: flags={flags} counts={total_counts} expected={nchanged}")
+
+    ext_ms = [e[0].elapsed_time(e[1]) for e in events]
+    app_ms = [e[1].elapsed_time(e[2]) for e in events]
+    ext_avg, app_avg = sum(ext_ms) / len(ext_ms), sum(app_ms) / len(app_ms)
+    ms_per_step = wall * 1e3 / args.steps
+    bytes_extract = (4.0 + 8.0 * rho) * N          # read old+new; write I(4)+V(2) and snapshot(2) per changed element
+    bytes_apply = 8.0 * rho * N                    # read I+V, write 2 per changed element
+    value = 4.0 * N / (ms_per_step * 1e-3) / 1e9
+    ach = bytes_extract / (ext_avg * 1e-3) / 1e9
+    combined = (bytes_extract + bytes_apply) / (ms_per_step * 1e-3) / 1e9
+    log(f"extract {ext_avg:.3f} ms (min {min(ext_ms):.3f}), apply {app_avg:.3f} ms (min {min(app_ms):.3f}), "
+        f"step {ms_per_step:.3f} ms; extract {ach:.0f} GB/s = {100 * ach / HBM_PEAK_GBS:.1f}% of peak; "
+        f"combined {combined:.0f} GB/s = {100 * combined / HBM_PEAK_GBS:.1f}%")
+
+    probe_gbs = None
+    if args.probe:
+        nbytes = min(2 * N, 16 << 30) // 32768 * 32768
+        sink = torch.empty(int(srs._lib.srs_stream_probe_sink_words(nbytes)), dtype=torch.int32, device=dev)
+        a = W0.flat.view(torch.int16)[: nbytes // 2]; b = W1.flat.view(torch.int16)[: nbytes // 2]
+        for _ in range(2):
+            ctx.stream_probe(a, b, sink)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(5):
+            ctx.stream_probe(a, b, sink)
+        e1.record(); torch.cuda.synchronize()
+        probe_gbs = 2 * nbytes * 5 / (e0.elapsed_time(e1) * 1e-3) / 1e9
+        log(f"two-stream read probe: {probe_gbs:.0f} GB/s")
+
+    cpu = None
+    if not args.no_cpu_baseline:
+        import oracle
+        # one more (untimed) step in a known direction, then the oracle on a sample of its buckets
+        i_next = args.warmup + args.steps
+        old_ws = versions[(i_next + 1) % 2]      # what the snapshot holds now
+        new_ws = versions[i_next % 2]
+        step(i_next)
+        torch.cuda.synchronize()
+        groups = 1 if args.tiny else args.cpu_groups
+        bpg = min(16, plan.nbuckets)
+        te, ta, elems, _ = cpu_baseline_and_check(torch, np, oracle, wl, old_ws, new_ws, (I, V, counts), bpg, groups)
+        cpu = {"value": round(4.0 * elems / (te + ta) / 1e9, 3), "unit": "GB/s", "cores": 1, "kind": "oracle",
+               "sample": f"{elems} elements ({elems / N * 100:.1f}% of the workload) in groups of {bpg} buckets spread "
+                         f"over the set; oracle extract {te:.2f}s + apply {ta:.2f}s, compute only"}
+
+    out = {
+        "metric": "extract+apply dense GB/s scanned",
+        "value": round(value, 1),
+        "unit": "GB/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "u16",
+        "data": "synthetic",
+        "config": {"workload": wl.name, "elements": N, "buckets": plan.nbuckets, "bucket_elems": wl.bucket_elems,
+                   "changed_fraction": round(rho, 6), "payload_cap": cap, "tile_elems": args.tile or 16384},
+        "sync_ms": round(ms_per_step, 4),
+        "extract_ms": round(ext_avg, 4),
+        "apply_ms": round(app_avg, 4),
+        "pct_hbm_peak_combined": round(100 * combined / HBM_PEAK_GBS, 2),
+        "pct_hbm_peak_extract": round(100 * ach / HBM_PEAK_GBS, 2),
+        "apply_strict_gbs": round(bytes_apply / (app_avg * 1e-3) / 1e9, 1),
+        "read_probe_gbs": None if probe_gbs is None else round(probe_gbs, 1),
+        "roofline": {"bound": "hbm", "kernel": "extract_kernel", "achieved": round(ach, 1), "peak": HBM_PEAK_GBS,
+                     "unit": "GB/s", "frac": round(ach / HBM_PEAK_GBS, 4),
+                     "traffic": MEASURED_TRAFFIC_BYTES.get(wl.name)},
+        "cpu_baseline": cpu,
+    }
+    print(json.dumps(out), flush=True)
+    plan.close(); ctx.close()
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())
