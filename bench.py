@@ -95,6 +95,7 @@ def main() -> int:
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--tile", type=int, default=0, help="extract tile elements (0 = library default)")
     ap.add_argument("--nontemporal", type=int, default=-1)
+    ap.add_argument("--interleave", type=int, default=0, help="buckets interleaved over consecutive workgroups (0 = default)")
     ap.add_argument("--tiny", action="store_true", help="structure-preserving tiny workload (debugging only)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-groups", type=int, default=10, help="oracle sample: groups of 16 buckets")
@@ -137,7 +138,11 @@ def main() -> int:
         ctx.set_option(srs.OPT_TILE_ELEMS, args.tile)
     if args.nontemporal >= 0:
         ctx.set_option(srs.OPT_NONTEMPORAL, args.nontemporal)
-    plan = ctx.plan(S.numels, wl.bucket_elems)
+    ctx.set_option(srs.OPT_INTERLEAVE, args.interleave) if args.interleave else None
+    # one plan per direction: each keeps its own device copy of the pointer table, so alternating the
+    # `new` version does not re-upload it every step
+    plans = [ctx.plan(S.numels, wl.bucket_elems), ctx.plan(S.numels, wl.bucket_elems)]
+    plan = plans[0]
     cap = synth.payload_capacity(wl)
     cap = (cap + 7) // 8 * 8
     I = torch.empty((plan.nbuckets, cap), dtype=torch.int32, device=dev)
@@ -147,15 +152,17 @@ def main() -> int:
         f"({plan.nbuckets * cap * 6 / 1e9:.2f} GB payload buffers)")
 
     versions = [W1, W0]
+    pairs = [ctx.bind_pairs(plans[d], S.tensors, versions[d].tensors) for d in (0, 1)]
+    rolls = [ctx.bind_weights(plans[d], R.tensors) for d in (0, 1)]
 
     def step(i, ev=None):
-        new = versions[i % 2]
+        d = i % 2
         if ev:
             ev[0].record()
-        ctx.extract_multi(plan, S.tensors, new.tensors, I, V, counts, cap)
+        ctx.extract_multi(plans[d], None, None, I, V, counts, cap, pairs=pairs[d])
         if ev:
             ev[1].record()
-        ctx.apply_multi(plan, R.tensors, I, V, counts, cap)
+        ctx.apply_multi(plans[d], None, I, V, counts, cap, tensors=rolls[d])
         if ev:
             ev[2].record()
 
@@ -254,7 +261,9 @@ def main() -> int:
         "cpu_baseline": cpu,
     }
     print(json.dumps(out), flush=True)
-    plan.close(); ctx.close()
+    for pl in plans:
+        pl.close()
+    ctx.close()
     return 0
 
 

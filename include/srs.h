@@ -60,13 +60,15 @@ typedef enum {
 #define SRS_OPT_TILE_ELEMS 2   /* elements per extract tile: 4096, 8192, 16384 or 32768 (tuning; affects
                                   plans created afterwards) */
 #define SRS_OPT_NONTEMPORAL 3  /* 1: stream weights with non-temporal loads */
+#define SRS_OPT_INTERLEAVE 4   /* buckets whose tiles are interleaved over consecutive workgroups, 1..4096
+                                  (tuning; affects plans created afterwards) */
 
-typedef struct srs_ctx srs_ctx;    /* per-stream scratch: tile status words, ticket counters, flag word */
+typedef struct srs_ctx srs_ctx;    /* per-stream scratch: tile status words, per-bucket ticket counters, flag word */
 typedef struct srs_plan srs_plan;  /* immutable bucket / segment / tile tables of one tensor list */
 
 /* Context.  srs_create selects `device`, allocates a few KiB of device scratch and synchronises.
- * The tile-status array grows on demand inside srs_extract* (that one call then allocates and
- * synchronises the device; later calls of the same or smaller size do not). */
+ * The tile-status and ticket arrays grow on demand inside srs_extract* (that one call then allocates
+ * and synchronises the device; later calls of the same or smaller size do not). */
 int srs_create(srs_ctx **out, int device);
 int srs_destroy(srs_ctx *ctx);                       /* synchronises the device, frees scratch */
 int srs_set_option(srs_ctx *ctx, int option, uint64_t value);

@@ -29,10 +29,13 @@ struct srs_ctx {
     int device = 0;
     unsigned long long *status = nullptr;   // tile status words
     uint64_t status_cap = 0;
-    uint32_t *counters = nullptr;           // [0] ticket, [32] finished, [64] flags
+    uint32_t *tickets = nullptr;            // per-bucket ticket counters
+    uint64_t tickets_cap = 0;               // in words
+    uint32_t *flags = nullptr;              // device flag word (own 256-byte allocation)
     uint32_t epoch = 1;
     uint32_t spin_limit = 1u << 24;
     uint32_t tile_elems = 16384;
+    uint32_t group = 32;                    // buckets whose tiles are interleaved over consecutive workgroups
     bool nontemporal = false;
 };
 
@@ -41,6 +44,8 @@ struct srs_plan {
     uint64_t total = 0, be = 0;
     uint32_t ntensors = 0, nbuckets = 0, nsegments = 0, ntiles = 0, tile_elems = 0;
     TileDesc *d_tiles = nullptr;
+    uint32_t *d_wg_bucket = nullptr;        // [ntiles] bucket served by each workgroup of extract
+    uint32_t *d_bucket_first = nullptr;     // [nbuckets+1] first tile of each bucket
     SegDesc *d_segs = nullptr;
     uint32_t *d_seg_begin = nullptr;
     PtrPair *d_pairs = nullptr;             // extract-side pointer table
@@ -61,8 +66,29 @@ int fill_status(srs_ctx *ctx, hipStream_t st) {
     return SRS_OK;
 }
 
-// make room for ntiles status words and hand out this launch's epoch
-int prepare_extract(srs_ctx *ctx, uint64_t ntiles, hipStream_t st, uint32_t *epoch) {
+// ticket counters sit 256 bytes apart (atomics on one cache line serialise) unless there are very
+// many buckets, which only happens with bucket sizes far below a tile
+uint32_t ticket_stride_for(uint64_t nb) { return nb <= 65536 ? 64u : 1u; }
+
+// make room for ntiles status words and nb ticket counters, rewind the counters and hand out this
+// launch's epoch
+int prepare_extract(srs_ctx *ctx, uint64_t ntiles, uint64_t nb, hipStream_t st, uint32_t *epoch, uint32_t *stride) {
+    *stride = ticket_stride_for(nb);
+    const uint64_t words = nb * (*stride);
+    if (words > ctx->tickets_cap) {
+        SRS_HIP(hipDeviceSynchronize());
+        if (ctx->tickets) SRS_HIP(hipFree(ctx->tickets));
+        ctx->tickets = nullptr; ctx->tickets_cap = 0;
+        const uint64_t cap = words + words / 4 + 4096;
+        SRS_HIP(hipMalloc((void **)&ctx->tickets, cap * sizeof(uint32_t)));
+        ctx->tickets_cap = cap;
+    }
+    {
+        const uint32_t threads = 256;
+        hipLaunchKernelGGL(zero_strided_kernel, dim3((uint32_t)((nb + threads - 1) / threads)), dim3(threads), 0, st,
+                           ctx->tickets, nb, *stride);
+        SRS_HIP(hipGetLastError());
+    }
     if (ntiles > ctx->status_cap) {
         SRS_HIP(hipDeviceSynchronize());
         if (ctx->status) SRS_HIP(hipFree(ctx->status));
@@ -132,11 +158,11 @@ int srs_create(srs_ctx **out, int device) {
     srs_ctx *ctx = new (std::nothrow) srs_ctx();
     if (!ctx) return SRS_ERR_NOMEM;
     ctx->device = device;
-    if (hipMalloc((void **)&ctx->counters, 96 * sizeof(uint32_t)) != hipSuccess) {
+    if (hipMalloc((void **)&ctx->flags, 256) != hipSuccess) {
         (void)hipGetLastError(); delete ctx; return SRS_ERR_HIP;
     }
-    if (hipMemset(ctx->counters, 0, 96 * sizeof(uint32_t)) != hipSuccess || hipDeviceSynchronize() != hipSuccess) {
-        (void)hipGetLastError(); (void)hipFree(ctx->counters); delete ctx; return SRS_ERR_HIP;
+    if (hipMemset(ctx->flags, 0, 256) != hipSuccess || hipDeviceSynchronize() != hipSuccess) {
+        (void)hipGetLastError(); (void)hipFree(ctx->flags); delete ctx; return SRS_ERR_HIP;
     }
     *out = ctx;
     return SRS_OK;
@@ -147,7 +173,8 @@ int srs_destroy(srs_ctx *ctx) {
     (void)hipSetDevice(ctx->device);
     (void)hipDeviceSynchronize();
     if (ctx->status) (void)hipFree(ctx->status);
-    if (ctx->counters) (void)hipFree(ctx->counters);
+    if (ctx->tickets) (void)hipFree(ctx->tickets);
+    if (ctx->flags) (void)hipFree(ctx->flags);
     delete ctx;
     return SRS_OK;
 }
@@ -163,6 +190,9 @@ int srs_set_option(srs_ctx *ctx, int option, uint64_t value) {
             ctx->tile_elems = (uint32_t)value; return SRS_OK;
         case SRS_OPT_NONTEMPORAL:
             ctx->nontemporal = value != 0; return SRS_OK;
+        case SRS_OPT_INTERLEAVE:
+            if (value == 0 || value > 4096) return SRS_ERR_INVALID;
+            ctx->group = (uint32_t)value; return SRS_OK;
         default: return SRS_ERR_INVALID;
     }
 }
@@ -171,9 +201,9 @@ int srs_status(srs_ctx *ctx, uint32_t *flags, void *stream) {
     if (!ctx || !flags) return SRS_ERR_INVALID;
     hipStream_t st = (hipStream_t)stream;
     SRS_HIP(hipSetDevice(ctx->device));
-    SRS_HIP(hipMemcpyAsync(flags, ctx->counters + 64, sizeof(uint32_t), hipMemcpyDeviceToHost, st));
+    SRS_HIP(hipMemcpyAsync(flags, ctx->flags, sizeof(uint32_t), hipMemcpyDeviceToHost, st));
     SRS_HIP(hipStreamSynchronize(st));
-    hipLaunchKernelGGL(fill_u64_kernel, dim3(1), dim3(64), 0, st, (unsigned long long *)(ctx->counters + 64), (uint64_t)1, 0ull);
+    hipLaunchKernelGGL(fill_u64_kernel, dim3(1), dim3(64), 0, st, (unsigned long long *)ctx->flags, (uint64_t)1, 0ull);
     SRS_HIP(hipGetLastError());
     return SRS_OK;
 }
@@ -199,15 +229,18 @@ int srs_extract(srs_ctx *ctx, void *old_snapshot, const void *new_w, uint64_t n,
     const uint64_t ntiles = (nb - 1) * tpb + (last_len + T - 1) / T;
     if (ntiles > 0x7fffffffull) return SRS_ERR_INVALID;
 
+    if (nb > 0x7fffffffull || (uint64_t)ctx->group * tpb > 0x7fffffffull) return SRS_ERR_INVALID;
+
     ExtractArgs a;
     std::memset(&a, 0, sizeof(a));
-    int rc = prepare_extract(ctx, ntiles, st, &a.epoch);
+    int rc = prepare_extract(ctx, ntiles, nb, st, &a.epoch, &a.ticket_stride);
     if (rc != SRS_OK) return rc;
     a.old_w = (uint16_t *)old_snapshot; a.new_w = (const uint16_t *)new_w; a.n = n;
     a.be = (uint32_t)bucket_elems; a.tiles_per_bucket = (uint32_t)tpb;
+    a.nb = (uint32_t)nb; a.last_tiles = (uint32_t)((last_len + T - 1) / T); a.group = ctx->group;
     a.ntiles = (uint32_t)ntiles;
     a.I = I; a.V = V; a.counts = counts; a.cap = cap;
-    a.status = ctx->status; a.ticket = ctx->counters; a.flags = ctx->counters + 64;
+    a.status = ctx->status; a.tickets = ctx->tickets; a.flags = ctx->flags;
     a.spin_limit = ctx->spin_limit;
     return launch_extract<false>(ctx, ctx->tile_elems, a, st);
 }
@@ -230,7 +263,7 @@ int srs_apply(srs_ctx *ctx, void *weights, uint64_t n, uint64_t bucket_elems,
     std::memset(&a, 0, sizeof(a));
     a.w = (uint16_t *)weights; a.n = n; a.be = (uint32_t)bucket_elems; a.nb = (uint32_t)nb;
     a.chunks_per_bucket = (uint32_t)cpb;
-    a.I = I; a.V = V; a.counts = counts; a.cap = cap; a.flags = ctx->counters + 64;
+    a.I = I; a.V = V; a.counts = counts; a.cap = cap; a.flags = ctx->flags;
     hipLaunchKernelGGL((apply_kernel<false>), dim3((uint32_t)(nb * cpb)), dim3(kThreads), 0, st, a);
     SRS_HIP(hipGetLastError());
     return SRS_OK;
@@ -260,12 +293,13 @@ int srs_plan_create(srs_ctx *ctx, const uint64_t *numel, uint32_t ntensors, uint
     // Walk the packed space: a segment is a maximal run of one tensor inside one bucket; a tile is a
     // run of at most tile_elems elements inside one segment.
     std::vector<SegDesc> segs;
-    std::vector<uint32_t> seg_begin;
+    std::vector<uint32_t> seg_begin, bucket_first, wg_bucket;
     std::vector<TileDesc> tiles;
     try {
         seg_begin.assign((size_t)p->nbuckets + 1, 0);
+        bucket_first.assign((size_t)p->nbuckets + 1, 0);
         uint64_t g = 0;                       // packed position of the current tensor's element 0
-        uint32_t cur_bucket = 0xffffffffu, first_tile = 0;
+        uint32_t cur_bucket = 0xffffffffu;
         for (uint32_t k = 0; k < ntensors; ++k) {
             uint64_t off = 0;
             while (off < numel[k]) {
@@ -275,23 +309,35 @@ int srs_plan_create(srs_ctx *ctx, const uint64_t *numel, uint32_t ntensors, uint
                 uint64_t len = numel[k] - off;
                 if (len > bucket_elems - boff) len = bucket_elems - boff;
                 if ((uint32_t)b != cur_bucket) {
-                    if (!tiles.empty()) tiles.back().last = 1;
                     cur_bucket = (uint32_t)b;
-                    first_tile = (uint32_t)tiles.size();
+                    bucket_first[b] = (uint32_t)tiles.size();
                     seg_begin[b] = (uint32_t)segs.size();
                 }
                 segs.push_back(SegDesc{(uint32_t)boff, (uint32_t)len, k, (uint32_t)off});
                 for (uint64_t t = 0; t < len; t += p->tile_elems) {
                     const uint64_t tl = (len - t < p->tile_elems) ? (len - t) : p->tile_elems;
-                    tiles.push_back(TileDesc{k, (uint32_t)(off + t), (uint32_t)b, (uint32_t)(boff + t), (uint32_t)tl,
-                                             first_tile, 0u, 0u});
+                    tiles.push_back(TileDesc{k, (uint32_t)(off + t), (uint32_t)(boff + t), (uint32_t)tl});
                 }
                 off += len;
             }
             g += numel[k];
         }
-        if (!tiles.empty()) tiles.back().last = 1;
         seg_begin[p->nbuckets] = (uint32_t)segs.size();
+        bucket_first[p->nbuckets] = (uint32_t)tiles.size();
+        // workgroup -> bucket: inside each group of `group` buckets, consecutive workgroups rotate
+        // over the buckets that still have tiles left, so every bucket is served exactly once per tile
+        wg_bucket.reserve(tiles.size());
+        std::vector<uint32_t> left;
+        for (uint32_t g0 = 0; g0 < p->nbuckets; g0 += ctx->group) {
+            const uint32_t g1 = (p->nbuckets - g0 < ctx->group) ? p->nbuckets : g0 + ctx->group;
+            left.assign(g1 - g0, 0);
+            uint64_t remaining = 0;
+            for (uint32_t b = g0; b < g1; ++b) { left[b - g0] = bucket_first[b + 1] - bucket_first[b]; remaining += left[b - g0]; }
+            while (remaining) {
+                for (uint32_t b = g0; b < g1; ++b)
+                    if (left[b - g0]) { wg_bucket.push_back(b); --left[b - g0]; --remaining; }
+            }
+        }
         p->h_pairs.assign(ntensors, PtrPair{nullptr, nullptr});
         p->h_wptrs.assign(ntensors, nullptr);
     } catch (const std::bad_alloc &) {
@@ -311,6 +357,8 @@ int srs_plan_create(srs_ctx *ctx, const uint64_t *numel, uint32_t ntensors, uint
     ok = ok && upload((void **)&p->d_tiles, tiles.empty() ? nullptr : tiles.data(), tiles.size() * sizeof(TileDesc));
     ok = ok && upload((void **)&p->d_segs, segs.empty() ? nullptr : segs.data(), segs.size() * sizeof(SegDesc));
     ok = ok && upload((void **)&p->d_seg_begin, seg_begin.data(), seg_begin.size() * sizeof(uint32_t));
+    ok = ok && upload((void **)&p->d_bucket_first, bucket_first.data(), bucket_first.size() * sizeof(uint32_t));
+    ok = ok && upload((void **)&p->d_wg_bucket, wg_bucket.empty() ? nullptr : wg_bucket.data(), wg_bucket.size() * sizeof(uint32_t));
     ok = ok && upload((void **)&p->d_pairs, nullptr, (size_t)ntensors * sizeof(PtrPair));
     ok = ok && upload((void **)&p->d_wptrs, nullptr, (size_t)ntensors * sizeof(uint16_t *));
     ok = ok && hipDeviceSynchronize() == hipSuccess;
@@ -335,6 +383,8 @@ int srs_plan_destroy(srs_plan *p) {
     if (p->d_tiles) (void)hipFree(p->d_tiles);
     if (p->d_segs) (void)hipFree(p->d_segs);
     if (p->d_seg_begin) (void)hipFree(p->d_seg_begin);
+    if (p->d_bucket_first) (void)hipFree(p->d_bucket_first);
+    if (p->d_wg_bucket) (void)hipFree(p->d_wg_bucket);
     if (p->d_pairs) (void)hipFree(p->d_pairs);
     if (p->d_wptrs) (void)hipFree(p->d_wptrs);
     delete p;
@@ -366,11 +416,12 @@ int srs_extract_multi(srs_ctx *ctx, srs_plan *plan, const srs_tensor_pair *t,
 
     ExtractArgs a;
     std::memset(&a, 0, sizeof(a));
-    int rc = prepare_extract(ctx, plan->ntiles, st, &a.epoch);
+    int rc = prepare_extract(ctx, plan->ntiles, plan->nbuckets, st, &a.epoch, &a.ticket_stride);
     if (rc != SRS_OK) return rc;
     a.tiles = plan->d_tiles; a.ptrs = plan->d_pairs; a.ntiles = plan->ntiles;
+    a.wg_bucket = plan->d_wg_bucket; a.bucket_first = plan->d_bucket_first; a.nb = plan->nbuckets;
     a.I = I; a.V = V; a.counts = counts; a.cap = cap;
-    a.status = ctx->status; a.ticket = ctx->counters; a.flags = ctx->counters + 64;
+    a.status = ctx->status; a.tickets = ctx->tickets; a.flags = ctx->flags;
     a.spin_limit = ctx->spin_limit;
     return launch_extract<true>(ctx, plan->tile_elems, a, st);
 }
@@ -402,7 +453,7 @@ int srs_apply_multi(srs_ctx *ctx, srs_plan *plan, const srs_tensor *t,
     std::memset(&a, 0, sizeof(a));
     a.segs = plan->d_segs; a.seg_begin = plan->d_seg_begin; a.wptrs = plan->d_wptrs; a.total = plan->total;
     a.be = (uint32_t)plan->be; a.nb = plan->nbuckets; a.chunks_per_bucket = (uint32_t)cpb;
-    a.I = I; a.V = V; a.counts = counts; a.cap = cap; a.flags = ctx->counters + 64;
+    a.I = I; a.V = V; a.counts = counts; a.cap = cap; a.flags = ctx->flags;
     hipLaunchKernelGGL((apply_kernel<true>), dim3((uint32_t)((uint64_t)plan->nbuckets * cpb)), dim3(kThreads), 0, st, a);
     SRS_HIP(hipGetLastError());
     return SRS_OK;

@@ -1,7 +1,12 @@
 // Device code of the sparse-weight-sync hot path for gfx950 (wave64, 256 CUs in 8 XCDs).
 //
-// extract_kernel: one pass over old/new.  Each workgroup takes one tile (a run of up to
-//   TILE = 2048*V elements that lies inside one tensor and one bucket) in ticket order, streams
+// extract_kernel: one pass over old/new.  Each workgroup is assigned a bucket by its block id
+//   (consecutive block ids rotate over a group of buckets, so that many buckets are in flight at
+//   once) and claims that bucket's next tile with an atomic ticket on the bucket's own counter:
+//   tickets on one address serialise at about 11 ns each on this chip, spread over 32 addresses
+//   they cost nothing.  A tile is a run of up to TILE = 2048*V elements inside one tensor and one
+//   bucket.  Ticket order within a bucket is start order, which is what makes the chained scan
+//   free of deadlock whatever order the hardware dispatches workgroups in.  The workgroup streams
 //   both inputs with 16-byte loads, forms per-lane change masks by XOR of the 16-bit patterns
 //   (Alg. 1: I = { i : W[i] != W_prev[i] }), ranks the changed elements with a packed DPP wave
 //   scan + an LDS combine across the four waves, chains tiles of the same bucket with a
@@ -29,15 +34,11 @@ constexpr uint32_t kStAgg = 1u, kStPrefix = 2u;   // tile status: aggregate only
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
-struct TileDesc {          // one extract tile of a tensor list (32 bytes)
+struct TileDesc {          // one extract tile of a tensor list (16 bytes)
     uint32_t tensor;       // index into the pointer table
     uint32_t tensor_off;   // first element inside the tensor
-    uint32_t bucket;
     uint32_t bucket_off;   // first element inside the bucket
     uint32_t len;          // 1 .. TILE
-    uint32_t first_tile;   // id of the first tile of this bucket
-    uint32_t last;         // 1 if this is the last tile of its bucket
-    uint32_t pad;
 };
 
 struct SegDesc {           // a run of one tensor inside one bucket (16 bytes)
@@ -50,14 +51,18 @@ struct SegDesc {           // a run of one tensor inside one bucket (16 bytes)
 struct PtrPair { uint16_t *old_w; const uint16_t *new_w; };
 
 struct ExtractArgs {
-    // single tensor
+    // single tensor: nb buckets of tiles_per_bucket tiles each, the last one of last_tiles tiles
     uint16_t *old_w; const uint16_t *new_w; uint64_t n; uint32_t be; uint32_t tiles_per_bucket;
+    uint32_t nb; uint32_t last_tiles; uint32_t group;      // group = buckets interleaved per group
     // tensor list
     const TileDesc *tiles; const PtrPair *ptrs;
+    const uint32_t *wg_bucket;      // [ntiles] bucket served by each workgroup
+    const uint32_t *bucket_first;   // [nb+1] id of each bucket's first tile
     uint32_t ntiles;
     int32_t *I; uint16_t *V; uint32_t *counts; uint64_t cap;
-    unsigned long long *status;    // [>= ntiles] {(epoch<<2|flag) : value}
-    uint32_t *ticket;              // [0] next tile id, [32] tiles finished (separate 128-byte lines)
+    unsigned long long *status;     // [>= ntiles] {(epoch<<2|flag) : value}
+    uint32_t *tickets;              // per-bucket ticket counters, ticket_stride words apart, zeroed per launch
+    uint32_t ticket_stride;
     uint32_t *flags;
     uint32_t epoch; uint32_t spin_limit;
 };
@@ -213,30 +218,53 @@ __global__ __launch_bounds__(kThreads) void extract_kernel(const ExtractArgs a) 
     __shared__ uint32_t s_stage[kStage];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    if (tid == 0) s_ticket = __hip_atomic_fetch_add(a.ticket, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+
+    // ---- which bucket this workgroup serves, then claim that bucket's next tile
+    uint32_t bucket, first_tile, bucket_tiles;
+    if (MULTI) {
+        bucket = a.wg_bucket[blockIdx.x];
+        first_tile = a.bucket_first[bucket];
+        bucket_tiles = a.bucket_first[bucket + 1] - first_tile;
+    } else {
+        // groups of `group` buckets; inside a group consecutive workgroups rotate over its buckets.
+        // Only the very last bucket may have fewer tiles: in its group the first last_tiles rounds
+        // rotate over all buckets, the remaining rounds over all but the last.
+        const uint32_t per_group = a.group * a.tiles_per_bucket;
+        const uint32_t g = blockIdx.x / per_group;
+        const uint32_t j = blockIdx.x - g * per_group;
+        const uint32_t g0 = g * a.group;
+        const uint32_t gb = (a.nb - g0 < a.group) ? (a.nb - g0) : a.group;      // buckets in this group
+        const bool has_short = (g0 + gb == a.nb) && (a.last_tiles < a.tiles_per_bucket);
+        uint32_t slot;
+        if (!has_short || j < a.last_tiles * gb) slot = j % gb;
+        else slot = (j - a.last_tiles * gb) % (gb - 1);
+        bucket = g0 + slot;
+        first_tile = bucket * a.tiles_per_bucket;
+        bucket_tiles = (bucket == a.nb - 1) ? a.last_tiles : a.tiles_per_bucket;
+    }
+    if (tid == 0)
+        s_ticket = __hip_atomic_fetch_add(a.tickets + (uint64_t)bucket * a.ticket_stride, 1u, __ATOMIC_RELAXED,
+                                          __HIP_MEMORY_SCOPE_AGENT);
     __syncthreads();
-    const uint32_t tile = uniform(s_ticket);
-    if (tile >= a.ntiles) return;          // cannot happen while the counters are consistent
+    const uint32_t k = uniform(s_ticket);
+    if (k >= bucket_tiles) return;         // cannot happen: each bucket is served by exactly bucket_tiles workgroups
+    const uint32_t tile = first_tile + k;
+    const bool last = (k == bucket_tiles - 1);
 
     // ---- where this tile lives
-    uint32_t bucket, bucket_off, len, first_tile, idx_base;
-    bool last;
+    uint32_t bucket_off, len, idx_base;
     uint16_t *po; const uint16_t *pn;
     if (MULTI) {
         const TileDesc d = a.tiles[tile];
         const PtrPair p = a.ptrs[d.tensor];
         po = p.old_w + d.tensor_off; pn = p.new_w + d.tensor_off;
-        bucket = d.bucket; bucket_off = d.bucket_off; len = d.len; first_tile = d.first_tile; last = d.last != 0;
+        bucket_off = d.bucket_off; len = d.len;
         idx_base = bucket_off;                          // index = position inside the bucket
     } else {
-        bucket = tile / a.tiles_per_bucket;
-        const uint32_t k = tile - bucket * a.tiles_per_bucket;
         const uint64_t b0 = (uint64_t)bucket * a.be;
         const uint32_t blen = (uint32_t)((a.n - b0 < a.be) ? (a.n - b0) : a.be);
         bucket_off = k * TILE;
         len = (blen - bucket_off < TILE) ? (blen - bucket_off) : TILE;
-        first_tile = bucket * a.tiles_per_bucket;
-        last = (bucket_off + len == blen);
         po = a.old_w + b0 + bucket_off; pn = a.new_w + b0 + bucket_off;
         idx_base = (uint32_t)(b0 + bucket_off);         // index = tensor-flat position
     }
@@ -349,21 +377,21 @@ __global__ __launch_bounds__(kThreads) void extract_kernel(const ExtractArgs a) 
         __syncthreads();
     }
 
-    // ---- the last workgroup to finish rewinds the counters for the next launch
-    if (tid == 0) {
-        const uint32_t d = __hip_atomic_fetch_add(a.ticket + 32, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        if (d == a.ntiles - 1) {
-            __hip_atomic_store(a.ticket, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            __hip_atomic_store(a.ticket + 32, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        }
-    }
 }
 
 // ---------------------------------------------------------------------------------------------
-// apply: W[I] <- V
+// apply: W[I] <- V.  One workgroup per (bucket, chunk of kApplyChunk pairs); each thread owns
+// kApplyPer pairs, kThreads apart, so that the index and value loads of a wave are contiguous and
+// all of a thread's loads are in flight before its first store.  For tensor lists the bucket's
+// segment table (start inside the bucket -> byte address of that element) is cached in LDS.
 // ---------------------------------------------------------------------------------------------
+constexpr int kApplyPer = (int)(kApplyChunk / kThreads);
+constexpr uint32_t kSegCache = 128;
+
 template <bool MULTI>
 __global__ __launch_bounds__(kThreads) void apply_kernel(const ApplyArgs a) {
+    __shared__ uint32_t s_off[kSegCache + 1];
+    __shared__ unsigned long long s_base[kSegCache];
     const uint32_t b = blockIdx.x / a.chunks_per_bucket;
     const uint32_t c = blockIdx.x - b * a.chunks_per_bucket;
     if (b >= a.nb) return;
@@ -371,37 +399,76 @@ __global__ __launch_bounds__(kThreads) void apply_kernel(const ApplyArgs a) {
     const uint64_t cnt = ((uint64_t)cnt_true < a.cap) ? cnt_true : a.cap;
     const uint64_t start = (uint64_t)c * kApplyChunk;
     if (start >= cnt) return;
-    const uint64_t end = (start + kApplyChunk < cnt) ? (start + kApplyChunk) : cnt;
-    const int32_t *const Ib = a.I + (uint64_t)b * a.cap;
-    const uint16_t *const Vb = a.V + (uint64_t)b * a.cap;
+    const uint32_t nvalid = (uint32_t)((cnt - start < kApplyChunk) ? (cnt - start) : kApplyChunk);
+    const int32_t *const Ib = a.I + (uint64_t)b * a.cap + start;
+    const uint16_t *const Vb = a.V + (uint64_t)b * a.cap + start;
+
+    int32_t idx[kApplyPer];
+    uint16_t val[kApplyPer];
+#pragma unroll
+    for (int j = 0; j < kApplyPer; ++j) {
+        const uint32_t k = threadIdx.x + j * kThreads;
+        idx[j] = (k < nvalid) ? Ib[k] : 0;
+        val[j] = (k < nvalid) ? Vb[k] : (uint16_t)0;
+    }
+
     bool bad = false;
     if (MULTI) {
         const uint64_t b0 = (uint64_t)b * a.be;
         const uint32_t blen = (uint32_t)((a.total - b0 < a.be) ? (a.total - b0) : a.be);
         const uint32_t s_lo = a.seg_begin[b], s_hi = a.seg_begin[b + 1];
-        for (uint64_t k = start + threadIdx.x; k < end; k += kThreads) {
-            const uint32_t idx = (uint32_t)Ib[k];
-            const uint16_t val = Vb[k];
-            if (idx >= blen) { bad = true; continue; }
-            // last segment of the bucket whose bucket_off <= idx
-            uint32_t lo = s_lo, hi = s_hi;          // invariant: segs[lo].bucket_off <= idx < segs[hi].bucket_off
-            while (hi - lo > 1) {
-                const uint32_t mid = (lo + hi) >> 1;
-                if (a.segs[mid].bucket_off <= idx) lo = mid; else hi = mid;
+        const uint32_t nseg = s_hi - s_lo;
+        const bool cached = nseg <= kSegCache;                 // uniform
+        if (cached) {
+            for (uint32_t s = threadIdx.x; s < nseg; s += kThreads) {
+                const SegDesc d = a.segs[s_lo + s];
+                s_off[s] = d.bucket_off;
+                // byte address of the element at bucket position 0 of this segment's tensor run
+                s_base[s] = (unsigned long long)(uintptr_t)(a.wptrs[d.tensor] + d.tensor_off) - 2ull * d.bucket_off;
             }
-            const SegDesc s = a.segs[lo];
-            const uint32_t off = idx - s.bucket_off;
-            if (off >= s.len) { bad = true; continue; }   // cannot happen for a well-formed plan
-            a.wptrs[s.tensor][(uint64_t)s.tensor_off + off] = val;
+            if (threadIdx.x == 0) s_off[nseg] = blen;
+            __syncthreads();
+        }
+        uint32_t hint = 0;                                      // segment of the previous pair (payloads ascend)
+#pragma unroll
+        for (int j = 0; j < kApplyPer; ++j) {
+            const uint32_t k = threadIdx.x + j * kThreads;
+            if (k >= nvalid) continue;
+            const uint32_t i = (uint32_t)idx[j];
+            if (i >= blen) { bad = true; continue; }
+            if (cached) {
+                uint32_t lo = hint;
+                if (!(s_off[lo] <= i && i < s_off[lo + 1])) {
+                    lo = 0; uint32_t hi = nseg;                 // s_off[lo] <= i < s_off[hi]
+                    while (hi - lo > 1) {
+                        const uint32_t mid = (lo + hi) >> 1;
+                        if (s_off[mid] <= i) lo = mid; else hi = mid;
+                    }
+                    hint = lo;
+                }
+                *reinterpret_cast<uint16_t *>((uintptr_t)(s_base[lo] + 2ull * i)) = val[j];
+            } else {
+                uint32_t lo = s_lo, hi = s_hi;                  // segs[lo].bucket_off <= i < segs[hi].bucket_off
+                while (hi - lo > 1) {
+                    const uint32_t mid = (lo + hi) >> 1;
+                    if (a.segs[mid].bucket_off <= i) lo = mid; else hi = mid;
+                }
+                const SegDesc d = a.segs[lo];
+                const uint32_t off = i - d.bucket_off;
+                if (off >= d.len) { bad = true; continue; }     // cannot happen for a well-formed plan
+                a.wptrs[d.tensor][(uint64_t)d.tensor_off + off] = val[j];
+            }
         }
     } else {
         const uint64_t lo = (uint64_t)b * a.be;
         const uint64_t hi = (lo + a.be < a.n) ? (lo + a.be) : a.n;
-        for (uint64_t k = start + threadIdx.x; k < end; k += kThreads) {
-            const int64_t idx = Ib[k];
-            const uint16_t val = Vb[k];
-            if (idx < (int64_t)lo || idx >= (int64_t)hi) { bad = true; continue; }
-            a.w[idx] = val;
+#pragma unroll
+        for (int j = 0; j < kApplyPer; ++j) {
+            const uint32_t k = threadIdx.x + j * kThreads;
+            if (k >= nvalid) continue;
+            const int64_t i = idx[j];
+            if (i < (int64_t)lo || i >= (int64_t)hi) { bad = true; continue; }
+            a.w[i] = val[j];
         }
     }
     if (bad) atomicOr(a.flags, kFlagBadIndex);
@@ -413,6 +480,12 @@ __global__ __launch_bounds__(kThreads) void apply_kernel(const ApplyArgs a) {
 __global__ void fill_u64_kernel(unsigned long long *p, uint64_t n, unsigned long long v) {
     const uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (i < n) p[i] = v;
+}
+
+// p[i*stride] = 0 for i < n: rewinds the per-bucket ticket counters before a launch
+__global__ void zero_strided_kernel(uint32_t *p, uint64_t n, uint32_t stride) {
+    const uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) p[i * stride] = 0u;
 }
 
 // two-stream read probe with extract's load shape; the XOR-reduction keeps the loads alive

@@ -26,7 +26,7 @@ _lib = C.CDLL(LIB_PATH)
 
 OK, ERR_INVALID, ERR_HIP, ERR_NOMEM, ERR_NO_DEVICE = 0, -1, -2, -3, -4
 FLAG_OVERFLOW, FLAG_BAD_INDEX, FLAG_TIMEOUT = 1, 2, 4
-OPT_SPIN_LIMIT, OPT_TILE_ELEMS, OPT_NONTEMPORAL = 1, 2, 3
+OPT_SPIN_LIMIT, OPT_TILE_ELEMS, OPT_NONTEMPORAL, OPT_INTERLEAVE = 1, 2, 3, 4
 
 EXPORTS = [
     "srs_create", "srs_destroy", "srs_set_option", "srs_strerror", "srs_version", "srs_status",
@@ -112,10 +112,6 @@ class Plan:
         tot, nb, ns, nt = _u64(), C.c_uint32(), C.c_uint32(), C.c_uint32()
         _check(_lib.srs_plan_info(self._h, C.byref(tot), C.byref(nb), C.byref(ns), C.byref(nt)), "srs_plan_info")
         self.total, self.nbuckets, self.nsegments, self.ntiles = tot.value, nb.value, ns.value, nt.value
-        self._pairs = None
-        self._pairs_key = None
-        self._tens = None
-        self._tens_key = None
 
     def close(self) -> None:
         if self._h:
@@ -184,42 +180,47 @@ class Context:
     def plan(self, numel: Sequence[int], bucket_elems: int) -> Plan:
         return Plan(self, numel, bucket_elems)
 
-    def extract_multi(self, plan: Plan, old: Sequence[torch.Tensor], new: Sequence[torch.Tensor], I: torch.Tensor,
-                      V: torch.Tensor, counts: torch.Tensor, cap: int, stream: Optional[torch.cuda.Stream] = None) -> None:
+    def bind_pairs(self, plan: Plan, old: Sequence[torch.Tensor], new: Sequence[torch.Tensor]):
+        """Marshals (old, new) tensor lists into the srs_tensor_pair[] host array once, for callers
+        that repeat the same call (the array can be passed to extract_multi as ``pairs=``)."""
         if len(old) != len(plan.numel) or len(new) != len(plan.numel):
             raise ValueError("tensor list does not match the plan")
-        key = (tuple(t.data_ptr() for t in old), tuple(t.data_ptr() for t in new))
-        if plan._pairs_key != key:
-            for k, (o, w) in enumerate(zip(old, new)):
-                _dev16(o, f"old[{k}]"), _dev16(w, f"new[{k}]")
-                if o.numel() != plan.numel[k] or w.numel() != plan.numel[k]:
-                    raise ValueError(f"tensor {k}: numel differs from the plan")
-            arr = (TensorPair * max(len(old), 1))()
-            for k, (o, w) in enumerate(zip(old, new)):
-                arr[k].old_snapshot, arr[k].new_w = o.data_ptr(), w.data_ptr()
-            plan._pairs, plan._pairs_key = arr, key
-        if cap > 0:
-            _payload_ok(I, V, counts, plan.nbuckets, cap)
-        _check(_lib.srs_extract_multi(self._h, plan._h, plan._pairs, I.data_ptr(), V.data_ptr(), counts.data_ptr(), cap,
-                                      _stream_ptr(stream)), "srs_extract_multi")
+        arr = (TensorPair * max(len(old), 1))()
+        for k, (o, w) in enumerate(zip(old, new)):
+            _dev16(o, f"old[{k}]"), _dev16(w, f"new[{k}]")
+            if o.numel() != plan.numel[k] or w.numel() != plan.numel[k]:
+                raise ValueError(f"tensor {k}: numel differs from the plan")
+            arr[k].old_snapshot, arr[k].new_w = o.data_ptr(), w.data_ptr()
+        return arr
 
-    def apply_multi(self, plan: Plan, weights: Sequence[torch.Tensor], I: torch.Tensor, V: torch.Tensor,
-                    counts: torch.Tensor, cap: int, stream: Optional[torch.cuda.Stream] = None) -> None:
+    def bind_weights(self, plan: Plan, weights: Sequence[torch.Tensor]):
         if len(weights) != len(plan.numel):
             raise ValueError("tensor list does not match the plan")
-        key = tuple(t.data_ptr() for t in weights)
-        if plan._tens_key != key:
-            for k, w in enumerate(weights):
-                _dev16(w, f"weights[{k}]")
-                if w.numel() != plan.numel[k]:
-                    raise ValueError(f"tensor {k}: numel differs from the plan")
-            arr = (Tensor * max(len(weights), 1))()
-            for k, w in enumerate(weights):
-                arr[k].weights = w.data_ptr()
-            plan._tens, plan._tens_key = arr, key
+        arr = (Tensor * max(len(weights), 1))()
+        for k, w in enumerate(weights):
+            _dev16(w, f"weights[{k}]")
+            if w.numel() != plan.numel[k]:
+                raise ValueError(f"tensor {k}: numel differs from the plan")
+            arr[k].weights = w.data_ptr()
+        return arr
+
+    def extract_multi(self, plan: Plan, old: Optional[Sequence[torch.Tensor]], new: Optional[Sequence[torch.Tensor]],
+                      I: torch.Tensor, V: torch.Tensor, counts: torch.Tensor, cap: int,
+                      stream: Optional[torch.cuda.Stream] = None, pairs=None) -> None:
+        if pairs is None:
+            pairs = self.bind_pairs(plan, old, new)
         if cap > 0:
             _payload_ok(I, V, counts, plan.nbuckets, cap)
-        _check(_lib.srs_apply_multi(self._h, plan._h, plan._tens, I.data_ptr(), V.data_ptr(), counts.data_ptr(), cap,
+        _check(_lib.srs_extract_multi(self._h, plan._h, pairs, I.data_ptr(), V.data_ptr(), counts.data_ptr(), cap,
+                                      _stream_ptr(stream)), "srs_extract_multi")
+
+    def apply_multi(self, plan: Plan, weights: Optional[Sequence[torch.Tensor]], I: torch.Tensor, V: torch.Tensor,
+                    counts: torch.Tensor, cap: int, stream: Optional[torch.cuda.Stream] = None, tensors=None) -> None:
+        if tensors is None:
+            tensors = self.bind_weights(plan, weights)
+        if cap > 0:
+            _payload_ok(I, V, counts, plan.nbuckets, cap)
+        _check(_lib.srs_apply_multi(self._h, plan._h, tensors, I.data_ptr(), V.data_ptr(), counts.data_ptr(), cap,
                                     _stream_ptr(stream)), "srs_apply_multi")
 
     # ---- measurement aid ------------------------------------------------------------------
