@@ -59,7 +59,8 @@ typedef enum {
 #define SRS_OPT_SPIN_LIMIT 1   /* max polls of a predecessor tile before SRS_FLAG_TIMEOUT (default 1<<24) */
 #define SRS_OPT_TILE_ELEMS 2   /* elements per extract tile: 4096, 8192, 16384 or 32768 (tuning; affects
                                   plans created afterwards) */
-#define SRS_OPT_NONTEMPORAL 3  /* 1: stream weights with non-temporal loads */
+#define SRS_OPT_REFRESH_GROUP 3 /* snapshot refresh granularity in 16-byte lanes: 0 = element-wise 2-byte stores,
+                                  4 = whole aligned 64 bytes around a change, 8 = 128 bytes (tuning) */
 #define SRS_OPT_INTERLEAVE 4   /* buckets whose tiles are interleaved over consecutive workgroups, 1..4096
                                   (tuning; affects plans created afterwards) */
 

@@ -35,8 +35,9 @@ struct srs_ctx {
     uint32_t epoch = 1;
     uint32_t spin_limit = 1u << 24;
     uint32_t tile_elems = 16384;
-    uint32_t group = 32;                    // buckets whose tiles are interleaved over consecutive workgroups
-    bool nontemporal = false;
+    uint32_t group = 1024;                  // buckets whose tiles are interleaved over consecutive workgroups
+    uint32_t refresh_group = 4;             // lanes (x16 bytes) rewritten around a change by the snapshot refresh
+    bool nontemporal = false;               // read probe only
 };
 
 struct srs_plan {
@@ -114,8 +115,9 @@ int launch_extract(const srs_ctx *ctx, uint32_t tile_elems, const ExtractArgs &a
     const dim3 grid(a.ntiles), block(kThreads);
 #define SRS_LAUNCH(VV)                                                                              \
     do {                                                                                            \
-        if (ctx->nontemporal) hipLaunchKernelGGL((extract_kernel<VV, MULTI, true>), grid, block, 0, st, a);  \
-        else hipLaunchKernelGGL((extract_kernel<VV, MULTI, false>), grid, block, 0, st, a);         \
+        if (ctx->refresh_group == 8) hipLaunchKernelGGL((extract_kernel<VV, MULTI, 8>), grid, block, 0, st, a);       \
+        else if (ctx->refresh_group == 4) hipLaunchKernelGGL((extract_kernel<VV, MULTI, 4>), grid, block, 0, st, a);  \
+        else hipLaunchKernelGGL((extract_kernel<VV, MULTI, 0>), grid, block, 0, st, a);                               \
     } while (0)
     switch (tile_elems) {
         case 4096: SRS_LAUNCH(2); break;
@@ -188,8 +190,9 @@ int srs_set_option(srs_ctx *ctx, int option, uint64_t value) {
         case SRS_OPT_TILE_ELEMS:
             if (!valid_tile_elems(value)) return SRS_ERR_INVALID;
             ctx->tile_elems = (uint32_t)value; return SRS_OK;
-        case SRS_OPT_NONTEMPORAL:
-            ctx->nontemporal = value != 0; return SRS_OK;
+        case SRS_OPT_REFRESH_GROUP:
+            if (value != 0 && value != 4 && value != 8) return SRS_ERR_INVALID;
+            ctx->refresh_group = (uint32_t)value; return SRS_OK;
         case SRS_OPT_INTERLEAVE:
             if (value == 0 || value > 4096) return SRS_ERR_INVALID;
             ctx->group = (uint32_t)value; return SRS_OK;
@@ -229,7 +232,8 @@ int srs_extract(srs_ctx *ctx, void *old_snapshot, const void *new_w, uint64_t n,
     const uint64_t ntiles = (nb - 1) * tpb + (last_len + T - 1) / T;
     if (ntiles > 0x7fffffffull) return SRS_ERR_INVALID;
 
-    if (nb > 0x7fffffffull || (uint64_t)ctx->group * tpb > 0x7fffffffull) return SRS_ERR_INVALID;
+    if (nb > 0x7fffffffull) return SRS_ERR_INVALID;
+    const uint64_t group = ctx->group < nb ? ctx->group : nb;     // group * tpb <= ntiles + tpb
 
     ExtractArgs a;
     std::memset(&a, 0, sizeof(a));
@@ -237,7 +241,7 @@ int srs_extract(srs_ctx *ctx, void *old_snapshot, const void *new_w, uint64_t n,
     if (rc != SRS_OK) return rc;
     a.old_w = (uint16_t *)old_snapshot; a.new_w = (const uint16_t *)new_w; a.n = n;
     a.be = (uint32_t)bucket_elems; a.tiles_per_bucket = (uint32_t)tpb;
-    a.nb = (uint32_t)nb; a.last_tiles = (uint32_t)((last_len + T - 1) / T); a.group = ctx->group;
+    a.nb = (uint32_t)nb; a.last_tiles = (uint32_t)((last_len + T - 1) / T); a.group = (uint32_t)group;
     a.ntiles = (uint32_t)ntiles;
     a.I = I; a.V = V; a.counts = counts; a.cap = cap;
     a.status = ctx->status; a.tickets = ctx->tickets; a.flags = ctx->flags;

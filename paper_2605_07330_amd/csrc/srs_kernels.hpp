@@ -208,8 +208,12 @@ __device__ __forceinline__ uint32_t look_back(const ExtractArgs &a, uint32_t til
 // ---------------------------------------------------------------------------------------------
 // extract
 // ---------------------------------------------------------------------------------------------
-template <int V, bool MULTI, bool NT>
+// RG = lanes per snapshot-refresh group: 0 refreshes element by element (2-byte stores); 4 / 8 rewrite
+// the whole aligned 64 / 128 bytes around a change from the new weights (unchanged elements get the
+// value they already hold), so that the memory system sees full-sector writes instead of masked ones.
+template <int V, bool MULTI, int RG>
 __global__ __launch_bounds__(kThreads) void extract_kernel(const ExtractArgs a) {
+    constexpr bool NT = false;
     static_assert(V % 2 == 0, "counts are scanned in packed pairs");
     constexpr uint32_t TILE = (uint32_t)V * kUnit;
     __shared__ uint32_t s_ticket;
@@ -296,6 +300,17 @@ __global__ __launch_bounds__(kThreads) void extract_kernel(const ExtractArgs a) 
     uint32_t pk[V / 2];
 #pragma unroll
     for (int j = 0; j < V; ++j) m[j] = diff_mask8(xo[j], xn[j]);
+
+    // ---- snapshot refresh of full tiles, RG lanes (RG*16 bytes) at a time
+    const bool group_refresh = (RG > 0) && aligned && len == TILE;      // uniform
+    if (group_refresh) {
+#pragma unroll
+        for (int j = 0; j < V; ++j) {
+            const unsigned long long changed = __ballot(m[j] != 0);
+            const uint32_t grp = (uint32_t)(changed >> (lane & ~(RG > 0 ? RG - 1 : 0))) & ((1u << (RG > 0 ? RG : 1)) - 1u);
+            if (grp) *reinterpret_cast<u32x4 *>(po + e0 + j * 512) = xn[j];
+        }
+    }
 #pragma unroll
     for (int q = 0; q < V / 2; ++q) pk[q] = __popc(m[2 * q]) | (__popc(m[2 * q + 1]) << 16);
 
@@ -371,7 +386,7 @@ __global__ __launch_bounds__(kThreads) void extract_kernel(const ExtractArgs a) 
             const uint64_t r = (uint64_t)excl + r0 + k;
             if (local < len) {                      // always true for a correct scan; keeps stores in bounds
                 if (r < a.cap) { Ib[r] = (int32_t)(idx_base + local); Vb[r] = val; }
-                po[local] = val;                    // snapshot refresh: W_prev <- W at changed positions
+                if (!group_refresh) po[local] = val;    // snapshot refresh: W_prev <- W at changed positions
             }
         }
         __syncthreads();

@@ -16,7 +16,7 @@ from typing import List, Optional, Sequence
 import torch  # loads the HIP runtime that libsrs.so binds to
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libsrs.so")
+LIB_PATH = os.environ.get("SRS_LIBRARY") or os.path.join(_HERE, "libsrs.so")   # override: a build of the same ABI
 
 if not os.path.exists(LIB_PATH):
     raise ImportError(f"{LIB_PATH} is missing: build it with `python -m paper_2605_07330_amd.build` "
@@ -26,7 +26,7 @@ _lib = C.CDLL(LIB_PATH)
 
 OK, ERR_INVALID, ERR_HIP, ERR_NOMEM, ERR_NO_DEVICE = 0, -1, -2, -3, -4
 FLAG_OVERFLOW, FLAG_BAD_INDEX, FLAG_TIMEOUT = 1, 2, 4
-OPT_SPIN_LIMIT, OPT_TILE_ELEMS, OPT_NONTEMPORAL, OPT_INTERLEAVE = 1, 2, 3, 4
+OPT_SPIN_LIMIT, OPT_TILE_ELEMS, OPT_REFRESH_GROUP, OPT_INTERLEAVE = 1, 2, 3, 4
 
 EXPORTS = [
     "srs_create", "srs_destroy", "srs_set_option", "srs_strerror", "srs_version", "srs_status",

@@ -1,0 +1,172 @@
+"""Full-size parity on the benchmark workloads (Qwen3-8B / 30B-A3B / 30B-A3B skewed / 32B shaped),
+in the launch configuration bench.py times.
+
+The oracle cannot redo 30 G elements inside a test, so each workload is checked in two ways:
+  * sampled buckets (first, last, around tensor boundaries, and a seeded random draw) are copied to
+    the host BEFORE the GPU run, extracted and applied by the oracle, and compared element by
+    element with the GPU payload and with the GPU's reconstructed weights for those buckets;
+  * properties that hold at any size are checked over the whole set on the device: the sum of the
+    counts equals the generator's number of changed elements, indices ascend strictly and stay
+    inside their bucket, the snapshot and the rollout copy both equal the new weights bit for bit
+    (the tensor-by-tensor comparison of the paper's Sec. 4.2 protocol), no device flag is raised.
+"""
+import gc
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2605_07330_amd import synth
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def bucket_segments(numels, be, b):
+    """(tensor, offset, length) runs of bucket b of the packed list -- plain bookkeeping."""
+    lo, hi, g, out = b * be, (b + 1) * be, 0, []
+    for k, m in enumerate(numels):
+        s, e = max(g, lo), min(g + m, hi)
+        if s < e:
+            out.append((k, s - g, e - s))
+        g += m
+    return out
+
+
+def sample_buckets(wl, count, seed):
+    nb, be = wl.num_buckets, wl.bucket_elems
+    picks = {0, 1, nb - 2, nb - 1}
+    g = 0
+    for t in wl.tensors[:3] + wl.tensors[-2:]:        # buckets that hold the ends of the largest tensors
+        g0 = g
+        g += t.numel
+        picks.update({g0 // be, (g - 1) // be})
+    # a bucket in the middle of the list, where many small tensors share one bucket (expert weights)
+    picks.add(nb // 2)
+    rng = np.random.default_rng(seed)
+    picks.update(int(x) for x in rng.integers(0, nb, size=max(0, count - len(picks))))
+    return sorted(p for p in picks if 0 <= p < nb)
+
+
+def host_slices(ws, segs):
+    out = []
+    for k, off, ln in segs:
+        t = ws.tensors[k][off:off + ln]
+        out.append(t.view(torch.int16).cpu().numpy().view(np.uint16).copy())
+    return out
+
+
+def check_workload(srs, wl, S, W1, R, nchanged, seed, nsample):
+    numels = S.numels
+    be = wl.bucket_elems
+    ctx = srs.Context(0)
+    try:
+        plan = ctx.plan(numels, be)
+        assert plan.nbuckets == wl.num_buckets and plan.total == wl.numel
+        cap = (synth.payload_capacity(wl) + 7) // 8 * 8
+        I = torch.full((plan.nbuckets, cap), -1, dtype=torch.int32, device=DEV)
+        V = torch.full((plan.nbuckets, cap), -1, dtype=torch.int16, device=DEV)
+        counts = torch.zeros(plan.nbuckets, dtype=torch.int32, device=DEV)
+
+        picks = sample_buckets(wl, nsample, seed)
+        before = {}
+        for b in picks:                                  # host copies taken before the GPU touches anything
+            segs = bucket_segments(numels, be, b)
+            before[b] = (segs, host_slices(S, segs), host_slices(W1, segs))
+        print(f"  {wl.name}: {len(picks)} sampled buckets copied; running extract + apply", flush=True)
+
+        ctx.extract_multi(plan, S.tensors, W1.tensors, I, V, counts, cap)
+        ctx.apply_multi(plan, R.tensors, I, V, counts, cap)
+        flags = ctx.status()
+        assert flags == 0, f"device flags {flags}"
+
+        # ---- whole-set properties
+        c64 = counts.to(torch.int64)
+        assert int(c64.sum().item()) == nchanged
+        assert int(c64.max().item()) <= cap
+        col = torch.arange(cap, device=DEV).unsqueeze(0)
+        live = col < c64.unsqueeze(1)
+        blen = torch.full((plan.nbuckets,), be, dtype=torch.int64, device=DEV)
+        blen[-1] = wl.numel - (plan.nbuckets - 1) * be
+        for lo in range(0, plan.nbuckets, 64):           # in slabs, to bound temporaries
+            hi = min(plan.nbuckets, lo + 64)
+            Ii, lv = I[lo:hi].to(torch.int64), live[lo:hi]
+            assert bool(((Ii >= 0) & (Ii < blen[lo:hi].unsqueeze(1)) | ~lv).all().item()), "index outside its bucket"
+            asc = (Ii[:, 1:] > Ii[:, :-1]) | ~lv[:, 1:]
+            assert bool(asc.all().item()), "indices not strictly ascending"
+            assert bool(((I[lo:hi] == -1) | lv).all().item()), "slot beyond counts was written"
+            del Ii, lv, asc
+        assert S.equal(W1), "snapshot differs from the new weights"
+        assert R.equal(W1), "reconstructed weights differ from the trainer's"
+
+        # ---- sampled buckets against the oracle
+        gc_host = counts.cpu().numpy().view(np.uint32)
+        for b in picks:
+            segs, olds, news = before[b]
+            lens = [ln for _, _, ln in segs]
+            oI, oV, oc, ovf = oracle.extract_multi([o.copy() for o in olds], news, lens, be, cap=cap)
+            assert ovf == 0 and oc.shape == (1,)
+            c = int(oc[0])
+            assert gc_host[b] == c, f"bucket {b}: count {gc_host[b]} != oracle {c}"
+            gI = I[b, :c].cpu().numpy(); gV = V[b, :c].cpu().numpy().view(np.uint16)
+            assert np.array_equal(gI, oI[0, :c]) and np.array_equal(gV, oV[0, :c]), f"bucket {b}: payload differs"
+            roll = [o.copy() for o in olds]
+            assert oracle.apply_multi(roll, lens, be, oI, oV, oc) == oracle.OK
+            got_roll = host_slices(R, segs)
+            for x, y, w in zip(roll, got_roll, news):
+                assert np.array_equal(x, y) and np.array_equal(x, w), f"bucket {b}: reconstruction differs"
+        print(f"  {wl.name}: ok ({nchanged} changed, {len(picks)} buckets matched the oracle)", flush=True)
+        plan.close()
+    finally:
+        ctx.close()
+
+
+def free_all():
+    gc.collect()
+    torch.cuda.empty_cache()
+
+
+@pytest.fixture(scope="module")
+def srs():
+    from paper_2605_07330_amd import srs as m
+    return m
+
+
+@pytest.mark.parametrize("cfg", [1, 2, 3])
+def test_full_size_workload(srs, cfg):
+    print(f"case full-size cfg={cfg}", flush=True)
+    wl = synth.workload(cfg)
+    S = synth.WeightSet(wl, DEV); W1 = synth.WeightSet(wl, DEV); R = synth.WeightSet(wl, DEV)
+    try:
+        synth.fill_base(S, cfg)
+        nchanged, _ = synth.make_update(W1, S, cfg)
+        R.copy_from(S)
+        if cfg == 3:                                      # the skewed set must really have empty buckets
+            assert nchanged < 0.006 * wl.numel
+        check_workload(srs, wl, S, W1, R, nchanged, seed=cfg, nsample=24)
+    finally:
+        del S, W1, R
+        free_all()
+
+
+def test_full_size_qwen3_32b_density_sweep(srs):
+    base = synth.workload(4)
+    S = synth.WeightSet(base, DEV); W1 = synth.WeightSet(base, DEV); R = synth.WeightSet(base, DEV)
+    try:
+        synth.fill_base(S, 4)
+        R.copy_from(S)
+        for step, p in enumerate([0.001, 0.01, 0.1], start=1):
+            print(f"case full-size cfg=4 density={p}", flush=True)
+            wl = synth.workload(4, density=p)
+            S.wl = W1.wl = R.wl = wl
+            # after the previous round S == W1 == R bitwise, so W1 can be rebuilt from S in place
+            nchanged, _ = synth.make_update(W1, S, 4, step=step)
+            sigma = (wl.numel * p * (1 - p)) ** 0.5
+            assert abs(nchanged - wl.numel * p) < 6 * sigma
+            check_workload(srs, wl, S, W1, R, nchanged, seed=40 + step, nsample=12)
+            # payload size against the cost model of Eq. (1)/(2): ratio 1/(3 rho)
+            assert abs((2 * wl.numel) / (6 * nchanged) - 1 / (3 * p)) < 0.01 / (3 * p)
+    finally:
+        del S, W1, R
+        free_all()

@@ -109,6 +109,38 @@ def test_single_tensor_tile_sizes_and_misaligned_bases(srs, tile, offset):
         c.close()
 
 
+@pytest.mark.parametrize("interleave", [1, 3, 1024])
+@pytest.mark.parametrize("rg", [0, 4, 8])
+def test_interleave_and_refresh_granularity_options(srs, interleave, rg):
+    """Every workgroup-to-bucket interleave and every snapshot-refresh granularity gives the same bits."""
+    print(f"case interleave={interleave} rg={rg}", flush=True)
+    c = srs.Context(0)
+    try:
+        c.set_option(srs.OPT_INTERLEAVE, interleave)
+        c.set_option(srs.OPT_REFRESH_GROUP, rg)
+        c.set_option(srs.OPT_TILE_ELEMS, 4096)
+        # single tensor: 11 buckets, the last one short (5 tiles instead of 9)
+        n, be = 10 * 36000 + 17000, 36000
+        old_h, new_h = make_pair(n, 0.03, seed=interleave * 10 + rg)
+        want = oracle.extract(old_h.copy(), new_h, be)[:3]
+        got, snap, roll, flags = run_single(srs, c, old_h, new_h, be)
+        assert flags == 0
+        assert_payload_equal(got, want, "single")
+        assert np.array_equal(snap, new_h) and np.array_equal(roll, new_h)
+        # tensor list
+        wl = synth.workload(2, tiny=True)
+        a = synth.WeightSet(wl, DEV); b = synth.WeightSet(wl, DEV); r = synth.WeightSet(wl, DEV)
+        synth.fill_base(a, 3); synth.make_update(b, a, 3); r.copy_from(a)
+        olds, news = a.to_numpy_u16(), b.to_numpy_u16()
+        want = oracle.extract_multi(olds, news, a.numels, wl.bucket_elems)[:3]
+        got, flags = run_multi(srs, c, wl, a, b, r, wl.bucket_elems)
+        assert flags == 0
+        assert_payload_equal(got, want, "list")
+        assert a.equal(b) and r.equal(b)
+    finally:
+        c.close()
+
+
 def test_bit_pattern_semantics(srs, ctx):
     old_h = np.array([0x0000, 0x7FC0, 0x7FC0, 0x7F80, 0x0001, 0x8000, 0x3F80] * 3, np.uint16)
     new_h = np.array([0x8000, 0x7FC0, 0x7FC1, 0xFF80, 0x0002, 0x8000, 0x3F80] * 3, np.uint16)
