@@ -28,9 +28,10 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0
 
-# HBM traffic per extract launch measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE), scaled by a
-# copy kernel of known size; filled in from profiles/ once measured for the named workload, else None.
-MEASURED_TRAFFIC_BYTES = {}
+# HBM traffic per extract launch measured with rocprofv3 --pmc (FETCH_SIZE x 2.00 + WRITE_SIZE x 1.00, the
+# factors from a 61.06 GB copy in the same runs): profiles/extract_apply_qwen3-30b-a3b.md.  Only the workload
+# that was profiled has a figure.
+MEASURED_TRAFFIC_BYTES = {"qwen3-30b-a3b": 142.8e9}
 
 
 def log(msg: str) -> None:
@@ -101,6 +102,10 @@ def main() -> int:
     ap.add_argument("--cpu-groups", type=int, default=10, help="oracle sample: groups of 16 buckets")
     ap.add_argument("--probe", action="store_true", help="also time the two-stream read probe")
     ap.add_argument("--no-check", action="store_true", help="skip the result checks (kernel experiments only)")
+    ap.add_argument("--regen", action="store_true",
+                    help="keep one new-weights version and rebuild it (untimed) before every step instead of "
+                         "alternating two resident versions: 3 weight sets instead of 4, for workloads that do not "
+                         "fit otherwise; step time is then the sum of the per-step event times")
     args = ap.parse_args()
 
     if args.gpus != 1:
@@ -125,11 +130,18 @@ def main() -> int:
         f"{wl.num_buckets} buckets of {wl.bucket_elems} elements")
 
     t0 = time.perf_counter()
-    W0 = synth.WeightSet(wl, dev); W1 = synth.WeightSet(wl, dev)
-    S = synth.WeightSet(wl, dev); R = synth.WeightSet(wl, dev)
-    synth.fill_base(W0, args.seed)
-    nchanged, _ = synth.make_update(W1, W0, args.seed)
-    S.copy_from(W0); R.copy_from(W0)
+    if args.regen:
+        S = synth.WeightSet(wl, dev); W1 = synth.WeightSet(wl, dev); R = synth.WeightSet(wl, dev)
+        synth.fill_base(S, args.seed)
+        nchanged, _ = synth.make_update(W1, S, args.seed)
+        R.copy_from(S)
+        W0 = W1
+    else:
+        W0 = synth.WeightSet(wl, dev); W1 = synth.WeightSet(wl, dev)
+        S = synth.WeightSet(wl, dev); R = synth.WeightSet(wl, dev)
+        synth.fill_base(W0, args.seed)
+        nchanged, _ = synth.make_update(W1, W0, args.seed)
+        S.copy_from(W0); R.copy_from(W0)
     torch.cuda.synchronize()
     rho = nchanged / N
     log(f"generated in {time.perf_counter() - t0:.1f}s: {nchanged} changed elements (rho = {rho:.5f})")
@@ -167,8 +179,17 @@ def main() -> int:
         if ev:
             ev[2].record()
 
+    def regen(i):
+        # S == W1 bitwise after a step, so the next update can be built from S into W1 in place
+        nonlocal nchanged, rho
+        if i > 0:
+            nchanged, _ = synth.make_update(W1, S, args.seed, step=i + 1)
+            rho = nchanged / N
+
     for i in range(args.warmup):
-        step(i)
+        if args.regen:
+            regen(i)
+        step(0 if args.regen else i)
     torch.cuda.synchronize()
     flags = ctx.status()
     if flags and not args.no_check:
@@ -178,12 +199,14 @@ def main() -> int:
     torch.cuda.synchronize()
     t_start = time.perf_counter()
     for k in range(args.steps):
-        step(args.warmup + k, events[k])
+        if args.regen:
+            regen(args.warmup + k)
+        step(0 if args.regen else args.warmup + k, events[k])
     torch.cuda.synchronize()
     wall = time.perf_counter() - t_start
 
     flags = ctx.status()
-    last_new = versions[(args.warmup + args.steps - 1) % 2] if args.warmup + args.steps else W0
+    last_new = W1 if args.regen else versions[(args.warmup + args.steps - 1) % 2]
     total_counts = int(counts.to(torch.int64).sum().item())
     ok = flags == 0 and total_counts == nchanged and torch.equal(S.flat.view(torch.int16), last_new.flat.view(torch.int16)) \
         and torch.equal(R.flat.view(torch.int16), last_new.flat.view(torch.int16))
@@ -193,7 +216,7 @@ def main() -> int:
     ext_ms = [e[0].elapsed_time(e[1]) for e in events]
     app_ms = [e[1].elapsed_time(e[2]) for e in events]
     ext_avg, app_avg = sum(ext_ms) / len(ext_ms), sum(app_ms) / len(app_ms)
-    ms_per_step = wall * 1e3 / args.steps
+    ms_per_step = (ext_avg + app_avg) if args.regen else wall * 1e3 / args.steps
     bytes_extract = (4.0 + 8.0 * rho) * N          # read old+new; write I(4)+V(2) and snapshot(2) per changed element
     bytes_apply = 8.0 * rho * N                    # read I+V, write 2 per changed element
     value = 4.0 * N / (ms_per_step * 1e-3) / 1e9
@@ -219,7 +242,7 @@ def main() -> int:
         log(f"two-stream read probe: {probe_gbs:.0f} GB/s")
 
     cpu = None
-    if not args.no_cpu_baseline:
+    if not args.no_cpu_baseline and not args.regen:
         import oracle
         # one more (untimed) step in a known direction, then the oracle on a sample of its buckets
         i_next = args.warmup + args.steps

@@ -1,0 +1,122 @@
+// membench -- measurement aid, not part of the method.  Prints the memory-system figures of the box
+// that the extract / apply kernels are designed around:
+//   1. workgroup dispatch rate and the cost of an atomic ticket on 1..64 distinct addresses
+//      (why each bucket has its own ticket counter and buckets are interleaved over workgroups);
+//   2. streaming read and write bandwidth;
+//   3. the cost of writing a sparse subset of 64-byte blocks, as 2-byte stores or as full 64-byte
+//      stores, alone and mixed with a streaming read (what the snapshot refresh and the scatter
+//      apply cost, and why they cost the same whatever the store width: the memory side pays per
+//      128-byte line touched).
+// Everything is in bounds by construction; no input, no arguments.
+#include <hip/hip_runtime.h>
+
+#include <cstdint>
+#include <cstdio>
+
+#define CK(x)                                                                      \
+    do {                                                                           \
+        hipError_t e_ = (x);                                                       \
+        if (e_ != hipSuccess) {                                                    \
+            std::printf("HIP error %s at line %d\n", hipGetErrorString(e_), __LINE__); \
+            return 1;                                                              \
+        }                                                                          \
+    } while (0)
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+__global__ __launch_bounds__(256) void k_empty(uint32_t *out) {
+    if (threadIdx.x == 1000) out[0] = 1;
+}
+
+__global__ __launch_bounds__(256) void k_ticket(uint32_t *ctr, uint32_t addresses, uint32_t *out) {
+    __shared__ uint32_t s;
+    if (threadIdx.x == 0)
+        s = __hip_atomic_fetch_add(ctr + (blockIdx.x % addresses) * 64, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __syncthreads();
+    if (s == 0xffffffffu) out[0] = 1;
+}
+
+// One workgroup per tile of 16384 16-bit elements.  STORE: 0 none, 1 one 2-byte store per chosen
+// 64-byte block, 2 the whole chosen block (4 lanes x 16 bytes), 3 every block (dense).
+// A block is chosen when hash(block) % keep == 0.
+template <int STORE, bool READ>
+__global__ __launch_bounds__(256) void k_mix(uint16_t *dst, const uint16_t *src, uint32_t keep, uint32_t *sink) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const uint64_t tile = (uint64_t)blockIdx.x * 16384;
+    const uint32_t e0 = wave * 4096 + lane * 8;
+    u32x4 acc = {0, 0, 0, 0};
+    if (READ) {
+#pragma unroll
+        for (int j = 0; j < 8; ++j) acc ^= *reinterpret_cast<const u32x4 *>(src + tile + e0 + j * 512);
+    }
+    if (STORE) {
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const uint32_t e = e0 + j * 512;
+            const uint32_t blk = (uint32_t)((tile + e) >> 5);
+            const bool hit = (STORE == 3) || (((blk * 2654435761u) >> 8) % keep == 0);
+            if (STORE == 1) {
+                if (hit && (lane & 3) == ((blk >> 3) & 3)) dst[tile + e + (blk & 7)] = (uint16_t)(blk + acc.x);
+            } else if (hit) {
+                const u32x4 v = {blk, acc.x, acc.y, acc.z};
+                *reinterpret_cast<u32x4 *>(dst + tile + e) = v;
+            }
+        }
+    }
+    if (READ && (acc.x ^ acc.y ^ acc.z ^ acc.w) == 0x12345u) sink[0] = 1;
+}
+
+int main() {
+    const uint64_t N = 8ull << 30;   // elements per buffer (16 GB)
+    const uint32_t nwg = (uint32_t)(N / 16384);
+    uint16_t *dst, *src;
+    uint32_t *sink, *ctr;
+    CK(hipMalloc(&dst, N * 2)); CK(hipMalloc(&src, N * 2)); CK(hipMalloc(&sink, 64)); CK(hipMalloc(&ctr, 64 * 64 * 4));
+    CK(hipMemset(dst, 0, N * 2)); CK(hipMemset(src, 1, N * 2)); CK(hipMemset(ctr, 0, 64 * 64 * 4));
+    hipEvent_t e0, e1;
+    CK(hipEventCreate(&e0)); CK(hipEventCreate(&e1));
+    float ms = 0;
+#define TIME(...)                                                          \
+    for (int rep_ = 0; rep_ < 2; ++rep_) {                                 \
+        CK(hipEventRecord(e0)); __VA_ARGS__; CK(hipEventRecord(e1));       \
+        CK(hipEventSynchronize(e1)); CK(hipEventElapsedTime(&ms, e0, e1)); \
+    }
+
+    std::printf("## dispatch and tickets (2,000,000 workgroups of 256 threads)\n");
+    const uint32_t M = 2000000;
+    TIME(hipLaunchKernelGGL(k_empty, dim3(M), dim3(256), 0, 0, sink));
+    std::printf("empty workgroups: %.3f ms = %.2f ns per workgroup\n", ms, ms * 1e6 / M);
+    for (uint32_t a : {1u, 2u, 4u, 8u, 16u, 32u, 64u}) {
+        TIME(hipLaunchKernelGGL(k_ticket, dim3(M), dim3(256), 0, 0, ctr, a, sink));
+        std::printf("one agent-scope fetch_add per workgroup on %2u address(es): %.3f ms = %.2f ns per ticket\n", a, ms,
+                    ms * 1e6 / M);
+    }
+
+    std::printf("## streaming (16 GB buffers)\n");
+    TIME(hipLaunchKernelGGL((k_mix<0, true>), dim3(nwg), dim3(256), 0, 0, dst, src, 1u, sink));
+    const float t_read = ms;
+    std::printf("read only: %.3f ms = %.0f GB/s\n", ms, N * 2 / (ms * 1e-3) / 1e9);
+    TIME(hipLaunchKernelGGL((k_mix<3, false>), dim3(nwg), dim3(256), 0, 0, dst, src, 1u, sink));
+    std::printf("write only (dense 16-byte stores): %.3f ms = %.0f GB/s\n", ms, N * 2 / (ms * 1e-3) / 1e9);
+    TIME(hipLaunchKernelGGL((k_mix<3, true>), dim3(nwg), dim3(256), 0, 0, dst, src, 1u, sink));
+    std::printf("read + dense write: %.3f ms = %.0f GB/s (both directions)\n", ms, N * 4 / (ms * 1e-3) / 1e9);
+
+    std::printf("## sparse block writes: 1/keep of the 64-byte blocks of a 16 GB buffer\n");
+    std::printf("%-5s %-9s %-10s | %-22s | %-22s | %-26s | %-26s\n", "keep", "blocks", "128B lines", "2B stores alone",
+                "64B stores alone", "2B stores + 16 GB read", "64B stores + 16 GB read");
+    for (uint32_t keep : {2u, 4u, 8u, 16u}) {
+        const double blocks = (double)N / 32 / keep;
+        const double lines = (double)N / 64 * (1.0 - (1.0 - 1.0 / keep) * (1.0 - 1.0 / keep));
+        float t1, t2, t3, t4;
+        TIME(hipLaunchKernelGGL((k_mix<1, false>), dim3(nwg), dim3(256), 0, 0, dst, src, keep, sink)); t1 = ms;
+        TIME(hipLaunchKernelGGL((k_mix<2, false>), dim3(nwg), dim3(256), 0, 0, dst, src, keep, sink)); t2 = ms;
+        TIME(hipLaunchKernelGGL((k_mix<1, true>), dim3(nwg), dim3(256), 0, 0, dst, src, keep, sink)); t3 = ms;
+        TIME(hipLaunchKernelGGL((k_mix<2, true>), dim3(nwg), dim3(256), 0, 0, dst, src, keep, sink)); t4 = ms;
+        std::printf("1/%-3u %6.1f M  %6.1f M   | %6.3f ms %5.1f ps/line | %6.3f ms %5.1f ps/line | +%6.3f ms %5.1f ps/line    | +%6.3f ms %5.1f ps/line\n",
+                    keep, blocks / 1e6, lines / 1e6, t1, t1 * 1e9 / lines, t2, t2 * 1e9 / lines, t3 - t_read,
+                    (t3 - t_read) * 1e9 / lines, t4 - t_read, (t4 - t_read) * 1e9 / lines);
+    }
+    CK(hipDeviceSynchronize());
+    std::printf("done\n");
+    return 0;
+}
