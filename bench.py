@@ -257,6 +257,7 @@ def main() -> int:
                "sample": f"{elems} elements ({elems / N * 100:.1f}% of the workload) in groups of {bpg} buckets spread "
                          f"over the set; oracle extract {te:.2f}s + apply {ta:.2f}s, compute only"}
 
+    default_run = not (args.tiny or args.density or args.tile or args.interleave or args.refresh_group >= 0)
     out = {
         "metric": "extract+apply dense GB/s scanned",
         "value": round(value, 1),
@@ -281,7 +282,7 @@ def main() -> int:
         "read_probe_gbs": None if probe_gbs is None else round(probe_gbs, 1),
         "roofline": {"bound": "hbm", "kernel": "extract_kernel", "achieved": round(ach, 1), "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": round(ach / HBM_PEAK_GBS, 4),
-                     "traffic": MEASURED_TRAFFIC_BYTES.get(wl.name)},
+                     "traffic": MEASURED_TRAFFIC_BYTES.get(wl.name) if default_run else None},
         "cpu_baseline": cpu,
         "checked": not args.no_check,
     }
