@@ -124,6 +124,35 @@ int srs_apply_multi(srs_ctx *ctx, srs_plan *plan, const srs_tensor *t,
                     const int32_t *I, const uint16_t *V, const uint32_t *counts, uint64_t cap, void *stream);
 
 /*
+ * Lossless index coding (Sec. 3.3, "Index delta encoding"): the indices of a payload are sorted, so their
+ * first differences (with a zero prepended) are stored instead; when every difference of a bucket is below
+ * 2^15 they fit 16 bits (b_i = 2 B instead of 4 B), otherwise the bucket keeps its 32-bit indices.
+ *
+ * srs_encode_indices reads an extract payload (I, counts; same layout and cap) and writes, per bucket b,
+ *   D[b*cap + r]   = (pos[r] - pos[r-1]) mod 2^16, pos[-1] = 0, where pos = I - b*base_stride is the position
+ *                    inside the bucket (base_stride = 0 for list payloads, bucket_elems for single-tensor ones),
+ *   max_gap[b]     = the bucket's largest difference (0 if empty): D is exact iff max_gap[b] < 32768,
+ *   anchors[b*nchunk + k] = pos[k*2048] for every started chunk of 2048 pairs, nchunk = ceil(cap/2048)
+ *                    (srs_anchor_count(nbuckets, cap) entries; redundant metadata of 4 B per 2048 pairs that
+ *                    lets the receiver decode chunks independently).
+ * A bucket is then sent as (D, V) at 4 B per pair, or as (I, V) at 6 B per pair when max_gap[b] >= 32768.
+ * Indices that do not ascend raise SRS_FLAG_BAD_INDEX and force that bucket to 32-bit transport.
+ *
+ * srs_apply_encoded / srs_apply_multi_encoded are srs_apply / srs_apply_multi for such payloads: buckets with
+ * max_gap[b] < 32768 are decoded from D (running sums from the chunk's anchor) and scattered in one kernel,
+ * the others are scattered from I_wide (only their slots of I_wide are read).  All arrays are device pointers.
+ */
+uint64_t srs_anchor_count(uint32_t nbuckets, uint64_t cap);
+int srs_encode_indices(srs_ctx *ctx, const int32_t *I, const uint32_t *counts, uint32_t nbuckets, uint64_t cap,
+                       uint64_t base_stride, uint16_t *D, uint32_t *max_gap, int32_t *anchors, void *stream);
+int srs_apply_encoded(srs_ctx *ctx, void *weights, uint64_t n, uint64_t bucket_elems, const uint16_t *D,
+                      const int32_t *I_wide, const uint16_t *V, const uint32_t *counts, const uint32_t *max_gap,
+                      const int32_t *anchors, uint64_t cap, void *stream);
+int srs_apply_multi_encoded(srs_ctx *ctx, srs_plan *plan, const srs_tensor *t, const uint16_t *D,
+                            const int32_t *I_wide, const uint16_t *V, const uint32_t *counts, const uint32_t *max_gap,
+                            const int32_t *anchors, uint64_t cap, void *stream);
+
+/*
  * Measurement aid (not part of the method): reads `bytes` bytes from each of a and b with the same
  * 16-byte streaming loads and launch shape as extract and writes one word per workgroup to `sink`
  * (at least srs_stream_probe_sink_words(bytes) uint32).  Gives the box's achievable two-stream read

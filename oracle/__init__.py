@@ -55,6 +55,12 @@ def _load():
         lib.srs_oracle_apply_multi.restype = C.c_int
         lib.srs_oracle_apply_multi.argtypes = [pp, u64p, C.c_uint32, C.c_uint64, C.c_uint64, C.c_uint64,
                                                i32p, u16p, u32p, C.c_uint64]
+        u16p_ = C.POINTER(C.c_uint16)
+        lib.srs_oracle_encode_indices.restype = C.c_int
+        lib.srs_oracle_encode_indices.argtypes = [i32p, u32p, C.c_uint64, C.c_uint64, C.c_uint64, C.c_uint64,
+                                                  u16p_, u32p, i32p]
+        lib.srs_oracle_decode_indices.restype = C.c_int
+        lib.srs_oracle_decode_indices.argtypes = [u16p_, i32p, u32p, u32p, C.c_uint64, C.c_uint64, C.c_uint64, i32p]
         lib.srs_oracle_num_buckets.restype = C.c_uint64
         lib.srs_oracle_num_buckets.argtypes = [u64p, C.c_uint32, C.c_uint64]
         _lib = lib
@@ -173,3 +179,41 @@ def apply_multi(w: Sequence[np.ndarray | None], numel: Sequence[int], be: int,
     if rc == BAD_ARG:
         raise ValueError("srs_oracle_apply_multi: bad argument")
     return rc
+
+
+ENC_CHUNK = 2048
+
+
+def encode_indices(I: np.ndarray, counts: np.ndarray, base_stride: int = 0, chunk: int = ENC_CHUNK
+                   ) -> Tuple[np.ndarray, np.ndarray, np.ndarray]:
+    """First differences of each bucket's sorted indices (Sec. 3.3).  Returns (D[nb, cap] uint16,
+    max_gap[nb] uint32, anchors[nb, ceil(cap/chunk)] int32); unused slots hold 0xFFFF / -1."""
+    lib = _load()
+    I = np.ascontiguousarray(I, np.int32)
+    counts = np.ascontiguousarray(counts, np.uint32)
+    nb, cap = I.shape
+    D = np.full((nb, cap), 0xFFFF, np.uint16)
+    max_gap = np.zeros(nb, np.uint32)
+    anchors = np.full((nb, (cap + chunk - 1) // chunk), -1, np.int32)
+    rc = lib.srs_oracle_encode_indices(_p(I, C.c_int32), _p(counts, C.c_uint32), nb, cap, base_stride, chunk,
+                                       _p(D, C.c_uint16), _p(max_gap, C.c_uint32), _p(anchors, C.c_int32))
+    if rc != OK:
+        raise ValueError(f"srs_oracle_encode_indices: {rc}")
+    return D, max_gap, anchors
+
+
+def decode_indices(D: np.ndarray, I_wide: np.ndarray, counts: np.ndarray, max_gap: np.ndarray, base_stride: int = 0
+                   ) -> np.ndarray:
+    """Running sums of the differences; buckets with max_gap >= 2^15 are taken from I_wide."""
+    lib = _load()
+    D = np.ascontiguousarray(D, np.uint16)
+    I_wide = np.ascontiguousarray(I_wide, np.int32)
+    counts = np.ascontiguousarray(counts, np.uint32)
+    max_gap = np.ascontiguousarray(max_gap, np.uint32)
+    nb, cap = D.shape
+    out = np.full((nb, cap), -1, np.int32)
+    rc = lib.srs_oracle_decode_indices(_p(D, C.c_uint16), _p(I_wide, C.c_int32), _p(counts, C.c_uint32),
+                                       _p(max_gap, C.c_uint32), nb, cap, base_stride, _p(out, C.c_int32))
+    if rc != OK:
+        raise ValueError(f"srs_oracle_decode_indices: {rc}")
+    return out

@@ -188,3 +188,62 @@ uint64_t srs_oracle_num_buckets(const uint64_t *numel, uint32_t ntensors, uint64
     for (uint32_t k = 0; k < ntensors; ++k) total += numel[k];
     return be ? (total + be - 1) / be : 0;
 }
+
+/* ------------------------------------------------------------------------------------------------
+ * Index delta coding (Sec. 3.3, "Index delta encoding"): because the indices of a payload are sorted,
+ * store the first differences, with a zero prepended, instead of the indices; when every difference
+ * of a payload is below 2^15 the differences fit 16 bits (b_i = 2 B), otherwise the payload keeps its
+ * 32-bit indices.  Here a payload is one bucket.  `base_stride` turns stored indices into positions
+ * inside the bucket first: position = I - b*base_stride (0 for tensor lists, whose indices already are
+ * positions inside the bucket; bucket_elems for single-tensor payloads, whose indices are tensor-flat).
+ *
+ * Outputs per bucket b with c = min(counts[b], cap) pairs:
+ *   D[b*cap + r]   = (pos[r] - pos[r-1]) mod 2^16, pos[-1] = 0            r < c
+ *   max_gap[b]     = max_r (pos[r] - pos[r-1]), 0 for an empty bucket; D is exact iff max_gap < 2^15
+ *   anchors[b*nchunk + k] = pos[k*chunk]   for k*chunk < c   (redundant metadata that lets a decoder
+ *                    start in the middle of a payload; nchunk = ceil(cap/chunk))
+ * ------------------------------------------------------------------------------------------------ */
+int srs_oracle_encode_indices(const int32_t *I, const uint32_t *counts, uint64_t nb, uint64_t cap,
+                              uint64_t base_stride, uint64_t chunk,
+                              uint16_t *D, uint32_t *max_gap, int32_t *anchors)
+{
+    if (cap == 0 || chunk == 0) return SRS_ORACLE_BAD_ARG;
+    uint64_t nchunk = (cap + chunk - 1) / chunk;
+    for (uint64_t b = 0; b < nb; ++b) {
+        uint64_t c = counts[b] < cap ? counts[b] : cap;
+        int64_t prev = 0;
+        uint32_t mg = 0;
+        for (uint64_t r = 0; r < c; ++r) {
+            int64_t pos = (int64_t)I[b * cap + r] - (int64_t)(b * base_stride);
+            int64_t d = pos - prev;
+            if (d < 0 || pos < 0) return SRS_ORACLE_BAD_INDEX;       /* not sorted / below the bucket */
+            D[b * cap + r] = (uint16_t)((uint64_t)d & 0xFFFFu);
+            if ((uint64_t)d > mg) mg = (uint32_t)d;
+            if (r % chunk == 0) anchors[b * nchunk + r / chunk] = (int32_t)pos;
+            prev = pos;
+        }
+        max_gap[b] = mg;
+    }
+    return SRS_ORACLE_OK;
+}
+
+/* Inverse: running sum of the differences (the anchors are not used).  Buckets whose max_gap is 2^15 or
+ * more are not decodable from D and are copied from I_wide instead (the sender ships them as int32). */
+int srs_oracle_decode_indices(const uint16_t *D, const int32_t *I_wide, const uint32_t *counts, const uint32_t *max_gap,
+                              uint64_t nb, uint64_t cap, uint64_t base_stride, int32_t *I_out)
+{
+    if (cap == 0) return SRS_ORACLE_BAD_ARG;
+    for (uint64_t b = 0; b < nb; ++b) {
+        uint64_t c = counts[b] < cap ? counts[b] : cap;
+        if (max_gap[b] >= 32768u) {
+            for (uint64_t r = 0; r < c; ++r) I_out[b * cap + r] = I_wide[b * cap + r];
+            continue;
+        }
+        int64_t pos = 0;
+        for (uint64_t r = 0; r < c; ++r) {
+            pos += D[b * cap + r];
+            I_out[b * cap + r] = (int32_t)(pos + (int64_t)(b * base_stride));
+        }
+    }
+    return SRS_ORACLE_OK;
+}

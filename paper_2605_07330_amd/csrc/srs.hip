@@ -135,6 +135,21 @@ bool valid_tile_elems(uint64_t v) { return v == 4096 || v == 8192 || v == 16384 
 
 }  // namespace
 
+namespace {
+// keeps the device copy of the apply-side pointer table in step with the caller's array
+int upload_weight_pointers(srs_plan *plan, const srs_tensor *t, hipStream_t st) {
+    bool same = plan->wptrs_valid;
+    for (uint32_t k = 0; same && k < plan->ntensors; ++k) same = plan->h_wptrs[k] == (uint16_t *)t[k].weights;
+    if (!same) {
+        for (uint32_t k = 0; k < plan->ntensors; ++k) plan->h_wptrs[k] = (uint16_t *)t[k].weights;
+        plan->wptrs_valid = false;
+        SRS_HIP(hipMemcpyAsync(plan->d_wptrs, plan->h_wptrs.data(), plan->ntensors * sizeof(uint16_t *), hipMemcpyHostToDevice, st));
+        plan->wptrs_valid = true;
+    }
+    return SRS_OK;
+}
+}  // namespace
+
 extern "C" {
 
 int srs_version(void) { return 100; }
@@ -441,14 +456,8 @@ int srs_apply_multi(srs_ctx *ctx, srs_plan *plan, const srs_tensor *t,
     hipStream_t st = (hipStream_t)stream;
     SRS_HIP(hipSetDevice(ctx->device));
 
-    bool same = plan->wptrs_valid;
-    for (uint32_t k = 0; same && k < plan->ntensors; ++k) same = plan->h_wptrs[k] == (uint16_t *)t[k].weights;
-    if (!same) {
-        for (uint32_t k = 0; k < plan->ntensors; ++k) plan->h_wptrs[k] = (uint16_t *)t[k].weights;
-        plan->wptrs_valid = false;
-        SRS_HIP(hipMemcpyAsync(plan->d_wptrs, plan->h_wptrs.data(), plan->ntensors * sizeof(uint16_t *), hipMemcpyHostToDevice, st));
-        plan->wptrs_valid = true;
-    }
+    int rc_up = upload_weight_pointers(plan, t, st);
+    if (rc_up != SRS_OK) return rc_up;
 
     const uint64_t slots = cap < plan->be ? cap : plan->be;
     const uint64_t cpb = (slots + kApplyChunk - 1) / kApplyChunk;
@@ -459,6 +468,100 @@ int srs_apply_multi(srs_ctx *ctx, srs_plan *plan, const srs_tensor *t,
     a.be = (uint32_t)plan->be; a.nb = plan->nbuckets; a.chunks_per_bucket = (uint32_t)cpb;
     a.I = I; a.V = V; a.counts = counts; a.cap = cap; a.flags = ctx->flags;
     hipLaunchKernelGGL((apply_kernel<true>), dim3((uint32_t)((uint64_t)plan->nbuckets * cpb)), dim3(kThreads), 0, st, a);
+    SRS_HIP(hipGetLastError());
+    return SRS_OK;
+}
+
+// ---------------------------------------------------------------------------------------------
+// 16-bit index coding
+// ---------------------------------------------------------------------------------------------
+
+uint64_t srs_anchor_count(uint32_t nbuckets, uint64_t cap) {
+    return (uint64_t)nbuckets * ((cap + kApplyChunk - 1) / kApplyChunk);
+}
+
+int srs_encode_indices(srs_ctx *ctx, const int32_t *I, const uint32_t *counts, uint32_t nbuckets, uint64_t cap,
+                       uint64_t base_stride, uint16_t *D, uint32_t *max_gap, int32_t *anchors, void *stream) {
+    if (!ctx || cap == 0 || base_stride > kMaxIndexable) return SRS_ERR_INVALID;
+    if (nbuckets == 0) return SRS_OK;
+    if (!I || !counts || !D || !max_gap || !anchors) return SRS_ERR_INVALID;
+    if (((uintptr_t)D & 1u) || (((uintptr_t)I | (uintptr_t)counts | (uintptr_t)max_gap | (uintptr_t)anchors) & 3u))
+        return SRS_ERR_INVALID;
+    hipStream_t st = (hipStream_t)stream;
+    SRS_HIP(hipSetDevice(ctx->device));
+    const uint64_t cpb = (cap + kApplyChunk - 1) / kApplyChunk;
+    if ((uint64_t)nbuckets * cpb > 0x7fffffffull) return SRS_ERR_INVALID;
+    hipLaunchKernelGGL(zero_strided_kernel, dim3((nbuckets + 255) / 256), dim3(256), 0, st, max_gap, (uint64_t)nbuckets, 1u);
+    SRS_HIP(hipGetLastError());
+    ApplyArgs a;
+    std::memset(&a, 0, sizeof(a));
+    a.nb = nbuckets; a.chunks_per_bucket = (uint32_t)cpb;
+    a.I = I; a.counts = counts; a.cap = cap; a.flags = ctx->flags; a.base_stride = base_stride;
+    hipLaunchKernelGGL(encode_indices_kernel, dim3((uint32_t)((uint64_t)nbuckets * cpb)), dim3(kThreads), 0, st, a, D,
+                       max_gap, anchors);
+    SRS_HIP(hipGetLastError());
+    return SRS_OK;
+}
+
+namespace {
+bool encoded_args_ok(const uint16_t *D, const int32_t *I_wide, const uint16_t *V, const uint32_t *counts,
+                     const uint32_t *max_gap, const int32_t *anchors) {
+    if (!D || !I_wide || !V || !counts || !max_gap || !anchors) return false;
+    if (((uintptr_t)D | (uintptr_t)V) & 1u) return false;
+    if (((uintptr_t)I_wide | (uintptr_t)counts | (uintptr_t)max_gap | (uintptr_t)anchors) & 3u) return false;
+    return true;
+}
+}  // namespace
+
+int srs_apply_encoded(srs_ctx *ctx, void *weights, uint64_t n, uint64_t bucket_elems, const uint16_t *D,
+                      const int32_t *I_wide, const uint16_t *V, const uint32_t *counts, const uint32_t *max_gap,
+                      const int32_t *anchors, uint64_t cap, void *stream) {
+    if (!ctx || bucket_elems == 0 || cap == 0 || n > kMaxIndexable || bucket_elems > kMaxIndexable) return SRS_ERR_INVALID;
+    if (n == 0) return SRS_OK;
+    if (!weights || ((uintptr_t)weights & 1u) || !encoded_args_ok(D, I_wide, V, counts, max_gap, anchors)) return SRS_ERR_INVALID;
+    hipStream_t st = (hipStream_t)stream;
+    SRS_HIP(hipSetDevice(ctx->device));
+    const uint64_t nb = (n + bucket_elems - 1) / bucket_elems;
+    const uint64_t cpb = (cap + kApplyChunk - 1) / kApplyChunk;       // the anchors' layout
+    if (nb * cpb > 0x7fffffffull) return SRS_ERR_INVALID;
+    ApplyArgs a;
+    std::memset(&a, 0, sizeof(a));
+    a.w = (uint16_t *)weights; a.n = n; a.be = (uint32_t)bucket_elems; a.nb = (uint32_t)nb;
+    a.chunks_per_bucket = (uint32_t)cpb;
+    a.I = I_wide; a.V = V; a.counts = counts; a.cap = cap; a.flags = ctx->flags;
+    a.D = D; a.max_gap = max_gap; a.anchors = anchors; a.base_stride = bucket_elems;
+    const dim3 grid((uint32_t)(nb * cpb));
+    hipLaunchKernelGGL((apply_encoded_kernel<false>), grid, dim3(kThreads), 0, st, a);
+    SRS_HIP(hipGetLastError());
+    hipLaunchKernelGGL((apply_kernel<false>), grid, dim3(kThreads), 0, st, a);      // buckets that kept 32-bit indices
+    SRS_HIP(hipGetLastError());
+    return SRS_OK;
+}
+
+int srs_apply_multi_encoded(srs_ctx *ctx, srs_plan *plan, const srs_tensor *t, const uint16_t *D, const int32_t *I_wide,
+                            const uint16_t *V, const uint32_t *counts, const uint32_t *max_gap, const int32_t *anchors,
+                            uint64_t cap, void *stream) {
+    if (!ctx || !plan || cap == 0 || plan->device != ctx->device) return SRS_ERR_INVALID;
+    if (plan->total == 0) return SRS_OK;
+    if (!t || !encoded_args_ok(D, I_wide, V, counts, max_gap, anchors)) return SRS_ERR_INVALID;
+    for (uint32_t k = 0; k < plan->ntensors; ++k)
+        if ((uintptr_t)t[k].weights & 1u) return SRS_ERR_INVALID;
+    hipStream_t st = (hipStream_t)stream;
+    SRS_HIP(hipSetDevice(ctx->device));
+    int rc = upload_weight_pointers(plan, t, st);
+    if (rc != SRS_OK) return rc;
+    const uint64_t cpb = (cap + kApplyChunk - 1) / kApplyChunk;
+    if ((uint64_t)plan->nbuckets * cpb > 0x7fffffffull) return SRS_ERR_INVALID;
+    ApplyArgs a;
+    std::memset(&a, 0, sizeof(a));
+    a.segs = plan->d_segs; a.seg_begin = plan->d_seg_begin; a.wptrs = plan->d_wptrs; a.total = plan->total;
+    a.be = (uint32_t)plan->be; a.nb = plan->nbuckets; a.chunks_per_bucket = (uint32_t)cpb;
+    a.I = I_wide; a.V = V; a.counts = counts; a.cap = cap; a.flags = ctx->flags;
+    a.D = D; a.max_gap = max_gap; a.anchors = anchors; a.base_stride = 0;
+    const dim3 grid((uint32_t)((uint64_t)plan->nbuckets * cpb));
+    hipLaunchKernelGGL((apply_encoded_kernel<true>), grid, dim3(kThreads), 0, st, a);
+    SRS_HIP(hipGetLastError());
+    hipLaunchKernelGGL((apply_kernel<true>), grid, dim3(kThreads), 0, st, a);
     SRS_HIP(hipGetLastError());
     return SRS_OK;
 }

@@ -75,6 +75,8 @@ struct ApplyArgs {
     uint32_t be; uint32_t nb; uint32_t chunks_per_bucket;
     const int32_t *I; const uint16_t *V; const uint32_t *counts; uint64_t cap;
     uint32_t *flags;
+    // 16-bit index coding (null / 0 when the payload carries 32-bit indices only)
+    const uint16_t *D; const uint32_t *max_gap; const int32_t *anchors; uint64_t base_stride;
 };
 
 // ---------------------------------------------------------------------------------------------
@@ -402,31 +404,34 @@ __global__ __launch_bounds__(kThreads) void extract_kernel(const ExtractArgs a) 
 // ---------------------------------------------------------------------------------------------
 constexpr int kApplyPer = (int)(kApplyChunk / kThreads);
 constexpr uint32_t kSegCache = 128;
+constexpr uint32_t kWideGap = 32768u;      // differences of 2^15 and more do not fit the 16-bit index coding
 
-template <bool MULTI>
-__global__ __launch_bounds__(kThreads) void apply_kernel(const ApplyArgs a) {
-    __shared__ uint32_t s_off[kSegCache + 1];
-    __shared__ unsigned long long s_base[kSegCache];
-    const uint32_t b = blockIdx.x / a.chunks_per_bucket;
+struct ApplyShared {
+    uint32_t off[kSegCache + 1];
+    unsigned long long base[kSegCache];
+    uint32_t wave_total[kWaves];
+};
+
+// Common front of the apply kernels: which (bucket, chunk) this workgroup owns and how many of the
+// chunk's pairs are valid; 0 when there is nothing to do.
+__device__ __forceinline__ uint32_t apply_chunk(const ApplyArgs &a, uint32_t &b, uint64_t &start) {
+    b = blockIdx.x / a.chunks_per_bucket;
     const uint32_t c = blockIdx.x - b * a.chunks_per_bucket;
-    if (b >= a.nb) return;
+    if (b >= a.nb) return 0;
     const uint32_t cnt_true = a.counts[b];
     const uint64_t cnt = ((uint64_t)cnt_true < a.cap) ? cnt_true : a.cap;
-    const uint64_t start = (uint64_t)c * kApplyChunk;
-    if (start >= cnt) return;
-    const uint32_t nvalid = (uint32_t)((cnt - start < kApplyChunk) ? (cnt - start) : kApplyChunk);
-    const int32_t *const Ib = a.I + (uint64_t)b * a.cap + start;
-    const uint16_t *const Vb = a.V + (uint64_t)b * a.cap + start;
+    start = (uint64_t)c * kApplyChunk;
+    if (start >= cnt) return 0;
+    return (uint32_t)((cnt - start < kApplyChunk) ? (cnt - start) : kApplyChunk);
+}
 
-    int32_t idx[kApplyPer];
-    uint16_t val[kApplyPer];
-#pragma unroll
-    for (int j = 0; j < kApplyPer; ++j) {
-        const uint32_t k = threadIdx.x + j * kThreads;
-        idx[j] = (k < nvalid) ? Ib[k] : 0;
-        val[j] = (k < nvalid) ? Vb[k] : (uint16_t)0;
-    }
-
+// Scatter of one thread's kApplyPer pairs of bucket b; pair j is live when bit j of `live` is set.
+// idx holds tensor-flat indices (single tensor) or positions inside the bucket (lists).  For lists the
+// bucket's segment table is cached in LDS (start inside the bucket -> byte address of that element).
+template <bool MULTI>
+__device__ __forceinline__ void scatter_pairs(const ApplyArgs &a, ApplyShared &sh, uint32_t b,
+                                              const int32_t (&idx)[kApplyPer], const uint16_t (&val)[kApplyPer],
+                                              uint32_t live) {
     bool bad = false;
     if (MULTI) {
         const uint64_t b0 = (uint64_t)b * a.be;
@@ -437,31 +442,30 @@ __global__ __launch_bounds__(kThreads) void apply_kernel(const ApplyArgs a) {
         if (cached) {
             for (uint32_t s = threadIdx.x; s < nseg; s += kThreads) {
                 const SegDesc d = a.segs[s_lo + s];
-                s_off[s] = d.bucket_off;
+                sh.off[s] = d.bucket_off;
                 // byte address of the element at bucket position 0 of this segment's tensor run
-                s_base[s] = (unsigned long long)(uintptr_t)(a.wptrs[d.tensor] + d.tensor_off) - 2ull * d.bucket_off;
+                sh.base[s] = (unsigned long long)(uintptr_t)(a.wptrs[d.tensor] + d.tensor_off) - 2ull * d.bucket_off;
             }
-            if (threadIdx.x == 0) s_off[nseg] = blen;
+            if (threadIdx.x == 0) sh.off[nseg] = blen;
             __syncthreads();
         }
         uint32_t hint = 0;                                      // segment of the previous pair (payloads ascend)
 #pragma unroll
         for (int j = 0; j < kApplyPer; ++j) {
-            const uint32_t k = threadIdx.x + j * kThreads;
-            if (k >= nvalid) continue;
+            if (!((live >> j) & 1u)) continue;
             const uint32_t i = (uint32_t)idx[j];
             if (i >= blen) { bad = true; continue; }
             if (cached) {
                 uint32_t lo = hint;
-                if (!(s_off[lo] <= i && i < s_off[lo + 1])) {
-                    lo = 0; uint32_t hi = nseg;                 // s_off[lo] <= i < s_off[hi]
+                if (!(sh.off[lo] <= i && i < sh.off[lo + 1])) {
+                    lo = 0; uint32_t hi = nseg;                 // off[lo] <= i < off[hi]
                     while (hi - lo > 1) {
                         const uint32_t mid = (lo + hi) >> 1;
-                        if (s_off[mid] <= i) lo = mid; else hi = mid;
+                        if (sh.off[mid] <= i) lo = mid; else hi = mid;
                     }
                     hint = lo;
                 }
-                *reinterpret_cast<uint16_t *>((uintptr_t)(s_base[lo] + 2ull * i)) = val[j];
+                *reinterpret_cast<uint16_t *>((uintptr_t)(sh.base[lo] + 2ull * i)) = val[j];
             } else {
                 uint32_t lo = s_lo, hi = s_hi;                  // segs[lo].bucket_off <= i < segs[hi].bucket_off
                 while (hi - lo > 1) {
@@ -479,12 +483,131 @@ __global__ __launch_bounds__(kThreads) void apply_kernel(const ApplyArgs a) {
         const uint64_t hi = (lo + a.be < a.n) ? (lo + a.be) : a.n;
 #pragma unroll
         for (int j = 0; j < kApplyPer; ++j) {
-            const uint32_t k = threadIdx.x + j * kThreads;
-            if (k >= nvalid) continue;
+            if (!((live >> j) & 1u)) continue;
             const int64_t i = idx[j];
             if (i < (int64_t)lo || i >= (int64_t)hi) { bad = true; continue; }
             a.w[i] = val[j];
         }
+    }
+    if (bad) atomicOr(a.flags, kFlagBadIndex);
+}
+
+// 32-bit indices.  When a.max_gap is given, buckets whose indices travel as 16-bit differences are
+// left to apply_encoded_kernel.
+template <bool MULTI>
+__global__ __launch_bounds__(kThreads) void apply_kernel(const ApplyArgs a) {
+    __shared__ ApplyShared sh;
+    uint32_t b; uint64_t start;
+    const uint32_t nvalid = apply_chunk(a, b, start);
+    if (nvalid == 0) return;
+    if (a.max_gap && a.max_gap[b] < kWideGap) return;
+    const int32_t *const Ib = a.I + (uint64_t)b * a.cap + start;
+    const uint16_t *const Vb = a.V + (uint64_t)b * a.cap + start;
+    int32_t idx[kApplyPer];
+    uint16_t val[kApplyPer];
+    uint32_t live = 0;
+#pragma unroll
+    for (int j = 0; j < kApplyPer; ++j) {           // pair k = thread + j*256: contiguous per wave
+        const uint32_t k = threadIdx.x + j * kThreads;
+        const bool ok = k < nvalid;
+        idx[j] = ok ? Ib[k] : 0;
+        val[j] = ok ? Vb[k] : (uint16_t)0;
+        live |= ok ? (1u << j) : 0u;
+    }
+    scatter_pairs<MULTI>(a, sh, b, idx, val, live);
+}
+
+// 16-bit first differences (Sec. 3.3, index delta coding) decoded on the fly: thread t owns the
+// kApplyPer consecutive pairs t*8 .. t*8+7 of the chunk, sums its differences, the workgroup scans the
+// 256 thread sums (DPP wave scan + LDS), and the chunk's anchor (the position of its first pair) turns
+// the running sums into positions inside the bucket.
+template <bool MULTI>
+__global__ __launch_bounds__(kThreads) void apply_encoded_kernel(const ApplyArgs a) {
+    __shared__ ApplyShared sh;
+    uint32_t b; uint64_t start;
+    const uint32_t nvalid = apply_chunk(a, b, start);
+    if (nvalid == 0) return;
+    if (a.max_gap[b] >= kWideGap) return;           // this bucket travels with 32-bit indices
+    const uint16_t *const Db = a.D + (uint64_t)b * a.cap + start;
+    const uint16_t *const Vb = a.V + (uint64_t)b * a.cap + start;
+    const uint32_t k0 = threadIdx.x * kApplyPer;
+    static_assert(kApplyPer == 8, "one 16-byte vector of differences per thread");
+    uint32_t d[kApplyPer];
+    uint16_t val[kApplyPer];
+    uint32_t live = 0;
+    const bool vec = ((((uintptr_t)Db) | ((uintptr_t)Vb)) & 15u) == 0 && k0 + kApplyPer <= nvalid;
+    if (vec) {
+        const u32x4 dv = *reinterpret_cast<const u32x4 *>(Db + k0);
+        const u32x4 vv = *reinterpret_cast<const u32x4 *>(Vb + k0);
+#pragma unroll
+        for (int j = 0; j < kApplyPer; ++j) { d[j] = pattern_at(dv, j); val[j] = (uint16_t)pattern_at(vv, j); }
+        live = 0xFFu;
+    } else {
+#pragma unroll
+        for (int j = 0; j < kApplyPer; ++j) {
+            const bool ok = k0 + j < nvalid;
+            d[j] = ok ? (uint32_t)Db[k0 + j] : 0u;
+            val[j] = ok ? Vb[k0 + j] : (uint16_t)0;
+            live |= ok ? (1u << j) : 0u;
+        }
+    }
+    const uint32_t first = Db[0];                    // the chunk's first difference is covered by the anchor
+    uint32_t run = 0;
+#pragma unroll
+    for (int j = 0; j < kApplyPer; ++j) { run += d[j]; d[j] = run; }      // inclusive inside the thread
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const uint32_t inc = wave_inclusive_scan(run);
+    if (lane == 63) sh.wave_total[wave] = inc;
+    __syncthreads();
+    uint32_t before = inc - run;
+#pragma unroll
+    for (int w = 0; w < kWaves; ++w) before += (w < wave) ? sh.wave_total[w] : 0u;
+    const uint32_t nchunk = a.chunks_per_bucket;
+    const int32_t anchor = a.anchors[(uint64_t)b * nchunk + (uint32_t)(start / kApplyChunk)];
+    const int64_t origin = (int64_t)anchor - (int64_t)first + (int64_t)((uint64_t)b * a.base_stride);
+    int32_t idx[kApplyPer];
+#pragma unroll
+    for (int j = 0; j < kApplyPer; ++j) idx[j] = (int32_t)(origin + (int64_t)before + (int64_t)d[j]);
+    scatter_pairs<MULTI>(a, sh, b, idx, val, live);
+}
+
+// First differences of each bucket's ascending indices, the bucket's largest difference and the
+// anchors (position of the first pair of every chunk of kApplyChunk pairs).  max_gap must be zero on
+// entry.  Indices that do not ascend raise kFlagBadIndex and force the bucket to 32-bit transport.
+__global__ __launch_bounds__(kThreads) void encode_indices_kernel(const ApplyArgs a, uint16_t *D, uint32_t *max_gap,
+                                                                  int32_t *anchors) {
+    __shared__ uint32_t s_gap[kWaves];
+    uint32_t b; uint64_t start;
+    const uint32_t nvalid = apply_chunk(a, b, start);
+    if (nvalid == 0) return;
+    const int32_t *const Ib = a.I + (uint64_t)b * a.cap;
+    const int64_t base = (int64_t)((uint64_t)b * a.base_stride);
+    uint32_t gap = 0;
+    bool bad = false;
+#pragma unroll
+    for (int j = 0; j < kApplyPer; ++j) {
+        const uint32_t k = threadIdx.x + j * kThreads;
+        if (k >= nvalid) continue;
+        const uint64_t r = start + k;
+        const int64_t cur = (int64_t)Ib[r] - base;
+        const int64_t prev = r ? ((int64_t)Ib[r - 1] - base) : 0;
+        int64_t dd = cur - prev;
+        if (dd < 0 || cur < 0) { bad = true; dd = 0xFFFFFFFFll; }
+        D[(uint64_t)b * a.cap + r] = (uint16_t)((uint64_t)dd & 0xFFFFu);
+        gap = ((uint64_t)dd > gap) ? (uint32_t)dd : gap;
+        if (k == 0) anchors[(uint64_t)b * a.chunks_per_bucket + (uint32_t)(start / kApplyChunk)] = (int32_t)cur;
+    }
+    // workgroup maximum: wave maximum by DPP-free shuffles is overkill here; use LDS atomics
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    if (lane == 0) s_gap[wave] = 0;
+    __syncthreads();
+    if (gap) atomicMax(&s_gap[wave], gap);
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        uint32_t g = 0;
+#pragma unroll
+        for (int w = 0; w < kWaves; ++w) g = s_gap[w] > g ? s_gap[w] : g;
+        if (g) atomicMax(max_gap + b, g);
     }
     if (bad) atomicOr(a.flags, kFlagBadIndex);
 }

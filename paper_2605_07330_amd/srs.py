@@ -32,6 +32,7 @@ EXPORTS = [
     "srs_create", "srs_destroy", "srs_set_option", "srs_strerror", "srs_version", "srs_status",
     "srs_extract", "srs_apply", "srs_plan_create", "srs_plan_info", "srs_plan_destroy",
     "srs_extract_multi", "srs_apply_multi", "srs_stream_probe", "srs_stream_probe_sink_words",
+    "srs_anchor_count", "srs_encode_indices", "srs_apply_encoded", "srs_apply_multi_encoded",
 ]
 
 
@@ -61,8 +62,13 @@ _lib.srs_apply_multi.argtypes = [_vp, _vp, C.POINTER(Tensor), _vp, _vp, _vp, _u6
 _lib.srs_stream_probe.argtypes = [_vp, _vp, _vp, _u64, _vp, _vp]
 _lib.srs_stream_probe_sink_words.argtypes = [_u64]
 _lib.srs_stream_probe_sink_words.restype = _u64
+_lib.srs_anchor_count.argtypes = [C.c_uint32, _u64]
+_lib.srs_anchor_count.restype = _u64
+_lib.srs_encode_indices.argtypes = [_vp, _vp, _vp, C.c_uint32, _u64, _u64, _vp, _vp, _vp, _vp]
+_lib.srs_apply_encoded.argtypes = [_vp, _vp, _u64, _u64, _vp, _vp, _vp, _vp, _vp, _vp, _u64, _vp]
+_lib.srs_apply_multi_encoded.argtypes = [_vp, _vp, C.POINTER(Tensor), _vp, _vp, _vp, _vp, _vp, _vp, _u64, _vp]
 for _n in EXPORTS:
-    if _n not in ("srs_strerror", "srs_stream_probe_sink_words"):
+    if _n not in ("srs_strerror", "srs_stream_probe_sink_words", "srs_anchor_count"):
         getattr(_lib, _n).restype = C.c_int
 
 
@@ -98,6 +104,20 @@ def _payload_ok(I: torch.Tensor, V: torch.Tensor, counts: torch.Tensor, nb: int,
         raise TypeError("V: expected contiguous 16-bit GPU tensor of at least nb*cap elements")
     if not (counts.is_cuda and counts.element_size() == 4 and counts.is_contiguous() and counts.numel() >= nb):
         raise TypeError("counts: expected contiguous 32-bit GPU tensor of at least nb elements")
+
+
+def anchor_count(nbuckets: int, cap: int) -> int:
+    return int(_lib.srs_anchor_count(nbuckets, cap))
+
+
+def _encoded_ok(D: torch.Tensor, max_gap: torch.Tensor, anchors: torch.Tensor, nb: int, cap: int) -> None:
+    if not (D.is_cuda and D.element_size() == 2 and D.is_contiguous() and D.numel() >= nb * cap):
+        raise TypeError("D: expected contiguous 16-bit GPU tensor of at least nb*cap elements")
+    if not (max_gap.is_cuda and max_gap.element_size() == 4 and max_gap.is_contiguous() and max_gap.numel() >= nb):
+        raise TypeError("max_gap: expected contiguous 32-bit GPU tensor of at least nb elements")
+    if not (anchors.is_cuda and anchors.dtype == torch.int32 and anchors.is_contiguous()
+            and anchors.numel() >= anchor_count(nb, cap)):
+        raise TypeError("anchors: expected contiguous int32 GPU tensor of srs_anchor_count(nb, cap) elements")
 
 
 class Plan:
@@ -223,6 +243,43 @@ class Context:
         _check(_lib.srs_apply_multi(self._h, plan._h, tensors, I.data_ptr(), V.data_ptr(), counts.data_ptr(), cap,
                                     _stream_ptr(stream)), "srs_apply_multi")
 
+    # ---- 16-bit index coding --------------------------------------------------------------
+    def encode_indices(self, I: torch.Tensor, counts: torch.Tensor, nbuckets: int, cap: int, base_stride: int,
+                       D: torch.Tensor, max_gap: torch.Tensor, anchors: torch.Tensor,
+                       stream: Optional[torch.cuda.Stream] = None) -> None:
+        if cap > 0:
+            _payload_ok(I, D, counts, nbuckets, cap)
+            _encoded_ok(D, max_gap, anchors, nbuckets, cap)
+        _check(_lib.srs_encode_indices(self._h, I.data_ptr(), counts.data_ptr(), nbuckets, cap, base_stride,
+                                       D.data_ptr(), max_gap.data_ptr(), anchors.data_ptr(), _stream_ptr(stream)),
+               "srs_encode_indices")
+
+    def apply_encoded(self, weights: torch.Tensor, bucket_elems: int, D: torch.Tensor, I_wide: torch.Tensor,
+                      V: torch.Tensor, counts: torch.Tensor, max_gap: torch.Tensor, anchors: torch.Tensor, cap: int,
+                      stream: Optional[torch.cuda.Stream] = None) -> None:
+        _dev16(weights, "weights")
+        n = weights.numel()
+        if bucket_elems > 0 and cap > 0:
+            nb = (n + bucket_elems - 1) // bucket_elems
+            _payload_ok(I_wide, V, counts, nb, cap)
+            _encoded_ok(D, max_gap, anchors, nb, cap)
+        _check(_lib.srs_apply_encoded(self._h, weights.data_ptr(), n, bucket_elems, D.data_ptr(), I_wide.data_ptr(),
+                                      V.data_ptr(), counts.data_ptr(), max_gap.data_ptr(), anchors.data_ptr(), cap,
+                                      _stream_ptr(stream)), "srs_apply_encoded")
+
+    def apply_multi_encoded(self, plan: Plan, weights: Optional[Sequence[torch.Tensor]], D: torch.Tensor,
+                            I_wide: torch.Tensor, V: torch.Tensor, counts: torch.Tensor, max_gap: torch.Tensor,
+                            anchors: torch.Tensor, cap: int, stream: Optional[torch.cuda.Stream] = None,
+                            tensors=None) -> None:
+        if tensors is None:
+            tensors = self.bind_weights(plan, weights)
+        if cap > 0:
+            _payload_ok(I_wide, V, counts, plan.nbuckets, cap)
+            _encoded_ok(D, max_gap, anchors, plan.nbuckets, cap)
+        _check(_lib.srs_apply_multi_encoded(self._h, plan._h, tensors, D.data_ptr(), I_wide.data_ptr(), V.data_ptr(),
+                                            counts.data_ptr(), max_gap.data_ptr(), anchors.data_ptr(), cap,
+                                            _stream_ptr(stream)), "srs_apply_multi_encoded")
+
     # ---- measurement aid ------------------------------------------------------------------
     def stream_probe(self, a: torch.Tensor, b: torch.Tensor, sink: torch.Tensor,
                      stream: Optional[torch.cuda.Stream] = None) -> None:
@@ -233,6 +290,14 @@ class Context:
             raise ValueError("sink too small")
         _check(_lib.srs_stream_probe(self._h, a.data_ptr(), b.data_ptr(), nbytes, sink.data_ptr(), _stream_ptr(stream)),
                "srs_stream_probe")
+
+
+def alloc_encoded(nbuckets: int, cap: int, device) -> tuple:
+    """(D, max_gap, anchors) device buffers for srs_encode_indices, filled with 0xFFFF / 0 / -1."""
+    D = torch.full((nbuckets, cap), -1, dtype=torch.int16, device=device)
+    max_gap = torch.zeros(nbuckets, dtype=torch.int32, device=device)
+    anchors = torch.full((max(anchor_count(nbuckets, cap), 1),), -1, dtype=torch.int32, device=device)
+    return D, max_gap, anchors
 
 
 def alloc_payload(nbuckets: int, cap: int, device) -> tuple:

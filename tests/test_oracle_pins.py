@@ -199,7 +199,7 @@ def test_payload_bytes_follow_cost_model_with_paper_numbers():
             payload = 4 * int(counts.sum()) + 2 * int(counts.sum())           # int32 + BF16 per pair
             frac = payload / (2 * n)                                            # of the dense BF16 bytes
             assert abs(full_gb * frac - want_gb) < tol + full_gb * 3 / n
-        else:                                 # label rho X tol src
+        elif len(row) == 5:                   # label rho X tol src
             rho, want_x, tol = map(float, row[1:4])
             k = round(rho * n)
             pos = np.sort(rng.choice(n, size=k, replace=False))
