@@ -102,6 +102,9 @@ def main() -> int:
     ap.add_argument("--cpu-groups", type=int, default=10, help="oracle sample: groups of 16 buckets")
     ap.add_argument("--probe", action="store_true", help="also time the two-stream read probe")
     ap.add_argument("--no-check", action="store_true", help="skip the result checks (kernel experiments only)")
+    ap.add_argument("--index-coding", action="store_true",
+                    help="also run the 16-bit index coding of Sec. 3.3: extract, srs_encode_indices, then "
+                         "srs_apply_multi_encoded instead of srs_apply_multi (not the headline path)")
     ap.add_argument("--regen", action="store_true",
                     help="keep one new-weights version and rebuild it (untimed) before every step instead of "
                          "alternating two resident versions: 3 weight sets instead of 4, for workloads that do not "
@@ -168,14 +171,22 @@ def main() -> int:
     pairs = [ctx.bind_pairs(plans[d], S.tensors, versions[d].tensors) for d in (0, 1)]
     rolls = [ctx.bind_weights(plans[d], R.tensors) for d in (0, 1)]
 
+    if args.index_coding:
+        D, max_gap, anchors = srs.alloc_encoded(plan.nbuckets, cap, dev)
+
     def step(i, ev=None):
         d = i % 2
         if ev:
             ev[0].record()
         ctx.extract_multi(plans[d], None, None, I, V, counts, cap, pairs=pairs[d])
+        if args.index_coding:
+            ctx.encode_indices(I, counts, plan.nbuckets, cap, 0, D, max_gap, anchors)
         if ev:
             ev[1].record()
-        ctx.apply_multi(plans[d], None, I, V, counts, cap, tensors=rolls[d])
+        if args.index_coding:
+            ctx.apply_multi_encoded(plans[d], None, D, I, V, counts, max_gap, anchors, cap, tensors=rolls[d])
+        else:
+            ctx.apply_multi(plans[d], None, I, V, counts, cap, tensors=rolls[d])
         if ev:
             ev[2].record()
 
@@ -257,7 +268,8 @@ def main() -> int:
                "sample": f"{elems} elements ({elems / N * 100:.1f}% of the workload) in groups of {bpg} buckets spread "
                          f"over the set; oracle extract {te:.2f}s + apply {ta:.2f}s, compute only"}
 
-    default_run = not (args.tiny or args.density or args.tile or args.interleave or args.refresh_group >= 0)
+    default_run = not (args.tiny or args.density or args.tile or args.interleave or args.refresh_group >= 0
+                       or args.index_coding)
     out = {
         "metric": "extract+apply dense GB/s scanned",
         "value": round(value, 1),
@@ -272,7 +284,8 @@ def main() -> int:
         "dtype": "u16",
         "data": "synthetic",
         "config": {"workload": wl.name, "elements": N, "buckets": plan.nbuckets, "bucket_elems": wl.bucket_elems,
-                   "changed_fraction": round(rho, 6), "payload_cap": cap, "tile_elems": args.tile or 16384},
+                   "changed_fraction": round(rho, 6), "payload_cap": cap, "tile_elems": args.tile or 16384,
+                   "index_coding": bool(args.index_coding)},
         "sync_ms": round(ms_per_step, 4),
         "extract_ms": round(ext_avg, 4),
         "apply_ms": round(app_avg, 4),

@@ -153,6 +153,31 @@ int srs_apply_multi_encoded(srs_ctx *ctx, srs_plan *plan, const srs_tensor *t, c
                             const int32_t *anchors, uint64_t cap, void *stream);
 
 /*
+ * Density routing (Sec. 3.4, WeightUpdater): parameters that are highly sparse take the (I, V) route, those
+ * that change on nearly every element are sent as a full copy.  The unit here is the bucket and the rule is
+ * the break-even of the cost model, Eq. (1): bucket b of len_b elements goes dense when
+ *     counts[b] > cap      (it overflowed its slot)      or
+ *     counts[b] * bytes_per_pair >= 2 * len_b            (6 B per pair with int32 indices, 4 B with 16-bit
+ *                                                         differences: break-even density 1/3 resp. 1/2).
+ * srs_route reads counts[nbuckets] and writes route_slot[b] (-1 = sparse, else the bucket's place s among the
+ * dense buckets, in bucket order), dense_bucket[s] = b, sparse_counts[b] (= counts[b] for sparse buckets, 0 for
+ * dense ones: pass it to srs_apply* in place of counts and the dense buckets are skipped there) and *n_dense.
+ * At most max_dense buckets go dense; a further candidate stays sparse, truncated to cap, and raises
+ * SRS_FLAG_OVERFLOW.  All pointers are device pointers; one small kernel, asynchronous.
+ *
+ * srs_pack_dense_multi gathers the new weights (t[k].new_w) of the dense buckets into dense[s*bucket_elems ..),
+ * the message body of the full-copy route; srs_unpack_dense_multi writes such bodies into the resident
+ * weights.  Both read dense_bucket and n_dense on the device (max_dense bounds the launch).
+ */
+int srs_route(srs_ctx *ctx, const uint32_t *counts, uint32_t nbuckets, uint64_t bucket_elems, uint64_t total_elems,
+              uint64_t cap, uint32_t bytes_per_pair, uint32_t max_dense, int32_t *route_slot, uint32_t *sparse_counts,
+              int32_t *dense_bucket, uint32_t *n_dense, void *stream);
+int srs_pack_dense_multi(srs_ctx *ctx, srs_plan *plan, const srs_tensor_pair *t, const int32_t *dense_bucket,
+                         const uint32_t *n_dense, uint32_t max_dense, uint16_t *dense, void *stream);
+int srs_unpack_dense_multi(srs_ctx *ctx, srs_plan *plan, const srs_tensor *t, const int32_t *dense_bucket,
+                           const uint32_t *n_dense, uint32_t max_dense, const uint16_t *dense, void *stream);
+
+/*
  * Measurement aid (not part of the method): reads `bytes` bytes from each of a and b with the same
  * 16-byte streaming loads and launch shape as extract and writes one word per workgroup to `sink`
  * (at least srs_stream_probe_sink_words(bytes) uint32).  Gives the box's achievable two-stream read

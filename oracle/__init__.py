@@ -61,6 +61,11 @@ def _load():
                                                   u16p_, u32p, i32p]
         lib.srs_oracle_decode_indices.restype = C.c_int
         lib.srs_oracle_decode_indices.argtypes = [u16p_, i32p, u32p, u32p, C.c_uint64, C.c_uint64, C.c_uint64, i32p]
+        lib.srs_oracle_route.restype = C.c_int
+        lib.srs_oracle_route.argtypes = [u32p, C.c_uint64, C.c_uint64, C.c_uint64, C.c_uint64, C.c_uint32, C.c_uint32,
+                                         i32p, u32p, i32p, u32p]
+        lib.srs_oracle_copy_dense_multi.restype = C.c_int
+        lib.srs_oracle_copy_dense_multi.argtypes = [pp, u64p, C.c_uint32, C.c_uint64, i32p, C.c_uint32, u16p_, C.c_int]
         lib.srs_oracle_num_buckets.restype = C.c_uint64
         lib.srs_oracle_num_buckets.argtypes = [u64p, C.c_uint32, C.c_uint64]
         _lib = lib
@@ -217,3 +222,38 @@ def decode_indices(D: np.ndarray, I_wide: np.ndarray, counts: np.ndarray, max_ga
     if rc != OK:
         raise ValueError(f"srs_oracle_decode_indices: {rc}")
     return out
+
+
+def route(counts: np.ndarray, be: int, total: int, cap: int, bytes_per_pair: int = 6, max_dense: int | None = None
+          ) -> Tuple[np.ndarray, np.ndarray, np.ndarray, int, int]:
+    """Per-bucket sparse / dense decision (Sec. 3.4 routing with the Eq. (1) break-even).
+    Returns (route_slot[nb] int32, sparse_counts[nb] uint32, dense_bucket[max_dense] int32, n_dense, n_dropped)."""
+    lib = _load()
+    counts = np.ascontiguousarray(counts, np.uint32)
+    nb = counts.size
+    max_dense = nb if max_dense is None else max_dense
+    slot = np.full(nb, -9, np.int32)
+    sc = np.zeros(nb, np.uint32)
+    db = np.full(max(max_dense, 1), -1, np.int32)
+    nd = C.c_uint32(0)
+    rc = lib.srs_oracle_route(_p(counts, C.c_uint32), nb, be, total, cap, bytes_per_pair, max_dense,
+                              _p(slot, C.c_int32), _p(sc, C.c_uint32), _p(db, C.c_int32), C.byref(nd))
+    if rc < 0:
+        raise ValueError("srs_oracle_route: bad argument")
+    return slot, sc, db, nd.value, rc
+
+
+def copy_dense_multi(w: Sequence[np.ndarray], numel: Sequence[int], be: int, dense_bucket: np.ndarray, n_dense: int,
+                     dense: np.ndarray, pack: bool) -> None:
+    """pack: dense[s] <- bucket dense_bucket[s] of the list; else the list <- dense[s]."""
+    lib = _load()
+    for a in w:
+        _u16(a, True)
+    ne = np.asarray(list(numel), np.uint64)
+    db = np.ascontiguousarray(dense_bucket, np.int32)
+    if dense.dtype != np.uint16 or not dense.flags.c_contiguous or dense.size < n_dense * be:
+        raise TypeError("dense: contiguous uint16 of at least n_dense*be elements")
+    rc = lib.srs_oracle_copy_dense_multi(_ptr_array(w), _p(ne, C.c_uint64), len(numel), be, _p(db, C.c_int32), n_dense,
+                                         _p(dense, C.c_uint16), int(pack))
+    if rc != OK:
+        raise ValueError("srs_oracle_copy_dense_multi: bad argument")

@@ -247,3 +247,64 @@ int srs_oracle_decode_indices(const uint16_t *D, const int32_t *I_wide, const ui
     }
     return SRS_ORACLE_OK;
 }
+
+/* ------------------------------------------------------------------------------------------------
+ * Density routing (Sec. 3.4, WeightUpdater): a parameter that is highly sparse goes the (I, V) way, one
+ * that changes on nearly every element is sent as a full copy.  The unit here is the bucket, and the rule
+ * is the cost model of Eq. (1): bucket b of len_b elements goes dense when its sparse payload would not
+ * be smaller than its dense bytes, counts[b] * bytes_per_pair >= 2 * len_b (bytes_per_pair = b_i + b_v:
+ * 6 with 32-bit indices, 4 with 16-bit differences), or when it does not fit its slot, counts[b] > cap.
+ *
+ * Outputs: route_slot[b] = -1 for a sparse bucket, else the bucket's place s = 0, 1, ... among the dense
+ * buckets in ascending bucket order; dense_bucket[s] = b; sparse_counts[b] = counts[b] for sparse buckets
+ * and 0 for dense ones (so that a plain apply skips them); *n_dense.  If more than max_dense buckets
+ * qualify, the surplus ones stay sparse with sparse_counts = min(counts, cap) and the return value is the
+ * number of such buckets (their update is then incomplete; the caller must enlarge max_dense).
+ * ------------------------------------------------------------------------------------------------ */
+int srs_oracle_route(const uint32_t *counts, uint64_t nb, uint64_t be, uint64_t total, uint64_t cap,
+                     uint32_t bytes_per_pair, uint32_t max_dense,
+                     int32_t *route_slot, uint32_t *sparse_counts, int32_t *dense_bucket, uint32_t *n_dense)
+{
+    if (be == 0 || cap == 0 || bytes_per_pair == 0) return SRS_ORACLE_BAD_ARG;
+    uint32_t nd = 0;
+    int dropped = 0;
+    for (uint64_t b = 0; b < nb; ++b) {
+        uint64_t lo = b * be;
+        uint64_t len = lo + be < total ? be : (total > lo ? total - lo : 0);
+        int dense = (counts[b] > cap) || ((uint64_t)counts[b] * bytes_per_pair >= 2 * len && counts[b] > 0);
+        if (dense && nd < max_dense) {
+            route_slot[b] = (int32_t)nd;
+            dense_bucket[nd] = (int32_t)b;
+            sparse_counts[b] = 0;
+            nd += 1;
+        } else {
+            if (dense) dropped += 1;
+            route_slot[b] = -1;
+            sparse_counts[b] = counts[b] < cap ? counts[b] : (uint32_t)cap;
+        }
+    }
+    *n_dense = nd;
+    return dropped;
+}
+
+/* The full-copy route for tensor lists: dense[s*be + j] <- packed position dense_bucket[s]*be + j of the
+ * list w (pack != 0), or the other way round (pack == 0), for every j inside the bucket. */
+int srs_oracle_copy_dense_multi(uint16_t *const *w, const uint64_t *numel, uint32_t ntensors, uint64_t be,
+                                const int32_t *dense_bucket, uint32_t n_dense, uint16_t *dense, int pack)
+{
+    if (be == 0) return SRS_ORACLE_BAD_ARG;
+    for (uint32_t s = 0; s < n_dense; ++s) {
+        uint64_t lo = (uint64_t)dense_bucket[s] * be, hi = lo + be;
+        uint64_t g = 0;
+        for (uint32_t k = 0; k < ntensors; ++k) {
+            for (uint64_t j = 0; j < numel[k]; ++j) {
+                uint64_t p = g + j;
+                if (p < lo || p >= hi) continue;
+                if (pack) dense[(uint64_t)s * be + (p - lo)] = w[k][j];
+                else w[k][j] = dense[(uint64_t)s * be + (p - lo)];
+            }
+            g += numel[k];
+        }
+    }
+    return SRS_ORACLE_OK;
+}

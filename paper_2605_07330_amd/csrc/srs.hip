@@ -44,6 +44,7 @@ struct srs_plan {
     int device = 0;
     uint64_t total = 0, be = 0;
     uint32_t ntensors = 0, nbuckets = 0, nsegments = 0, ntiles = 0, tile_elems = 0;
+    uint32_t max_bucket_tiles = 0;          // most tiles in any one bucket
     TileDesc *d_tiles = nullptr;
     uint32_t *d_wg_bucket = nullptr;        // [ntiles] bucket served by each workgroup of extract
     uint32_t *d_bucket_first = nullptr;     // [nbuckets+1] first tile of each bucket
@@ -136,6 +137,21 @@ bool valid_tile_elems(uint64_t v) { return v == 4096 || v == 8192 || v == 16384 
 }  // namespace
 
 namespace {
+// keeps the device copy of the extract-side pointer table in step with the caller's array
+int upload_pair_pointers(srs_plan *plan, const srs_tensor_pair *t, hipStream_t st) {
+    bool same = plan->pairs_valid;
+    for (uint32_t k = 0; same && k < plan->ntensors; ++k)
+        same = plan->h_pairs[k].old_w == (uint16_t *)t[k].old_snapshot && plan->h_pairs[k].new_w == (const uint16_t *)t[k].new_w;
+    if (!same) {
+        for (uint32_t k = 0; k < plan->ntensors; ++k)
+            plan->h_pairs[k] = PtrPair{(uint16_t *)t[k].old_snapshot, (const uint16_t *)t[k].new_w};
+        plan->pairs_valid = false;
+        SRS_HIP(hipMemcpyAsync(plan->d_pairs, plan->h_pairs.data(), plan->ntensors * sizeof(PtrPair), hipMemcpyHostToDevice, st));
+        plan->pairs_valid = true;
+    }
+    return SRS_OK;
+}
+
 // keeps the device copy of the apply-side pointer table in step with the caller's array
 int upload_weight_pointers(srs_plan *plan, const srs_tensor *t, hipStream_t st) {
     bool same = plan->wptrs_valid;
@@ -147,6 +163,34 @@ int upload_weight_pointers(srs_plan *plan, const srs_tensor *t, hipStream_t st) 
         plan->wptrs_valid = true;
     }
     return SRS_OK;
+}
+}  // namespace
+
+namespace {
+template <bool PACK>
+int launch_dense_copy(srs_ctx *ctx, srs_plan *plan, const int32_t *dense_bucket, const uint32_t *n_dense,
+                      uint32_t max_dense, uint16_t *dense, hipStream_t st) {
+    if (max_dense == 0 || plan->max_bucket_tiles == 0) return SRS_OK;
+    if ((uint64_t)max_dense * plan->max_bucket_tiles > 0x7fffffffull) return SRS_ERR_INVALID;
+    DenseCopyArgs a;
+    std::memset(&a, 0, sizeof(a));
+    a.tiles = plan->d_tiles; a.bucket_first = plan->d_bucket_first; a.pairs = plan->d_pairs; a.wptrs = plan->d_wptrs;
+    a.dense_bucket = dense_bucket; a.n_dense = n_dense; a.max_dense = max_dense;
+    a.tiles_per_bucket_max = plan->max_bucket_tiles; a.be = plan->be; a.dense = dense;
+    hipLaunchKernelGGL((dense_copy_kernel<PACK>), dim3(max_dense * plan->max_bucket_tiles), dim3(kThreads), 0, st, a);
+    SRS_HIP(hipGetLastError());
+    (void)ctx;
+    return SRS_OK;
+}
+}  // namespace
+
+namespace {
+bool encoded_args_ok(const uint16_t *D, const int32_t *I_wide, const uint16_t *V, const uint32_t *counts,
+                     const uint32_t *max_gap, const int32_t *anchors) {
+    if (!D || !I_wide || !V || !counts || !max_gap || !anchors) return false;
+    if (((uintptr_t)D | (uintptr_t)V) & 1u) return false;
+    if (((uintptr_t)I_wide | (uintptr_t)counts | (uintptr_t)max_gap | (uintptr_t)anchors) & 3u) return false;
+    return true;
 }
 }  // namespace
 
@@ -343,6 +387,8 @@ int srs_plan_create(srs_ctx *ctx, const uint64_t *numel, uint32_t ntensors, uint
         }
         seg_begin[p->nbuckets] = (uint32_t)segs.size();
         bucket_first[p->nbuckets] = (uint32_t)tiles.size();
+        for (uint32_t b = 0; b < p->nbuckets; ++b)
+            if (bucket_first[b + 1] - bucket_first[b] > p->max_bucket_tiles) p->max_bucket_tiles = bucket_first[b + 1] - bucket_first[b];
         // workgroup -> bucket: inside each group of `group` buckets, consecutive workgroups rotate
         // over the buckets that still have tiles left, so every bucket is served exactly once per tile
         wg_bucket.reserve(tiles.size());
@@ -422,16 +468,8 @@ int srs_extract_multi(srs_ctx *ctx, srs_plan *plan, const srs_tensor_pair *t,
     hipStream_t st = (hipStream_t)stream;
     SRS_HIP(hipSetDevice(ctx->device));
 
-    bool same = plan->pairs_valid;
-    for (uint32_t k = 0; same && k < plan->ntensors; ++k)
-        same = plan->h_pairs[k].old_w == (uint16_t *)t[k].old_snapshot && plan->h_pairs[k].new_w == (const uint16_t *)t[k].new_w;
-    if (!same) {
-        for (uint32_t k = 0; k < plan->ntensors; ++k)
-            plan->h_pairs[k] = PtrPair{(uint16_t *)t[k].old_snapshot, (const uint16_t *)t[k].new_w};
-        plan->pairs_valid = false;
-        SRS_HIP(hipMemcpyAsync(plan->d_pairs, plan->h_pairs.data(), plan->ntensors * sizeof(PtrPair), hipMemcpyHostToDevice, st));
-        plan->pairs_valid = true;
-    }
+    int rc_up = upload_pair_pointers(plan, t, st);
+    if (rc_up != SRS_OK) return rc_up;
 
     ExtractArgs a;
     std::memset(&a, 0, sizeof(a));
@@ -503,16 +541,6 @@ int srs_encode_indices(srs_ctx *ctx, const int32_t *I, const uint32_t *counts, u
     return SRS_OK;
 }
 
-namespace {
-bool encoded_args_ok(const uint16_t *D, const int32_t *I_wide, const uint16_t *V, const uint32_t *counts,
-                     const uint32_t *max_gap, const int32_t *anchors) {
-    if (!D || !I_wide || !V || !counts || !max_gap || !anchors) return false;
-    if (((uintptr_t)D | (uintptr_t)V) & 1u) return false;
-    if (((uintptr_t)I_wide | (uintptr_t)counts | (uintptr_t)max_gap | (uintptr_t)anchors) & 3u) return false;
-    return true;
-}
-}  // namespace
-
 int srs_apply_encoded(srs_ctx *ctx, void *weights, uint64_t n, uint64_t bucket_elems, const uint16_t *D,
                       const int32_t *I_wide, const uint16_t *V, const uint32_t *counts, const uint32_t *max_gap,
                       const int32_t *anchors, uint64_t cap, void *stream) {
@@ -564,6 +592,58 @@ int srs_apply_multi_encoded(srs_ctx *ctx, srs_plan *plan, const srs_tensor *t, c
     hipLaunchKernelGGL((apply_kernel<true>), grid, dim3(kThreads), 0, st, a);
     SRS_HIP(hipGetLastError());
     return SRS_OK;
+}
+
+// ---------------------------------------------------------------------------------------------
+// density routing and the dense (full-copy) route
+// ---------------------------------------------------------------------------------------------
+
+int srs_route(srs_ctx *ctx, const uint32_t *counts, uint32_t nbuckets, uint64_t bucket_elems, uint64_t total_elems,
+              uint64_t cap, uint32_t bytes_per_pair, uint32_t max_dense, int32_t *route_slot, uint32_t *sparse_counts,
+              int32_t *dense_bucket, uint32_t *n_dense, void *stream) {
+    if (!ctx || bucket_elems == 0 || cap == 0 || bytes_per_pair == 0) return SRS_ERR_INVALID;
+    if (!n_dense || ((uintptr_t)n_dense & 3u)) return SRS_ERR_INVALID;
+    if (nbuckets && (!counts || !route_slot || !sparse_counts || (!dense_bucket && max_dense))) return SRS_ERR_INVALID;
+    if (((uintptr_t)counts | (uintptr_t)route_slot | (uintptr_t)sparse_counts | (uintptr_t)dense_bucket) & 3u) return SRS_ERR_INVALID;
+    hipStream_t st = (hipStream_t)stream;
+    SRS_HIP(hipSetDevice(ctx->device));
+    RouteArgs a;
+    std::memset(&a, 0, sizeof(a));
+    a.counts = counts; a.nb = nbuckets; a.be = bucket_elems; a.total = total_elems; a.cap = cap;
+    a.bytes_per_pair = bytes_per_pair; a.max_dense = max_dense;
+    a.route_slot = route_slot; a.sparse_counts = sparse_counts; a.dense_bucket = dense_bucket; a.n_dense = n_dense;
+    a.flags = ctx->flags;
+    hipLaunchKernelGGL(route_kernel, dim3(1), dim3(kThreads), 0, st, a);
+    SRS_HIP(hipGetLastError());
+    return SRS_OK;
+}
+
+int srs_pack_dense_multi(srs_ctx *ctx, srs_plan *plan, const srs_tensor_pair *t, const int32_t *dense_bucket,
+                         const uint32_t *n_dense, uint32_t max_dense, uint16_t *dense, void *stream) {
+    if (!ctx || !plan || plan->device != ctx->device) return SRS_ERR_INVALID;
+    if (plan->total == 0 || max_dense == 0) return SRS_OK;
+    if (!t || !dense_bucket || !n_dense || !dense || ((uintptr_t)dense & 1u)) return SRS_ERR_INVALID;
+    for (uint32_t k = 0; k < plan->ntensors; ++k)
+        if (((uintptr_t)t[k].old_snapshot | (uintptr_t)t[k].new_w) & 1u) return SRS_ERR_INVALID;
+    hipStream_t st = (hipStream_t)stream;
+    SRS_HIP(hipSetDevice(ctx->device));
+    int rc = upload_pair_pointers(plan, t, st);
+    if (rc != SRS_OK) return rc;
+    return launch_dense_copy<true>(ctx, plan, dense_bucket, n_dense, max_dense, dense, st);
+}
+
+int srs_unpack_dense_multi(srs_ctx *ctx, srs_plan *plan, const srs_tensor *t, const int32_t *dense_bucket,
+                           const uint32_t *n_dense, uint32_t max_dense, const uint16_t *dense, void *stream) {
+    if (!ctx || !plan || plan->device != ctx->device) return SRS_ERR_INVALID;
+    if (plan->total == 0 || max_dense == 0) return SRS_OK;
+    if (!t || !dense_bucket || !n_dense || !dense || ((uintptr_t)dense & 1u)) return SRS_ERR_INVALID;
+    for (uint32_t k = 0; k < plan->ntensors; ++k)
+        if ((uintptr_t)t[k].weights & 1u) return SRS_ERR_INVALID;
+    hipStream_t st = (hipStream_t)stream;
+    SRS_HIP(hipSetDevice(ctx->device));
+    int rc = upload_weight_pointers(plan, t, st);
+    if (rc != SRS_OK) return rc;
+    return launch_dense_copy<false>(ctx, plan, dense_bucket, n_dense, max_dense, const_cast<uint16_t *>(dense), st);
 }
 
 // ---------------------------------------------------------------------------------------------

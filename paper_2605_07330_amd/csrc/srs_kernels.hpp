@@ -613,6 +613,90 @@ __global__ __launch_bounds__(kThreads) void encode_indices_kernel(const ApplyArg
 }
 
 // ---------------------------------------------------------------------------------------------
+// density routing (Sec. 3.4): buckets whose sparse payload would not be smaller than their dense bytes,
+// or that overflowed their slot, travel as a full copy.
+// ---------------------------------------------------------------------------------------------
+struct RouteArgs {
+    const uint32_t *counts; uint32_t nb; uint64_t be; uint64_t total; uint64_t cap;
+    uint32_t bytes_per_pair; uint32_t max_dense;
+    int32_t *route_slot; uint32_t *sparse_counts; int32_t *dense_bucket; uint32_t *n_dense;
+    uint32_t *flags;
+};
+
+// One workgroup walks the buckets 256 at a time, so that dense slots are handed out in bucket order.
+__global__ __launch_bounds__(kThreads) void route_kernel(const RouteArgs a) {
+    __shared__ uint32_t s_wave[kWaves];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    uint32_t taken = 0;                                 // dense buckets before this round (uniform)
+    bool dropped = false;
+    for (uint32_t b0 = 0; b0 < a.nb; b0 += kThreads) {
+        const uint32_t b = b0 + threadIdx.x;
+        bool dense = false;
+        uint32_t cnt = 0;
+        if (b < a.nb) {
+            cnt = a.counts[b];
+            const uint64_t lo = (uint64_t)b * a.be;
+            const uint64_t len = (lo + a.be < a.total) ? a.be : (a.total > lo ? a.total - lo : 0);
+            dense = ((uint64_t)cnt > a.cap) || (cnt > 0 && (uint64_t)cnt * a.bytes_per_pair >= 2 * len);
+        }
+        const unsigned long long mask = __ballot(dense);
+        const uint32_t in_wave = __builtin_popcountll(mask & ((1ull << lane) - 1ull));
+        if (lane == 0) s_wave[wave] = (uint32_t)__builtin_popcountll(mask);
+        __syncthreads();
+        uint32_t before = taken, round_total = 0;
+#pragma unroll
+        for (int w = 0; w < kWaves; ++w) { before += (w < wave) ? s_wave[w] : 0u; round_total += s_wave[w]; }
+        __syncthreads();
+        if (b < a.nb) {
+            const uint32_t slot = before + in_wave;
+            if (dense && slot < a.max_dense) {
+                a.route_slot[b] = (int32_t)slot; a.dense_bucket[slot] = (int32_t)b; a.sparse_counts[b] = 0;
+            } else {
+                if (dense) dropped = true;
+                a.route_slot[b] = -1;
+                a.sparse_counts[b] = ((uint64_t)cnt < a.cap) ? cnt : (uint32_t)a.cap;
+            }
+        }
+        taken += round_total;
+    }
+    if (threadIdx.x == 0) *a.n_dense = (taken < a.max_dense) ? taken : a.max_dense;
+    if (dropped) atomicOr(a.flags, kFlagOverflow);
+}
+
+struct DenseCopyArgs {
+    const TileDesc *tiles; const uint32_t *bucket_first; const PtrPair *pairs; uint16_t *const *wptrs;
+    const int32_t *dense_bucket; const uint32_t *n_dense; uint32_t max_dense; uint32_t tiles_per_bucket_max;
+    uint64_t be; uint16_t *dense;
+};
+
+// PACK: dense[s] <- the new weights of bucket dense_bucket[s];  !PACK: resident weights <- dense[s].
+// One workgroup per (dense slot, tile of the bucket), tiles as in extract's plan.
+template <bool PACK>
+__global__ __launch_bounds__(kThreads) void dense_copy_kernel(const DenseCopyArgs a) {
+    const uint32_t s = blockIdx.x / a.tiles_per_bucket_max;
+    const uint32_t j = blockIdx.x - s * a.tiles_per_bucket_max;
+    if (s >= a.max_dense || s >= *a.n_dense) return;
+    const uint32_t b = (uint32_t)a.dense_bucket[s];
+    const uint32_t first = a.bucket_first[b];
+    if (j >= a.bucket_first[b + 1] - first) return;
+    const TileDesc d = a.tiles[first + j];
+    uint16_t *const slot = a.dense + (uint64_t)s * a.be + d.bucket_off;
+    uint16_t *const w = PACK ? const_cast<uint16_t *>(a.pairs[d.tensor].new_w) + d.tensor_off
+                             : a.wptrs[d.tensor] + d.tensor_off;
+    uint16_t *const dst = PACK ? slot : w;
+    const uint16_t *const src = PACK ? w : slot;
+    const bool aligned = ((((uintptr_t)dst) | ((uintptr_t)src)) & 15u) == 0;
+    if (aligned) {
+        const uint32_t nvec = d.len / 8;
+        for (uint32_t v = threadIdx.x; v < nvec; v += kThreads)
+            reinterpret_cast<u32x4 *>(dst)[v] = reinterpret_cast<const u32x4 *>(src)[v];
+        for (uint32_t e = nvec * 8 + threadIdx.x; e < d.len; e += kThreads) dst[e] = src[e];
+    } else {
+        for (uint32_t e = threadIdx.x; e < d.len; e += kThreads) dst[e] = src[e];
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
 // small utilities
 // ---------------------------------------------------------------------------------------------
 __global__ void fill_u64_kernel(unsigned long long *p, uint64_t n, unsigned long long v) {

@@ -33,6 +33,7 @@ EXPORTS = [
     "srs_extract", "srs_apply", "srs_plan_create", "srs_plan_info", "srs_plan_destroy",
     "srs_extract_multi", "srs_apply_multi", "srs_stream_probe", "srs_stream_probe_sink_words",
     "srs_anchor_count", "srs_encode_indices", "srs_apply_encoded", "srs_apply_multi_encoded",
+    "srs_route", "srs_pack_dense_multi", "srs_unpack_dense_multi",
 ]
 
 
@@ -67,6 +68,9 @@ _lib.srs_anchor_count.restype = _u64
 _lib.srs_encode_indices.argtypes = [_vp, _vp, _vp, C.c_uint32, _u64, _u64, _vp, _vp, _vp, _vp]
 _lib.srs_apply_encoded.argtypes = [_vp, _vp, _u64, _u64, _vp, _vp, _vp, _vp, _vp, _vp, _u64, _vp]
 _lib.srs_apply_multi_encoded.argtypes = [_vp, _vp, C.POINTER(Tensor), _vp, _vp, _vp, _vp, _vp, _vp, _u64, _vp]
+_lib.srs_route.argtypes = [_vp, _vp, C.c_uint32, _u64, _u64, _u64, C.c_uint32, C.c_uint32, _vp, _vp, _vp, _vp, _vp]
+_lib.srs_pack_dense_multi.argtypes = [_vp, _vp, C.POINTER(TensorPair), _vp, _vp, C.c_uint32, _vp, _vp]
+_lib.srs_unpack_dense_multi.argtypes = [_vp, _vp, C.POINTER(Tensor), _vp, _vp, C.c_uint32, _vp, _vp]
 for _n in EXPORTS:
     if _n not in ("srs_strerror", "srs_stream_probe_sink_words", "srs_anchor_count"):
         getattr(_lib, _n).restype = C.c_int
@@ -279,6 +283,47 @@ class Context:
         _check(_lib.srs_apply_multi_encoded(self._h, plan._h, tensors, D.data_ptr(), I_wide.data_ptr(), V.data_ptr(),
                                             counts.data_ptr(), max_gap.data_ptr(), anchors.data_ptr(), cap,
                                             _stream_ptr(stream)), "srs_apply_multi_encoded")
+
+    # ---- density routing and the dense route ----------------------------------------------
+    def route(self, counts: torch.Tensor, nbuckets: int, bucket_elems: int, total_elems: int, cap: int,
+              bytes_per_pair: int, max_dense: int, route_slot: torch.Tensor, sparse_counts: torch.Tensor,
+              dense_bucket: torch.Tensor, n_dense: torch.Tensor, stream: Optional[torch.cuda.Stream] = None) -> None:
+        for name, t, need in (("counts", counts, nbuckets), ("route_slot", route_slot, nbuckets),
+                              ("sparse_counts", sparse_counts, nbuckets), ("dense_bucket", dense_bucket, max_dense),
+                              ("n_dense", n_dense, 1)):
+            if not (t.is_cuda and t.element_size() == 4 and t.is_contiguous() and t.numel() >= need):
+                raise TypeError(f"{name}: expected contiguous 32-bit GPU tensor of at least {need} elements")
+        _check(_lib.srs_route(self._h, counts.data_ptr(), nbuckets, bucket_elems, total_elems, cap, bytes_per_pair,
+                              max_dense, route_slot.data_ptr(), sparse_counts.data_ptr(), dense_bucket.data_ptr(),
+                              n_dense.data_ptr(), _stream_ptr(stream)), "srs_route")
+
+    @staticmethod
+    def _dense_ok(plan: Plan, dense_bucket: torch.Tensor, n_dense: torch.Tensor, max_dense: int, dense: torch.Tensor):
+        if not (dense.is_cuda and dense.element_size() == 2 and dense.is_contiguous()
+                and dense.numel() >= max_dense * plan.bucket_elems):
+            raise TypeError("dense: expected contiguous 16-bit GPU tensor of max_dense*bucket_elems elements")
+        if not (dense_bucket.is_cuda and dense_bucket.element_size() == 4 and dense_bucket.numel() >= max_dense):
+            raise TypeError("dense_bucket: expected 32-bit GPU tensor of max_dense elements")
+        if not (n_dense.is_cuda and n_dense.element_size() == 4 and n_dense.numel() >= 1):
+            raise TypeError("n_dense: expected 32-bit GPU tensor")
+
+    def pack_dense_multi(self, plan: Plan, old: Optional[Sequence[torch.Tensor]], new: Optional[Sequence[torch.Tensor]],
+                         dense_bucket: torch.Tensor, n_dense: torch.Tensor, max_dense: int, dense: torch.Tensor,
+                         stream: Optional[torch.cuda.Stream] = None, pairs=None) -> None:
+        if pairs is None:
+            pairs = self.bind_pairs(plan, old, new)
+        self._dense_ok(plan, dense_bucket, n_dense, max_dense, dense)
+        _check(_lib.srs_pack_dense_multi(self._h, plan._h, pairs, dense_bucket.data_ptr(), n_dense.data_ptr(), max_dense,
+                                         dense.data_ptr(), _stream_ptr(stream)), "srs_pack_dense_multi")
+
+    def unpack_dense_multi(self, plan: Plan, weights: Optional[Sequence[torch.Tensor]], dense_bucket: torch.Tensor,
+                           n_dense: torch.Tensor, max_dense: int, dense: torch.Tensor,
+                           stream: Optional[torch.cuda.Stream] = None, tensors=None) -> None:
+        if tensors is None:
+            tensors = self.bind_weights(plan, weights)
+        self._dense_ok(plan, dense_bucket, n_dense, max_dense, dense)
+        _check(_lib.srs_unpack_dense_multi(self._h, plan._h, tensors, dense_bucket.data_ptr(), n_dense.data_ptr(),
+                                           max_dense, dense.data_ptr(), _stream_ptr(stream)), "srs_unpack_dense_multi")
 
     # ---- measurement aid ------------------------------------------------------------------
     def stream_probe(self, a: torch.Tensor, b: torch.Tensor, sink: torch.Tensor,
