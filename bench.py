@@ -86,6 +86,69 @@ def cpu_baseline_and_check(torch, np, oracle, wl, old_ws, new_ws, payload, bucke
     return t_extract, t_apply, elems, len(starts) * buckets_per_group
 
 
+def bench_cast(args, torch, srs, synth, wl, dev) -> int:
+    """Fused cast + diff: W (BF16 model parameters) <- round(master FP32), payload out, then apply to the
+    rollout copy.  Before every step the master weights are rebuilt (untimed) from a fresh sparse update of W."""
+    N = wl.numel
+    W = synth.WeightSet(wl, dev); R = synth.WeightSet(wl, dev)
+    master = torch.empty(N, dtype=torch.float32, device=dev)
+    masters, off = [], 0
+    for t in wl.tensors:
+        masters.append(master[off:off + t.numel]); off += t.numel
+    synth.fill_base(W, args.seed)
+    R.copy_from(W)
+    ctx = srs.Context(0)
+    if args.tile:
+        ctx.set_option(srs.OPT_TILE_ELEMS, args.tile)
+    plan = ctx.plan(W.numels, wl.bucket_elems)
+    cap = (synth.payload_capacity(wl) + 7) // 8 * 8
+    I = torch.empty((plan.nbuckets, cap), dtype=torch.int32, device=dev)
+    V = torch.empty((plan.nbuckets, cap), dtype=torch.int16, device=dev)
+    counts = torch.zeros(plan.nbuckets, dtype=torch.int32, device=dev)
+    pairs = ctx.bind_cast_pairs(plan, W.tensors, masters)
+    rolls = ctx.bind_weights(plan, R.tensors)
+    chunk = 1 << 26
+    ext, app, rho = [], [], 0.0
+    for i in range(args.warmup + args.steps):
+        changed = 0
+        for c, lo in enumerate(range(0, N, chunk)):        # master <- weights that round to an updated W, chunk by chunk
+            hi = min(N, lo + chunk)
+            new = torch.empty(hi - lo, dtype=torch.bfloat16, device=dev)
+            n_c, _ = synth.iid_update_(new, W.flat[lo:hi], wl.density, args.seed, salt=(i + 1) * 100003 + c)
+            changed += n_c
+            synth.master_from_(master[lo:hi], new, args.seed, salt=(i + 1) * 100003 + c)
+        rho = changed / N
+        e = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+        e[0].record()
+        ctx.extract_cast_multi(plan, None, None, I, V, counts, cap, pairs=pairs)
+        e[1].record()
+        ctx.apply_multi(plan, None, I, V, counts, cap, tensors=rolls)
+        e[2].record()
+        torch.cuda.synchronize()
+        flags = ctx.status()
+        total = int(counts.to(torch.int64).sum().item())
+        if flags or total != changed or not torch.equal(R.flat.view(torch.int16), W.flat.view(torch.int16)):
+            raise SystemExit(f"bench self-check failed (cast): flags={flags} counts={total} expected={changed}")
+        if i >= args.warmup:
+            ext.append(e[0].elapsed_time(e[1])); app.append(e[1].elapsed_time(e[2]))
+    ext_avg, app_avg = sum(ext) / len(ext), sum(app) / len(app)
+    bytes_extract = (6.0 + 8.0 * rho) * N          # read 4 (master) + 2 (parameters); write payload 6 rho + parameters 2 rho
+    ach = bytes_extract / (ext_avg * 1e-3) / 1e9
+    log(f"cast+diff extract {ext_avg:.3f} ms (min {min(ext):.3f}), apply {app_avg:.3f} ms; "
+        f"{ach:.0f} GB/s = {100 * ach / HBM_PEAK_GBS:.1f}% of peak on (6 + 8 rho) N bytes")
+    out = {"metric": "fused cast+diff extract + apply, dense GB/s scanned", "value": round(6.0 * N / ((ext_avg + app_avg) * 1e-3) / 1e9, 1),
+           "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ext_avg + app_avg, 4),
+           "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "u16", "data": "synthetic",
+           "config": {"workload": wl.name + "+fp32-master", "elements": N, "changed_fraction": round(rho, 6)},
+           "extract_ms": round(ext_avg, 4), "apply_ms": round(app_avg, 4),
+           "roofline": {"bound": "hbm", "kernel": "extract_kernel<cast>", "achieved": round(ach, 1), "peak": HBM_PEAK_GBS,
+                        "unit": "GB/s", "frac": round(ach / HBM_PEAK_GBS, 4), "traffic": None},
+           "cpu_baseline": None}
+    print(json.dumps(out), flush=True)
+    plan.close(); ctx.close()
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -105,6 +168,10 @@ def main() -> int:
     ap.add_argument("--index-coding", action="store_true",
                     help="also run the 16-bit index coding of Sec. 3.3: extract, srs_encode_indices, then "
                          "srs_apply_multi_encoded instead of srs_apply_multi (not the headline path)")
+    ap.add_argument("--cast", action="store_true",
+                    help="time the fused cast + diff instead (srs_extract_cast_multi on FP32 master weights that are "
+                         "rebuilt, untimed, before every step; implies 3 resident sets: master, model parameters, "
+                         "rollout copy) -- not the headline path")
     ap.add_argument("--regen", action="store_true",
                     help="keep one new-weights version and rebuild it (untimed) before every step instead of "
                          "alternating two resident versions: 3 weight sets instead of 4, for workloads that do not "
@@ -131,6 +198,9 @@ def main() -> int:
     N = wl.numel
     log(f"workload {wl.name}: {len(wl.tensors)} tensors, {N} elements ({2 * N / 1e9:.2f} GB), "
         f"{wl.num_buckets} buckets of {wl.bucket_elems} elements")
+
+    if args.cast:
+        return bench_cast(args, torch, srs, synth, wl, dev)
 
     t0 = time.perf_counter()
     if args.regen:

@@ -124,6 +124,23 @@ int srs_apply_multi(srs_ctx *ctx, srs_plan *plan, const srs_tensor *t,
                     const int32_t *I, const uint16_t *V, const uint32_t *counts, uint64_t cap, void *stream);
 
 /*
+ * Fused cast + diff.  The Trainer's hook sits where the FP32 master weights are cast and copied into the BF16
+ * model parameters (Alg. 1: CastAndCopy, then I_t = { i : W[i] != W_prev[i] }; Sec. 3.4 "Trainer").  These
+ * calls do both at once, so that no snapshot W_prev exists: for every element r = round_BF16(master[i]);
+ * if r differs bitwise from weights[i] the pair (i, r) is emitted; weights[i] <- r.  `weights` holds the old
+ * model parameters on entry and the new ones on completion; the payload is exactly what srs_extract(old =
+ * weights before, new = round_BF16(master)) would give, with the same layout, capacity rule and flags.
+ * round_BF16 rounds the binary32 value to the nearest BF16, ties to even; a NaN becomes 0x7FC0.
+ * master: device pointer(s) to FP32 data, 4-byte aligned (16-byte alignment of both buffers takes the vector
+ * path).  In the list form t[k].old_snapshot is tensor k's BF16 model parameters and t[k].new_w its FP32
+ * master weights.
+ */
+int srs_extract_cast(srs_ctx *ctx, void *weights, const float *master, uint64_t n, uint64_t bucket_elems,
+                     int32_t *I, uint16_t *V, uint32_t *counts, uint64_t cap, void *stream);
+int srs_extract_cast_multi(srs_ctx *ctx, srs_plan *plan, const srs_tensor_pair *t,
+                           int32_t *I, uint16_t *V, uint32_t *counts, uint64_t cap, void *stream);
+
+/*
  * Lossless index coding (Sec. 3.3, "Index delta encoding"): the indices of a payload are sorted, so their
  * first differences (with a zero prepended) are stored instead; when every difference of a bucket is below
  * 2^15 they fit 16 bits (b_i = 2 B instead of 4 B), otherwise the bucket keeps its 32-bit indices.

@@ -66,6 +66,13 @@ def _load():
                                          i32p, u32p, i32p, u32p]
         lib.srs_oracle_copy_dense_multi.restype = C.c_int
         lib.srs_oracle_copy_dense_multi.argtypes = [pp, u64p, C.c_uint32, C.c_uint64, i32p, C.c_uint32, u16p_, C.c_int]
+        lib.srs_oracle_round_bf16_array.restype = None
+        lib.srs_oracle_round_bf16_array.argtypes = [u32p, C.c_uint64, u16p_]
+        lib.srs_oracle_extract_cast.restype = C.c_int
+        lib.srs_oracle_extract_cast.argtypes = [u16p_, u32p, C.c_uint64, C.c_uint64, i32p, u16p_, u32p, C.c_uint64]
+        lib.srs_oracle_extract_cast_multi.restype = C.c_int
+        lib.srs_oracle_extract_cast_multi.argtypes = [pp, C.POINTER(u32p), u64p, C.c_uint32, C.c_uint64,
+                                                      i32p, u16p_, u32p, C.c_uint64]
         lib.srs_oracle_num_buckets.restype = C.c_uint64
         lib.srs_oracle_num_buckets.argtypes = [u64p, C.c_uint32, C.c_uint64]
         _lib = lib
@@ -257,3 +264,61 @@ def copy_dense_multi(w: Sequence[np.ndarray], numel: Sequence[int], be: int, den
                                          _p(dense, C.c_uint16), int(pack))
     if rc != OK:
         raise ValueError("srs_oracle_copy_dense_multi: bad argument")
+
+
+def _f32bits(a: np.ndarray) -> np.ndarray:
+    if not isinstance(a, np.ndarray) or a.dtype not in (np.float32, np.uint32) or a.ndim != 1 or not a.flags.c_contiguous:
+        raise TypeError("master weights: 1-D contiguous float32 (or their uint32 bit patterns)")
+    return a.view(np.uint32)
+
+
+def round_bf16(master: np.ndarray) -> np.ndarray:
+    """Round-to-nearest-even binary32 -> BF16 bit patterns (NaN -> 0x7FC0)."""
+    lib = _load()
+    m = _f32bits(master)
+    out = np.empty(m.size, np.uint16)
+    lib.srs_oracle_round_bf16_array(_p(m, C.c_uint32), m.size, _p(out, C.c_uint16))
+    return out
+
+
+def extract_cast(w: np.ndarray, master: np.ndarray, be: int, cap: int | None = None
+                 ) -> Tuple[np.ndarray, np.ndarray, np.ndarray, int]:
+    """Fused cast + diff of Alg. 1 on one tensor: w (BF16 patterns, in/out) <- round_bf16(master)."""
+    lib = _load()
+    _u16(w, True)
+    m = _f32bits(master)
+    if m.size != w.size:
+        raise ValueError("size mismatch")
+    cap = be if cap is None else cap
+    nb = num_buckets(w.size, be) if be else 0
+    I = np.full((nb, max(cap, 0)), -1, np.int32)
+    V = np.full((nb, max(cap, 0)), 0xFFFF, np.uint16)
+    counts = np.zeros(nb, np.uint32)
+    rc = lib.srs_oracle_extract_cast(_p(w, C.c_uint16), _p(m, C.c_uint32), w.size, be, _p(I, C.c_int32),
+                                     _p(V, C.c_uint16), _p(counts, C.c_uint32), cap)
+    if rc < 0:
+        raise ValueError(f"srs_oracle_extract_cast: bad argument ({rc})")
+    return I, V, counts, rc
+
+
+def extract_cast_multi(w: Sequence[np.ndarray], master: Sequence[np.ndarray], numel: Sequence[int], be: int,
+                       cap: int | None = None) -> Tuple[np.ndarray, np.ndarray, np.ndarray, int]:
+    lib = _load()
+    for a in w:
+        _u16(a, True)
+    ms = [_f32bits(a) for a in master]
+    ne = np.asarray(list(numel), np.uint64)
+    nb = num_buckets(int(ne.sum()), be) if be else 0
+    cap = be if cap is None else cap
+    I = np.full((nb, max(cap, 0)), -1, np.int32)
+    V = np.full((nb, max(cap, 0)), 0xFFFF, np.uint16)
+    counts = np.zeros(nb, np.uint32)
+    T = C.POINTER(C.c_uint32)
+    mp = (T * max(len(ms), 1))()
+    for k, a in enumerate(ms):
+        mp[k] = _p(a, C.c_uint32)
+    rc = lib.srs_oracle_extract_cast_multi(_ptr_array(w), mp, _p(ne, C.c_uint64), len(numel), be, _p(I, C.c_int32),
+                                           _p(V, C.c_uint16), _p(counts, C.c_uint32), cap)
+    if rc < 0:
+        raise ValueError(f"srs_oracle_extract_cast_multi: bad argument ({rc})")
+    return I, V, counts, rc

@@ -308,3 +308,87 @@ int srs_oracle_copy_dense_multi(uint16_t *const *w, const uint64_t *numel, uint3
     }
     return SRS_ORACLE_OK;
 }
+
+/* ------------------------------------------------------------------------------------------------
+ * Fused cast + diff: the Trainer's hook sits where the FP32 master weights are cast and copied into the
+ * BF16 model parameters (Alg. 1: CastAndCopy W <- round_BF16(W_main), then I_t = { i : W[i] != W_prev[i] };
+ * Sec. 3.4 "Trainer").  Done in one step there is no W_prev to keep: for every element
+ *     r = round_BF16(master[i]);   if r != w[i] (bit patterns): emit (i, r);   w[i] <- r
+ * so that w holds the old model parameters on entry and the new ones on exit, and the payload is the
+ * same as extract(old = w_before, new = round_BF16(master)).
+ *
+ * round_BF16 is IEEE round-to-nearest-even on the upper 16 bits of the binary32 pattern; a NaN becomes
+ * the canonical quiet NaN 0x7FC0 (the paper does not say, and library casts differ among themselves on
+ * NaN; every other input has exactly one correctly rounded result, which is pinned against a library
+ * cast).
+ * ------------------------------------------------------------------------------------------------ */
+static uint16_t srs_oracle_round_bf16(uint32_t x)
+{
+    if ((x & 0x7fffffffu) > 0x7f800000u) return 0x7fc0u;                 /* NaN */
+    uint32_t lsb = (x >> 16) & 1u;                                       /* ties go to the even pattern */
+    return (uint16_t)((x + 0x7fffu + lsb) >> 16);
+}
+
+/* exported so that the rounding itself can be pinned against a library cast */
+void srs_oracle_round_bf16_array(const uint32_t *master_bits, uint64_t n, uint16_t *out)
+{
+    for (uint64_t i = 0; i < n; ++i) out[i] = srs_oracle_round_bf16(master_bits[i]);
+}
+
+/* Single tensor: w (in/out, n BF16 patterns), master_bits (n binary32 patterns).  Payload as in
+ * srs_oracle_extract (tensor-flat indices). */
+int srs_oracle_extract_cast(uint16_t *w, const uint32_t *master_bits, uint64_t n, uint64_t be,
+                            int32_t *I, uint16_t *V, uint32_t *counts, uint64_t cap)
+{
+    if (be == 0 || cap == 0 || n > 0x7fffffffULL || be > 0x7fffffffULL) return SRS_ORACLE_BAD_ARG;
+    uint64_t nb = (n + be - 1) / be;
+    int overflowed = 0;
+    for (uint64_t b = 0; b < nb; ++b) {
+        uint64_t lo = b * be;
+        uint64_t hi = lo + be < n ? lo + be : n;
+        uint64_t c = 0;
+        for (uint64_t i = lo; i < hi; ++i) {
+            uint16_t r = srs_oracle_round_bf16(master_bits[i]);
+            if (r != w[i]) {
+                if (c < cap) { I[b * cap + c] = (int32_t)i; V[b * cap + c] = r; }
+                c += 1;
+                w[i] = r;
+            }
+        }
+        counts[b] = (uint32_t)c;
+        if (c > cap) overflowed += 1;
+    }
+    return overflowed;
+}
+
+/* Tensor list, all buckets; indices are positions inside the bucket. */
+int srs_oracle_extract_cast_multi(uint16_t *const *w, const uint32_t *const *master_bits,
+                                  const uint64_t *numel, uint32_t ntensors, uint64_t be,
+                                  int32_t *I, uint16_t *V, uint32_t *counts, uint64_t cap)
+{
+    if (be == 0 || cap == 0 || be > 0x7fffffffULL) return SRS_ORACLE_BAD_ARG;
+    uint64_t total = 0;
+    for (uint32_t k = 0; k < ntensors; ++k) {
+        if (numel[k] > 0x7fffffffULL) return SRS_ORACLE_BAD_ARG;
+        total += numel[k];
+    }
+    uint64_t nb = (total + be - 1) / be;
+    for (uint64_t b = 0; b < nb; ++b) counts[b] = 0;
+    uint64_t g = 0;
+    for (uint32_t k = 0; k < ntensors; ++k) {
+        for (uint64_t j = 0; j < numel[k]; ++j) {
+            uint64_t p = g + j, b = p / be;
+            uint16_t r = srs_oracle_round_bf16(master_bits[k][j]);
+            if (r != w[k][j]) {
+                uint64_t c = counts[b];
+                if (c < cap) { I[b * cap + c] = (int32_t)(p - b * be); V[b * cap + c] = r; }
+                counts[b] = (uint32_t)(c + 1);
+                w[k][j] = r;
+            }
+        }
+        g += numel[k];
+    }
+    int overflowed = 0;
+    for (uint64_t b = 0; b < nb; ++b) if (counts[b] > cap) overflowed += 1;
+    return overflowed;
+}

@@ -112,11 +112,12 @@ int prepare_extract(srs_ctx *ctx, uint64_t ntiles, uint64_t nb, hipStream_t st, 
 }
 
 template <bool MULTI>
-int launch_extract(const srs_ctx *ctx, uint32_t tile_elems, const ExtractArgs &a, hipStream_t st) {
+int launch_extract(const srs_ctx *ctx, uint32_t tile_elems, const ExtractArgs &a, hipStream_t st, bool cast) {
     const dim3 grid(a.ntiles), block(kThreads);
-#define SRS_LAUNCH(VV)                                                                              \
-    do {                                                                                            \
-        if (ctx->refresh_group == 8) hipLaunchKernelGGL((extract_kernel<VV, MULTI, 8>), grid, block, 0, st, a);       \
+#define SRS_LAUNCH(VV)                                                                                                \
+    do {                                                                                                              \
+        if (cast) hipLaunchKernelGGL((extract_kernel<VV, MULTI, 4, true>), grid, block, 0, st, a);                    \
+        else if (ctx->refresh_group == 8) hipLaunchKernelGGL((extract_kernel<VV, MULTI, 8>), grid, block, 0, st, a);  \
         else if (ctx->refresh_group == 4) hipLaunchKernelGGL((extract_kernel<VV, MULTI, 4>), grid, block, 0, st, a);  \
         else hipLaunchKernelGGL((extract_kernel<VV, MULTI, 0>), grid, block, 0, st, a);                               \
     } while (0)
@@ -141,10 +142,10 @@ namespace {
 int upload_pair_pointers(srs_plan *plan, const srs_tensor_pair *t, hipStream_t st) {
     bool same = plan->pairs_valid;
     for (uint32_t k = 0; same && k < plan->ntensors; ++k)
-        same = plan->h_pairs[k].old_w == (uint16_t *)t[k].old_snapshot && plan->h_pairs[k].new_w == (const uint16_t *)t[k].new_w;
+        same = plan->h_pairs[k].old_w == (uint16_t *)t[k].old_snapshot && plan->h_pairs[k].new_w == t[k].new_w;
     if (!same) {
         for (uint32_t k = 0; k < plan->ntensors; ++k)
-            plan->h_pairs[k] = PtrPair{(uint16_t *)t[k].old_snapshot, (const uint16_t *)t[k].new_w};
+            plan->h_pairs[k] = PtrPair{(uint16_t *)t[k].old_snapshot, t[k].new_w};
         plan->pairs_valid = false;
         SRS_HIP(hipMemcpyAsync(plan->d_pairs, plan->h_pairs.data(), plan->ntensors * sizeof(PtrPair), hipMemcpyHostToDevice, st));
         plan->pairs_valid = true;
@@ -274,12 +275,14 @@ int srs_status(srs_ctx *ctx, uint32_t *flags, void *stream) {
 // single tensor
 // ---------------------------------------------------------------------------------------------
 
-int srs_extract(srs_ctx *ctx, void *old_snapshot, const void *new_w, uint64_t n, uint64_t bucket_elems,
-                int32_t *I, uint16_t *V, uint32_t *counts, uint64_t cap, void *stream) {
+namespace {
+int extract_single(srs_ctx *ctx, void *old_snapshot, const void *new_w, uint64_t n, uint64_t bucket_elems,
+                   int32_t *I, uint16_t *V, uint32_t *counts, uint64_t cap, void *stream, bool cast) {
     if (!ctx || bucket_elems == 0 || cap == 0 || n > kMaxIndexable || bucket_elems > kMaxIndexable) return SRS_ERR_INVALID;
     if (n == 0) return SRS_OK;
     if (!old_snapshot || !new_w || !I || !V || !counts) return SRS_ERR_INVALID;
-    if (((uintptr_t)old_snapshot | (uintptr_t)new_w | (uintptr_t)V) & 1u) return SRS_ERR_INVALID;
+    if (((uintptr_t)old_snapshot | (uintptr_t)V) & 1u) return SRS_ERR_INVALID;
+    if ((uintptr_t)new_w & (cast ? 3u : 1u)) return SRS_ERR_INVALID;
     if (((uintptr_t)I | (uintptr_t)counts) & 3u) return SRS_ERR_INVALID;
     hipStream_t st = (hipStream_t)stream;
     SRS_HIP(hipSetDevice(ctx->device));
@@ -298,14 +301,25 @@ int srs_extract(srs_ctx *ctx, void *old_snapshot, const void *new_w, uint64_t n,
     std::memset(&a, 0, sizeof(a));
     int rc = prepare_extract(ctx, ntiles, nb, st, &a.epoch, &a.ticket_stride);
     if (rc != SRS_OK) return rc;
-    a.old_w = (uint16_t *)old_snapshot; a.new_w = (const uint16_t *)new_w; a.n = n;
+    a.old_w = (uint16_t *)old_snapshot; a.new_w = new_w; a.n = n;
     a.be = (uint32_t)bucket_elems; a.tiles_per_bucket = (uint32_t)tpb;
     a.nb = (uint32_t)nb; a.last_tiles = (uint32_t)((last_len + T - 1) / T); a.group = (uint32_t)group;
     a.ntiles = (uint32_t)ntiles;
     a.I = I; a.V = V; a.counts = counts; a.cap = cap;
     a.status = ctx->status; a.tickets = ctx->tickets; a.flags = ctx->flags;
     a.spin_limit = ctx->spin_limit;
-    return launch_extract<false>(ctx, ctx->tile_elems, a, st);
+    return launch_extract<false>(ctx, ctx->tile_elems, a, st, cast);
+}
+}  // namespace
+
+int srs_extract(srs_ctx *ctx, void *old_snapshot, const void *new_w, uint64_t n, uint64_t bucket_elems,
+                int32_t *I, uint16_t *V, uint32_t *counts, uint64_t cap, void *stream) {
+    return extract_single(ctx, old_snapshot, new_w, n, bucket_elems, I, V, counts, cap, stream, false);
+}
+
+int srs_extract_cast(srs_ctx *ctx, void *weights, const float *master, uint64_t n, uint64_t bucket_elems,
+                     int32_t *I, uint16_t *V, uint32_t *counts, uint64_t cap, void *stream) {
+    return extract_single(ctx, weights, master, n, bucket_elems, I, V, counts, cap, stream, true);
 }
 
 int srs_apply(srs_ctx *ctx, void *weights, uint64_t n, uint64_t bucket_elems,
@@ -456,15 +470,16 @@ int srs_plan_destroy(srs_plan *p) {
     return SRS_OK;
 }
 
-int srs_extract_multi(srs_ctx *ctx, srs_plan *plan, const srs_tensor_pair *t,
-                      int32_t *I, uint16_t *V, uint32_t *counts, uint64_t cap, void *stream) {
+namespace {
+int extract_multi(srs_ctx *ctx, srs_plan *plan, const srs_tensor_pair *t,
+                  int32_t *I, uint16_t *V, uint32_t *counts, uint64_t cap, void *stream, bool cast) {
     if (!ctx || !plan || cap == 0 || plan->device != ctx->device) return SRS_ERR_INVALID;
     if (plan->total == 0) return SRS_OK;
     if (!t || !I || !V || !counts) return SRS_ERR_INVALID;
     if (((uintptr_t)V & 1u) || (((uintptr_t)I | (uintptr_t)counts) & 3u)) return SRS_ERR_INVALID;
     // numel is not known here any more, but a tensor with elements has at least one segment
     for (uint32_t k = 0; k < plan->ntensors; ++k)
-        if (((uintptr_t)t[k].old_snapshot | (uintptr_t)t[k].new_w) & 1u) return SRS_ERR_INVALID;
+        if (((uintptr_t)t[k].old_snapshot & 1u) || ((uintptr_t)t[k].new_w & (cast ? 3u : 1u))) return SRS_ERR_INVALID;
     hipStream_t st = (hipStream_t)stream;
     SRS_HIP(hipSetDevice(ctx->device));
 
@@ -480,7 +495,18 @@ int srs_extract_multi(srs_ctx *ctx, srs_plan *plan, const srs_tensor_pair *t,
     a.I = I; a.V = V; a.counts = counts; a.cap = cap;
     a.status = ctx->status; a.tickets = ctx->tickets; a.flags = ctx->flags;
     a.spin_limit = ctx->spin_limit;
-    return launch_extract<true>(ctx, plan->tile_elems, a, st);
+    return launch_extract<true>(ctx, plan->tile_elems, a, st, cast);
+}
+}  // namespace
+
+int srs_extract_multi(srs_ctx *ctx, srs_plan *plan, const srs_tensor_pair *t,
+                      int32_t *I, uint16_t *V, uint32_t *counts, uint64_t cap, void *stream) {
+    return extract_multi(ctx, plan, t, I, V, counts, cap, stream, false);
+}
+
+int srs_extract_cast_multi(srs_ctx *ctx, srs_plan *plan, const srs_tensor_pair *t,
+                           int32_t *I, uint16_t *V, uint32_t *counts, uint64_t cap, void *stream) {
+    return extract_multi(ctx, plan, t, I, V, counts, cap, stream, true);
 }
 
 int srs_apply_multi(srs_ctx *ctx, srs_plan *plan, const srs_tensor *t,

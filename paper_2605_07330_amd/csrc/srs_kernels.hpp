@@ -48,11 +48,11 @@ struct SegDesc {           // a run of one tensor inside one bucket (16 bytes)
     uint32_t tensor_off;
 };
 
-struct PtrPair { uint16_t *old_w; const uint16_t *new_w; };
+struct PtrPair { uint16_t *old_w; const void *new_w; };   // new_w: BF16 weights, or FP32 master weights (CAST)
 
 struct ExtractArgs {
     // single tensor: nb buckets of tiles_per_bucket tiles each, the last one of last_tiles tiles
-    uint16_t *old_w; const uint16_t *new_w; uint64_t n; uint32_t be; uint32_t tiles_per_bucket;
+    uint16_t *old_w; const void *new_w; uint64_t n; uint32_t be; uint32_t tiles_per_bucket;
     uint32_t nb; uint32_t last_tiles; uint32_t group;      // group = buckets interleaved per group
     // tensor list
     const TileDesc *tiles; const PtrPair *ptrs;
@@ -122,6 +122,33 @@ __device__ __forceinline__ u32x4 load8_guarded(const uint16_t *p, uint32_t e, ui
     uint32_t h[8];
 #pragma unroll
     for (int k = 0; k < 8; ++k) h[k] = (e + k < len) ? (uint32_t)p[e + k] : 0u;
+    u32x4 r;
+    r.x = h[0] | (h[1] << 16); r.y = h[2] | (h[3] << 16);
+    r.z = h[4] | (h[5] << 16); r.w = h[6] | (h[7] << 16);
+    return r;
+}
+
+// binary32 pattern -> BF16 pattern, round to nearest even; NaN -> 0x7FC0
+__device__ __forceinline__ uint32_t round_bf16(uint32_t x) {
+    const uint32_t r = (x + 0x7FFFu + ((x >> 16) & 1u)) >> 16;
+    return ((x & 0x7FFFFFFFu) > 0x7F800000u) ? 0x7FC0u : r;
+}
+
+// eight consecutive master weights (two 16-byte vectors) -> eight BF16 patterns in memory order
+__device__ __forceinline__ u32x4 round8_bf16(u32x4 f0, u32x4 f1) {
+    u32x4 r;
+    r.x = round_bf16(f0.x) | (round_bf16(f0.y) << 16);
+    r.y = round_bf16(f0.z) | (round_bf16(f0.w) << 16);
+    r.z = round_bf16(f1.x) | (round_bf16(f1.y) << 16);
+    r.w = round_bf16(f1.z) | (round_bf16(f1.w) << 16);
+    return r;
+}
+
+// guarded, any alignment (4-byte elements): elements at or beyond len read as BF16 pattern 0
+__device__ __forceinline__ u32x4 load8_guarded_cast(const uint32_t *p, uint32_t e, uint32_t len) {
+    uint32_t h[8];
+#pragma unroll
+    for (int k = 0; k < 8; ++k) h[k] = (e + k < len) ? round_bf16(p[e + k]) : 0u;
     u32x4 r;
     r.x = h[0] | (h[1] << 16); r.y = h[2] | (h[3] << 16);
     r.z = h[4] | (h[5] << 16); r.w = h[6] | (h[7] << 16);
@@ -213,7 +240,10 @@ __device__ __forceinline__ uint32_t look_back(const ExtractArgs &a, uint32_t til
 // RG = lanes per snapshot-refresh group: 0 refreshes element by element (2-byte stores); 4 / 8 rewrite
 // the whole aligned 64 / 128 bytes around a change from the new weights (unchanged elements get the
 // value they already hold), so that the memory system sees full-sector writes instead of masked ones.
-template <int V, bool MULTI, int RG>
+// CAST: `new` is not a BF16 buffer but the FP32 master weights; each element is rounded to BF16
+// (nearest even, NaN -> 0x7FC0) on the fly and `old` is the model-parameter buffer itself: the cast-and-
+// copy of Alg. 1 fused with its diff, so that no snapshot exists at all.
+template <int V, bool MULTI, int RG, bool CAST = false>
 __global__ __launch_bounds__(kThreads) void extract_kernel(const ExtractArgs a) {
     constexpr bool NT = false;
     static_assert(V % 2 == 0, "counts are scanned in packed pairs");
@@ -259,11 +289,11 @@ __global__ __launch_bounds__(kThreads) void extract_kernel(const ExtractArgs a) 
 
     // ---- where this tile lives
     uint32_t bucket_off, len, idx_base;
-    uint16_t *po; const uint16_t *pn;
+    uint16_t *po; const void *pn_raw; uint64_t pn_off;      // new weights: base pointer and element offset
     if (MULTI) {
         const TileDesc d = a.tiles[tile];
         const PtrPair p = a.ptrs[d.tensor];
-        po = p.old_w + d.tensor_off; pn = p.new_w + d.tensor_off;
+        po = p.old_w + d.tensor_off; pn_raw = p.new_w; pn_off = d.tensor_off;
         bucket_off = d.bucket_off; len = d.len;
         idx_base = bucket_off;                          // index = position inside the bucket
     } else {
@@ -271,7 +301,7 @@ __global__ __launch_bounds__(kThreads) void extract_kernel(const ExtractArgs a) 
         const uint32_t blen = (uint32_t)((a.n - b0 < a.be) ? (a.n - b0) : a.be);
         bucket_off = k * TILE;
         len = (blen - bucket_off < TILE) ? (blen - bucket_off) : TILE;
-        po = a.old_w + b0 + bucket_off; pn = a.new_w + b0 + bucket_off;
+        po = a.old_w + b0 + bucket_off; pn_raw = a.new_w; pn_off = b0 + bucket_off;
         idx_base = (uint32_t)(b0 + bucket_off);         // index = tensor-flat position
     }
 
@@ -279,20 +309,40 @@ __global__ __launch_bounds__(kThreads) void extract_kernel(const ExtractArgs a) 
     // of lane l holds elements (j*64 + l)*8 .. +8, so ascending order is (wave, j, lane, element).
     u32x4 xo[V], xn[V];
     const uint32_t e0 = (uint32_t)wave * (V * 512u) + (uint32_t)lane * 8u;
-    const bool aligned = ((((uintptr_t)po) | ((uintptr_t)pn)) & 15u) == 0;
+    // with CAST pn addresses 32-bit elements: pf is the same position in the master weights
+    const uint32_t *const pf = reinterpret_cast<const uint32_t *>(pn_raw) + pn_off;
+    const uint16_t *const pn = reinterpret_cast<const uint16_t *>(pn_raw) + pn_off;
+    const bool aligned = CAST ? (((((uintptr_t)po) | ((uintptr_t)pf)) & 15u) == 0)
+                              : (((((uintptr_t)po) | ((uintptr_t)pn)) & 15u) == 0);
     if (aligned && len == TILE) {
+        if (CAST) {
+            u32x4 f0[V], f1[V];
 #pragma unroll
-        for (int j = 0; j < V; ++j) xn[j] = load16<NT>(pn + e0 + j * 512);
+            for (int j = 0; j < V; ++j) {
+                f0[j] = *reinterpret_cast<const u32x4 *>(pf + e0 + j * 512);
+                f1[j] = *reinterpret_cast<const u32x4 *>(pf + e0 + j * 512 + 4);
+            }
 #pragma unroll
-        for (int j = 0; j < V; ++j) xo[j] = load16<NT>(po + e0 + j * 512);
+            for (int j = 0; j < V; ++j) xo[j] = load16<NT>(po + e0 + j * 512);
+#pragma unroll
+            for (int j = 0; j < V; ++j) xn[j] = round8_bf16(f0[j], f1[j]);
+        } else {
+#pragma unroll
+            for (int j = 0; j < V; ++j) xn[j] = load16<NT>(pn + e0 + j * 512);
+#pragma unroll
+            for (int j = 0; j < V; ++j) xo[j] = load16<NT>(po + e0 + j * 512);
+        }
     } else {
 #pragma unroll
         for (int j = 0; j < V; ++j) {
             const uint32_t e = e0 + j * 512;
             if (aligned && e + 8 <= len) {
-                xn[j] = load16<false>(pn + e); xo[j] = load16<false>(po + e);
+                xo[j] = load16<false>(po + e);
+                if (CAST) xn[j] = round8_bf16(*reinterpret_cast<const u32x4 *>(pf + e), *reinterpret_cast<const u32x4 *>(pf + e + 4));
+                else xn[j] = load16<false>(pn + e);
             } else {
-                xn[j] = load8_guarded(pn, e, len); xo[j] = load8_guarded(po, e, len);
+                xo[j] = load8_guarded(po, e, len);
+                xn[j] = CAST ? load8_guarded_cast(pf, e, len) : load8_guarded(pn, e, len);
             }
         }
     }
@@ -681,7 +731,7 @@ __global__ __launch_bounds__(kThreads) void dense_copy_kernel(const DenseCopyArg
     if (j >= a.bucket_first[b + 1] - first) return;
     const TileDesc d = a.tiles[first + j];
     uint16_t *const slot = a.dense + (uint64_t)s * a.be + d.bucket_off;
-    uint16_t *const w = PACK ? const_cast<uint16_t *>(a.pairs[d.tensor].new_w) + d.tensor_off
+    uint16_t *const w = PACK ? const_cast<uint16_t *>(static_cast<const uint16_t *>(a.pairs[d.tensor].new_w)) + d.tensor_off
                              : a.wptrs[d.tensor] + d.tensor_off;
     uint16_t *const dst = PACK ? slot : w;
     const uint16_t *const src = PACK ? w : slot;

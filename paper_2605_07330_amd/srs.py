@@ -34,6 +34,7 @@ EXPORTS = [
     "srs_extract_multi", "srs_apply_multi", "srs_stream_probe", "srs_stream_probe_sink_words",
     "srs_anchor_count", "srs_encode_indices", "srs_apply_encoded", "srs_apply_multi_encoded",
     "srs_route", "srs_pack_dense_multi", "srs_unpack_dense_multi",
+    "srs_extract_cast", "srs_extract_cast_multi",
 ]
 
 
@@ -68,6 +69,8 @@ _lib.srs_anchor_count.restype = _u64
 _lib.srs_encode_indices.argtypes = [_vp, _vp, _vp, C.c_uint32, _u64, _u64, _vp, _vp, _vp, _vp]
 _lib.srs_apply_encoded.argtypes = [_vp, _vp, _u64, _u64, _vp, _vp, _vp, _vp, _vp, _vp, _u64, _vp]
 _lib.srs_apply_multi_encoded.argtypes = [_vp, _vp, C.POINTER(Tensor), _vp, _vp, _vp, _vp, _vp, _vp, _u64, _vp]
+_lib.srs_extract_cast.argtypes = [_vp, _vp, _vp, _u64, _u64, _vp, _vp, _vp, _u64, _vp]
+_lib.srs_extract_cast_multi.argtypes = [_vp, _vp, C.POINTER(TensorPair), _vp, _vp, _vp, _u64, _vp]
 _lib.srs_route.argtypes = [_vp, _vp, C.c_uint32, _u64, _u64, _u64, C.c_uint32, C.c_uint32, _vp, _vp, _vp, _vp, _vp]
 _lib.srs_pack_dense_multi.argtypes = [_vp, _vp, C.POINTER(TensorPair), _vp, _vp, C.c_uint32, _vp, _vp]
 _lib.srs_unpack_dense_multi.argtypes = [_vp, _vp, C.POINTER(Tensor), _vp, _vp, C.c_uint32, _vp, _vp]
@@ -246,6 +249,42 @@ class Context:
             _payload_ok(I, V, counts, plan.nbuckets, cap)
         _check(_lib.srs_apply_multi(self._h, plan._h, tensors, I.data_ptr(), V.data_ptr(), counts.data_ptr(), cap,
                                     _stream_ptr(stream)), "srs_apply_multi")
+
+    # ---- fused cast + diff ----------------------------------------------------------------
+    def extract_cast(self, weights: torch.Tensor, master: torch.Tensor, bucket_elems: int, I: torch.Tensor,
+                     V: torch.Tensor, counts: torch.Tensor, cap: int, stream: Optional[torch.cuda.Stream] = None) -> None:
+        _dev16(weights, "weights")
+        if not (master.is_cuda and master.dtype == torch.float32 and master.is_contiguous()
+                and master.numel() == weights.numel()):
+            raise TypeError("master: expected contiguous float32 GPU tensor of the same numel")
+        n = weights.numel()
+        if bucket_elems > 0 and cap > 0:
+            _payload_ok(I, V, counts, (n + bucket_elems - 1) // bucket_elems, cap)
+        _check(_lib.srs_extract_cast(self._h, weights.data_ptr(), master.data_ptr(), n, bucket_elems, I.data_ptr(),
+                                     V.data_ptr(), counts.data_ptr(), cap, _stream_ptr(stream)), "srs_extract_cast")
+
+    def bind_cast_pairs(self, plan: Plan, weights: Sequence[torch.Tensor], master: Sequence[torch.Tensor]):
+        if len(weights) != len(plan.numel) or len(master) != len(plan.numel):
+            raise ValueError("tensor list does not match the plan")
+        arr = (TensorPair * max(len(weights), 1))()
+        for k, (w, m) in enumerate(zip(weights, master)):
+            _dev16(w, f"weights[{k}]")
+            if not (m.is_cuda and m.dtype == torch.float32 and m.is_contiguous()):
+                raise TypeError(f"master[{k}]: expected contiguous float32 GPU tensor")
+            if w.numel() != plan.numel[k] or m.numel() != plan.numel[k]:
+                raise ValueError(f"tensor {k}: numel differs from the plan")
+            arr[k].old_snapshot, arr[k].new_w = w.data_ptr(), m.data_ptr()
+        return arr
+
+    def extract_cast_multi(self, plan: Plan, weights: Optional[Sequence[torch.Tensor]],
+                           master: Optional[Sequence[torch.Tensor]], I: torch.Tensor, V: torch.Tensor,
+                           counts: torch.Tensor, cap: int, stream: Optional[torch.cuda.Stream] = None, pairs=None) -> None:
+        if pairs is None:
+            pairs = self.bind_cast_pairs(plan, weights, master)
+        if cap > 0:
+            _payload_ok(I, V, counts, plan.nbuckets, cap)
+        _check(_lib.srs_extract_cast_multi(self._h, plan._h, pairs, I.data_ptr(), V.data_ptr(), counts.data_ptr(), cap,
+                                           _stream_ptr(stream)), "srs_extract_cast_multi")
 
     # ---- 16-bit index coding --------------------------------------------------------------
     def encode_indices(self, I: torch.Tensor, counts: torch.Tensor, nbuckets: int, cap: int, base_stride: int,

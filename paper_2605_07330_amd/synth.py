@@ -353,6 +353,18 @@ def make_update(new: WeightSet, old: WeightSet, seed: int, step: int = 1, want_m
     return total, (masks if want_masks else None)
 
 
+def master_from_(master_flat: torch.Tensor, w_flat: torch.Tensor, seed: int, salt: int = 0) -> None:
+    """FP32 master weights that round (nearest even) to the given BF16 weights: master = w * (1 + u * 2^-10)
+    with u uniform in (-1, 1).  The relative offset stays below half a BF16 ulp (2^-9 of the value at
+    least), so the rounding gives w back; zeros stay zero."""
+    n = w_flat.numel()
+    for c, lo in enumerate(range(0, n, _CHUNK)):
+        hi = min(n, lo + _CHUNK)
+        g = _gen(w_flat.device, seed, salt, c, 6)
+        u = torch.rand(hi - lo, generator=g, device=w_flat.device, dtype=torch.float32) * 2.0 - 1.0
+        master_flat[lo:hi] = w_flat[lo:hi].float() * (1.0 + u * (2.0 ** -10))
+
+
 def payload_capacity(wl: Workload, max_bucket_count: Optional[int] = None) -> int:
     """Per-bucket payload slots: from the known worst bucket when given, else 1.25 * p * be + 4096
     (five sigma of an iid 1 % bucket of 33.5 M elements is under 3000)."""
