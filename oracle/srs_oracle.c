@@ -41,6 +41,12 @@
  * over every change mask of tiny tensors, the generator's own change mask, the
  * payload-size closed form of Eq. (1)/(2), and numpy's flatnonzero / fancy
  * indexing as an independent library statement of the same definition.
+ * Further down: index delta coding (pinned to numpy diff / cumsum, the 2^15
+ * width rule, the paper's 3.2 B per changed element), density routing (brute
+ * force of the Eq. (1) break-even), fused cast + diff (rounding pinned to a
+ * library cast on every non-NaN class of input; fused == cast then extract).
+ * parity unpinned: only the BF16 pattern a NaN master weight rounds to (0x7FC0
+ * here) -- the paper is silent and library casts disagree on it.
  */
 #include <stdint.h>
 #include <stddef.h>

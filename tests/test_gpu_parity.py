@@ -246,6 +246,33 @@ def test_tensor_lists_odd_shapes(srs, ctx, numel, be):
         assert np.array_equal(u16(o), w) and np.array_equal(u16(r), w)
 
 
+def test_bucket_with_more_segments_than_the_lds_cache(srs, ctx):
+    """1000 tensors of 37 elements share few buckets: apply's segment table does not fit its LDS cache."""
+    numel = [37] * 1000 + [5000] + [1] * 300
+    be = 20000
+    rng = np.random.default_rng(12)
+    olds = [rng.integers(0, 1 << 16, size=m, dtype=np.uint16) for m in numel]
+    news = [o.copy() for o in olds]
+    for w in news:
+        w[rng.random(w.size) < 0.2] ^= 0x8001
+    want = oracle.extract_multi([o.copy() for o in olds], news, numel, be)[:3]
+    d_old = [from_u16(o, DEV) for o in olds]; d_new = [from_u16(w, DEV) for w in news]
+    d_roll = [from_u16(o, DEV) for o in olds]; d_roll2 = [from_u16(o, DEV) for o in olds]
+    plan = ctx.plan(numel, be)
+    assert plan.nsegments > 1300
+    I, V, counts = srs.alloc_payload(plan.nbuckets, be, DEV)
+    ctx.extract_multi(plan, d_old, d_new, I, V, counts, be)
+    ctx.apply_multi(plan, d_roll, I, V, counts, be)
+    D, mg, an = srs.alloc_encoded(plan.nbuckets, be, DEV)
+    ctx.encode_indices(I, counts, plan.nbuckets, be, 0, D, mg, an)
+    ctx.apply_multi_encoded(plan, d_roll2, D, I, V, counts, mg, an, be)
+    assert ctx.status() == 0
+    plan.close()
+    assert_payload_equal(payload_to_host(I, V, counts), want, "many segments")
+    for o, r, r2, w in zip(d_old, d_roll, d_roll2, news):
+        assert np.array_equal(u16(o), w) and np.array_equal(u16(r), w) and np.array_equal(u16(r2), w)
+
+
 def test_capacity_overflow(srs, ctx):
     n, be, cap = 200000, 50000, 300
     old_h, new_h = make_pair(n, 0.01, seed=77)                  # ~500 changes per bucket > cap
