@@ -116,6 +116,17 @@ int srs_plan_info(const srs_plan *plan, uint64_t *total_elems, uint32_t *nbucket
                   uint32_t *ntiles);
 int srs_plan_destroy(srs_plan *plan);
 
+/* Host only (touches no device): the tables srs_plan_create builds, for inspection and tests.  All output
+ * pointers are HOST arrays and may be NULL; call once with NULL arrays to get the sizes.
+ *   tiles[4*ntiles]     : tensor, first element inside the tensor, first element inside the bucket, length
+ *   segs[4*nsegments]   : first element inside the bucket, length, tensor, first element inside the tensor
+ *   seg_begin[nb+1], bucket_first[nb+1] : first segment / first tile of each bucket
+ *   wg_bucket[ntiles]   : the bucket that extract's workgroup i serves
+ * tile_elems and interleave as in SRS_OPT_TILE_ELEMS / SRS_OPT_INTERLEAVE. */
+int srs_plan_layout(const uint64_t *numel, uint32_t ntensors, uint64_t bucket_elems, uint32_t tile_elems,
+                    uint32_t interleave, uint32_t *nbuckets, uint32_t *nsegments, uint32_t *ntiles, uint32_t *tiles,
+                    uint32_t *segs, uint32_t *seg_begin, uint32_t *bucket_first, uint32_t *wg_bucket);
+
 /* t[ntensors] (host array) gives the device pointers of each tensor, in plan order.  The library
  * keeps a device copy and re-uploads it (hipMemcpyAsync on `stream`) only when a pointer changed. */
 int srs_extract_multi(srs_ctx *ctx, srs_plan *plan, const srs_tensor_pair *t,

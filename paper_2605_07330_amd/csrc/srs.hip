@@ -37,7 +37,6 @@ struct srs_ctx {
     uint32_t tile_elems = 16384;
     uint32_t group = 1024;                  // buckets whose tiles are interleaved over consecutive workgroups
     uint32_t refresh_group = 4;             // lanes (x16 bytes) rewritten around a change by the snapshot refresh
-    bool nontemporal = false;               // read probe only
 };
 
 struct srs_plan {
@@ -138,6 +137,82 @@ bool valid_tile_elems(uint64_t v) { return v == 4096 || v == 8192 || v == 16384 
 }  // namespace
 
 namespace {
+// Host tables of a tensor list: a segment is a maximal run of one tensor inside one bucket, a tile a run
+// of at most tile_elems elements inside one segment; wg_bucket tells extract's workgroup i which bucket to
+// serve: inside each group of `group` buckets consecutive workgroups rotate over the buckets that still
+// have tiles left, so every bucket is served exactly once per tile.
+struct Layout {
+    std::vector<SegDesc> segs;
+    std::vector<uint32_t> seg_begin, bucket_first, wg_bucket;
+    std::vector<TileDesc> tiles;
+    uint32_t nbuckets = 0, max_bucket_tiles = 0;
+};
+
+int build_layout(const uint64_t *numel, uint32_t ntensors, uint64_t bucket_elems, uint32_t tile_elems, uint32_t group,
+                 Layout &L) {
+    uint64_t total = 0;
+    for (uint32_t k = 0; k < ntensors; ++k) {
+        if (numel[k] > kMaxIndexable) return SRS_ERR_INVALID;
+        total += numel[k];
+    }
+    const uint64_t nb64 = (total + bucket_elems - 1) / bucket_elems;
+    if (nb64 > 0x7fffffffull || group == 0 || tile_elems == 0) return SRS_ERR_INVALID;
+    L.nbuckets = (uint32_t)nb64;
+    try {
+        L.seg_begin.assign((size_t)L.nbuckets + 1, 0);
+        L.bucket_first.assign((size_t)L.nbuckets + 1, 0);
+        uint64_t g = 0;                       // packed position of the current tensor's element 0
+        uint32_t cur_bucket = 0xffffffffu;
+        for (uint32_t k = 0; k < ntensors; ++k) {
+            uint64_t off = 0;
+            while (off < numel[k]) {
+                const uint64_t pos = g + off;
+                const uint64_t b = pos / bucket_elems;
+                const uint64_t boff = pos - b * bucket_elems;
+                uint64_t len = numel[k] - off;
+                if (len > bucket_elems - boff) len = bucket_elems - boff;
+                if ((uint32_t)b != cur_bucket) {
+                    cur_bucket = (uint32_t)b;
+                    L.bucket_first[b] = (uint32_t)L.tiles.size();
+                    L.seg_begin[b] = (uint32_t)L.segs.size();
+                }
+                L.segs.push_back(SegDesc{(uint32_t)boff, (uint32_t)len, k, (uint32_t)off});
+                for (uint64_t t = 0; t < len; t += tile_elems) {
+                    const uint64_t tl = (len - t < tile_elems) ? (len - t) : tile_elems;
+                    L.tiles.push_back(TileDesc{k, (uint32_t)(off + t), (uint32_t)(boff + t), (uint32_t)tl});
+                }
+                if (L.tiles.size() > 0x7fffffffull) return SRS_ERR_INVALID;
+                off += len;
+            }
+            g += numel[k];
+        }
+        L.seg_begin[L.nbuckets] = (uint32_t)L.segs.size();
+        L.bucket_first[L.nbuckets] = (uint32_t)L.tiles.size();
+        for (uint32_t b = 0; b < L.nbuckets; ++b) {
+            const uint32_t nt = L.bucket_first[b + 1] - L.bucket_first[b];
+            if (nt > L.max_bucket_tiles) L.max_bucket_tiles = nt;
+        }
+        L.wg_bucket.reserve(L.tiles.size());
+        std::vector<uint32_t> left;
+        for (uint32_t g0 = 0; g0 < L.nbuckets; g0 += group) {
+            const uint32_t g1 = (L.nbuckets - g0 < group) ? L.nbuckets : g0 + group;
+            left.assign(g1 - g0, 0);
+            uint64_t remaining = 0;
+            for (uint32_t b = g0; b < g1; ++b) {
+                left[b - g0] = L.bucket_first[b + 1] - L.bucket_first[b];
+                remaining += left[b - g0];
+            }
+            while (remaining) {
+                for (uint32_t b = g0; b < g1; ++b)
+                    if (left[b - g0]) { L.wg_bucket.push_back(b); --left[b - g0]; --remaining; }
+            }
+        }
+    } catch (const std::bad_alloc &) {
+        return SRS_ERR_NOMEM;
+    }
+    return SRS_OK;
+}
+
 // keeps the device copy of the extract-side pointer table in step with the caller's array
 int upload_pair_pointers(srs_plan *plan, const srs_tensor_pair *t, hipStream_t st) {
     bool same = plan->pairs_valid;
@@ -367,61 +442,21 @@ int srs_plan_create(srs_ctx *ctx, const uint64_t *numel, uint32_t ntensors, uint
     p->device = ctx->device; p->total = total; p->be = bucket_elems; p->ntensors = ntensors;
     p->nbuckets = (uint32_t)nb64; p->tile_elems = ctx->tile_elems;
 
-    // Walk the packed space: a segment is a maximal run of one tensor inside one bucket; a tile is a
-    // run of at most tile_elems elements inside one segment.
-    std::vector<SegDesc> segs;
-    std::vector<uint32_t> seg_begin, bucket_first, wg_bucket;
-    std::vector<TileDesc> tiles;
+    Layout L;
+    {
+        const int rc = build_layout(numel, ntensors, bucket_elems, p->tile_elems, ctx->group, L);
+        if (rc != SRS_OK) { delete p; return rc; }
+    }
     try {
-        seg_begin.assign((size_t)p->nbuckets + 1, 0);
-        bucket_first.assign((size_t)p->nbuckets + 1, 0);
-        uint64_t g = 0;                       // packed position of the current tensor's element 0
-        uint32_t cur_bucket = 0xffffffffu;
-        for (uint32_t k = 0; k < ntensors; ++k) {
-            uint64_t off = 0;
-            while (off < numel[k]) {
-                const uint64_t pos = g + off;
-                const uint64_t b = pos / bucket_elems;
-                const uint64_t boff = pos - b * bucket_elems;
-                uint64_t len = numel[k] - off;
-                if (len > bucket_elems - boff) len = bucket_elems - boff;
-                if ((uint32_t)b != cur_bucket) {
-                    cur_bucket = (uint32_t)b;
-                    bucket_first[b] = (uint32_t)tiles.size();
-                    seg_begin[b] = (uint32_t)segs.size();
-                }
-                segs.push_back(SegDesc{(uint32_t)boff, (uint32_t)len, k, (uint32_t)off});
-                for (uint64_t t = 0; t < len; t += p->tile_elems) {
-                    const uint64_t tl = (len - t < p->tile_elems) ? (len - t) : p->tile_elems;
-                    tiles.push_back(TileDesc{k, (uint32_t)(off + t), (uint32_t)(boff + t), (uint32_t)tl});
-                }
-                off += len;
-            }
-            g += numel[k];
-        }
-        seg_begin[p->nbuckets] = (uint32_t)segs.size();
-        bucket_first[p->nbuckets] = (uint32_t)tiles.size();
-        for (uint32_t b = 0; b < p->nbuckets; ++b)
-            if (bucket_first[b + 1] - bucket_first[b] > p->max_bucket_tiles) p->max_bucket_tiles = bucket_first[b + 1] - bucket_first[b];
-        // workgroup -> bucket: inside each group of `group` buckets, consecutive workgroups rotate
-        // over the buckets that still have tiles left, so every bucket is served exactly once per tile
-        wg_bucket.reserve(tiles.size());
-        std::vector<uint32_t> left;
-        for (uint32_t g0 = 0; g0 < p->nbuckets; g0 += ctx->group) {
-            const uint32_t g1 = (p->nbuckets - g0 < ctx->group) ? p->nbuckets : g0 + ctx->group;
-            left.assign(g1 - g0, 0);
-            uint64_t remaining = 0;
-            for (uint32_t b = g0; b < g1; ++b) { left[b - g0] = bucket_first[b + 1] - bucket_first[b]; remaining += left[b - g0]; }
-            while (remaining) {
-                for (uint32_t b = g0; b < g1; ++b)
-                    if (left[b - g0]) { wg_bucket.push_back(b); --left[b - g0]; --remaining; }
-            }
-        }
         p->h_pairs.assign(ntensors, PtrPair{nullptr, nullptr});
         p->h_wptrs.assign(ntensors, nullptr);
     } catch (const std::bad_alloc &) {
         delete p; return SRS_ERR_NOMEM;
     }
+    p->max_bucket_tiles = L.max_bucket_tiles;
+    std::vector<SegDesc> &segs = L.segs;
+    std::vector<uint32_t> &seg_begin = L.seg_begin, &bucket_first = L.bucket_first, &wg_bucket = L.wg_bucket;
+    std::vector<TileDesc> &tiles = L.tiles;
     if (tiles.size() > 0x7fffffffull) { delete p; return SRS_ERR_INVALID; }
     p->nsegments = (uint32_t)segs.size();
     p->ntiles = (uint32_t)tiles.size();
@@ -452,6 +487,26 @@ int srs_plan_info(const srs_plan *plan, uint64_t *total_elems, uint32_t *nbucket
     if (nbuckets) *nbuckets = plan->nbuckets;
     if (nsegments) *nsegments = plan->nsegments;
     if (ntiles) *ntiles = plan->ntiles;
+    return SRS_OK;
+}
+
+int srs_plan_layout(const uint64_t *numel, uint32_t ntensors, uint64_t bucket_elems, uint32_t tile_elems,
+                    uint32_t interleave, uint32_t *nbuckets, uint32_t *nsegments, uint32_t *ntiles, uint32_t *tiles,
+                    uint32_t *segs, uint32_t *seg_begin, uint32_t *bucket_first, uint32_t *wg_bucket) {
+    if ((!numel && ntensors) || bucket_elems == 0 || bucket_elems > kMaxIndexable || !valid_tile_elems(tile_elems) ||
+        interleave == 0 || interleave > 4096)
+        return SRS_ERR_INVALID;
+    Layout L;
+    const int rc = build_layout(numel, ntensors, bucket_elems, tile_elems, interleave, L);
+    if (rc != SRS_OK) return rc;
+    if (nbuckets) *nbuckets = L.nbuckets;
+    if (nsegments) *nsegments = (uint32_t)L.segs.size();
+    if (ntiles) *ntiles = (uint32_t)L.tiles.size();
+    if (tiles) std::memcpy(tiles, L.tiles.data(), L.tiles.size() * sizeof(TileDesc));
+    if (segs) std::memcpy(segs, L.segs.data(), L.segs.size() * sizeof(SegDesc));
+    if (seg_begin) std::memcpy(seg_begin, L.seg_begin.data(), L.seg_begin.size() * sizeof(uint32_t));
+    if (bucket_first) std::memcpy(bucket_first, L.bucket_first.data(), L.bucket_first.size() * sizeof(uint32_t));
+    if (wg_bucket) std::memcpy(wg_bucket, L.wg_bucket.data(), L.wg_bucket.size() * sizeof(uint32_t));
     return SRS_OK;
 }
 
@@ -690,12 +745,8 @@ int srs_stream_probe(srs_ctx *ctx, const void *a, const void *b, uint64_t bytes,
     const uint64_t tile_bytes = 16384ull * 2ull;
     const uint64_t blocks = (bytes + tile_bytes - 1) / tile_bytes;
     if (blocks > 0x7fffffffull) return SRS_ERR_INVALID;
-    if (ctx->nontemporal)
-        hipLaunchKernelGGL((stream_probe_kernel<8, true>), dim3((uint32_t)blocks), dim3(kThreads), 0, st,
-                           (const uint16_t *)a, (const uint16_t *)b, nvec, sink);
-    else
-        hipLaunchKernelGGL((stream_probe_kernel<8, false>), dim3((uint32_t)blocks), dim3(kThreads), 0, st,
-                           (const uint16_t *)a, (const uint16_t *)b, nvec, sink);
+    hipLaunchKernelGGL((stream_probe_kernel<8, false>), dim3((uint32_t)blocks), dim3(kThreads), 0, st,
+                       (const uint16_t *)a, (const uint16_t *)b, nvec, sink);
     SRS_HIP(hipGetLastError());
     return SRS_OK;
 }

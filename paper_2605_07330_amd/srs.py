@@ -34,7 +34,7 @@ EXPORTS = [
     "srs_extract_multi", "srs_apply_multi", "srs_stream_probe", "srs_stream_probe_sink_words",
     "srs_anchor_count", "srs_encode_indices", "srs_apply_encoded", "srs_apply_multi_encoded",
     "srs_route", "srs_pack_dense_multi", "srs_unpack_dense_multi",
-    "srs_extract_cast", "srs_extract_cast_multi",
+    "srs_extract_cast", "srs_extract_cast_multi", "srs_plan_layout",
 ]
 
 
@@ -71,6 +71,8 @@ _lib.srs_apply_encoded.argtypes = [_vp, _vp, _u64, _u64, _vp, _vp, _vp, _vp, _vp
 _lib.srs_apply_multi_encoded.argtypes = [_vp, _vp, C.POINTER(Tensor), _vp, _vp, _vp, _vp, _vp, _vp, _u64, _vp]
 _lib.srs_extract_cast.argtypes = [_vp, _vp, _vp, _u64, _u64, _vp, _vp, _vp, _u64, _vp]
 _lib.srs_extract_cast_multi.argtypes = [_vp, _vp, C.POINTER(TensorPair), _vp, _vp, _vp, _u64, _vp]
+_lib.srs_plan_layout.argtypes = [C.POINTER(_u64), C.c_uint32, _u64, C.c_uint32, C.c_uint32, _u32p, _u32p, _u32p,
+                                 _vp, _vp, _vp, _vp, _vp]
 _lib.srs_route.argtypes = [_vp, _vp, C.c_uint32, _u64, _u64, _u64, C.c_uint32, C.c_uint32, _vp, _vp, _vp, _vp, _vp]
 _lib.srs_pack_dense_multi.argtypes = [_vp, _vp, C.POINTER(TensorPair), _vp, _vp, C.c_uint32, _vp, _vp]
 _lib.srs_unpack_dense_multi.argtypes = [_vp, _vp, C.POINTER(Tensor), _vp, _vp, C.c_uint32, _vp, _vp]
@@ -111,6 +113,24 @@ def _payload_ok(I: torch.Tensor, V: torch.Tensor, counts: torch.Tensor, nb: int,
         raise TypeError("V: expected contiguous 16-bit GPU tensor of at least nb*cap elements")
     if not (counts.is_cuda and counts.element_size() == 4 and counts.is_contiguous() and counts.numel() >= nb):
         raise TypeError("counts: expected contiguous 32-bit GPU tensor of at least nb elements")
+
+
+def plan_layout(numel: Sequence[int], bucket_elems: int, tile_elems: int = 16384, interleave: int = 1024) -> dict:
+    """Host-only view of the tables a plan holds (numpy arrays); needs no GPU."""
+    import numpy as np
+    numel = [int(x) for x in numel]
+    arr = (_u64 * max(len(numel), 1))(*numel)
+    nb, ns, nt = C.c_uint32(), C.c_uint32(), C.c_uint32()
+    _check(_lib.srs_plan_layout(arr, len(numel), bucket_elems, tile_elems, interleave, C.byref(nb), C.byref(ns),
+                                C.byref(nt), None, None, None, None, None), "srs_plan_layout")
+    tiles = np.zeros((nt.value, 4), np.uint32); segs = np.zeros((ns.value, 4), np.uint32)
+    seg_begin = np.zeros(nb.value + 1, np.uint32); bucket_first = np.zeros(nb.value + 1, np.uint32)
+    wg_bucket = np.zeros(nt.value, np.uint32)
+    _check(_lib.srs_plan_layout(arr, len(numel), bucket_elems, tile_elems, interleave, None, None, None,
+                                tiles.ctypes.data, segs.ctypes.data, seg_begin.ctypes.data, bucket_first.ctypes.data,
+                                wg_bucket.ctypes.data), "srs_plan_layout")
+    return {"nbuckets": nb.value, "tiles": tiles, "segs": segs, "seg_begin": seg_begin, "bucket_first": bucket_first,
+            "wg_bucket": wg_bucket}
 
 
 def anchor_count(nbuckets: int, cap: int) -> int:
