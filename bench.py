@@ -162,7 +162,9 @@ def main() -> int:
     ap.add_argument("--interleave", type=int, default=0, help="buckets interleaved over consecutive workgroups (0 = default)")
     ap.add_argument("--tiny", action="store_true", help="structure-preserving tiny workload (debugging only)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-groups", type=int, default=10, help="oracle sample: groups of 16 buckets")
+    ap.add_argument("--cpu-groups", type=int, default=36,
+                    help="oracle sample: groups of 16 buckets spread over the set (36 groups = 63 %% of the default "
+                         "workload, about 12 s of single-thread oracle work)")
     ap.add_argument("--probe", action="store_true", help="also time the two-stream read probe")
     ap.add_argument("--no-check", action="store_true", help="skip the result checks (kernel experiments only)")
     ap.add_argument("--index-coding", action="store_true",
@@ -310,7 +312,7 @@ def main() -> int:
     probe_gbs = None
     if args.probe:
         nbytes = min(2 * N, 16 << 30) // 32768 * 32768
-        sink = torch.empty(int(srs._lib.srs_stream_probe_sink_words(nbytes)), dtype=torch.int32, device=dev)
+        sink = torch.empty(srs.stream_probe_sink_words(nbytes), dtype=torch.int32, device=dev)
         a = W0.flat.view(torch.int16)[: nbytes // 2]; b = W1.flat.view(torch.int16)[: nbytes // 2]
         for _ in range(2):
             ctx.stream_probe(a, b, sink)

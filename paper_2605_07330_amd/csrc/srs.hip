@@ -270,6 +270,73 @@ bool encoded_args_ok(const uint16_t *D, const int32_t *I_wide, const uint16_t *V
 }
 }  // namespace
 
+
+namespace {
+int extract_single(srs_ctx *ctx, void *old_snapshot, const void *new_w, uint64_t n, uint64_t bucket_elems,
+                   int32_t *I, uint16_t *V, uint32_t *counts, uint64_t cap, void *stream, bool cast) {
+    if (!ctx || bucket_elems == 0 || cap == 0 || n > kMaxIndexable || bucket_elems > kMaxIndexable) return SRS_ERR_INVALID;
+    if (n == 0) return SRS_OK;
+    if (!old_snapshot || !new_w || !I || !V || !counts) return SRS_ERR_INVALID;
+    if (((uintptr_t)old_snapshot | (uintptr_t)V) & 1u) return SRS_ERR_INVALID;
+    if ((uintptr_t)new_w & (cast ? 3u : 1u)) return SRS_ERR_INVALID;
+    if (((uintptr_t)I | (uintptr_t)counts) & 3u) return SRS_ERR_INVALID;
+    hipStream_t st = (hipStream_t)stream;
+    SRS_HIP(hipSetDevice(ctx->device));
+
+    const uint64_t T = ctx->tile_elems;
+    const uint64_t nb = (n + bucket_elems - 1) / bucket_elems;
+    const uint64_t tpb = (bucket_elems + T - 1) / T;
+    const uint64_t last_len = n - (nb - 1) * bucket_elems;
+    const uint64_t ntiles = (nb - 1) * tpb + (last_len + T - 1) / T;
+    if (ntiles > 0x7fffffffull) return SRS_ERR_INVALID;
+
+    if (nb > 0x7fffffffull) return SRS_ERR_INVALID;
+    const uint64_t group = ctx->group < nb ? ctx->group : nb;     // group * tpb <= ntiles + tpb
+
+    ExtractArgs a;
+    std::memset(&a, 0, sizeof(a));
+    int rc = prepare_extract(ctx, ntiles, nb, st, &a.epoch, &a.ticket_stride);
+    if (rc != SRS_OK) return rc;
+    a.old_w = (uint16_t *)old_snapshot; a.new_w = new_w; a.n = n;
+    a.be = (uint32_t)bucket_elems; a.tiles_per_bucket = (uint32_t)tpb;
+    a.nb = (uint32_t)nb; a.last_tiles = (uint32_t)((last_len + T - 1) / T); a.group = (uint32_t)group;
+    a.ntiles = (uint32_t)ntiles;
+    a.I = I; a.V = V; a.counts = counts; a.cap = cap;
+    a.status = ctx->status; a.tickets = ctx->tickets; a.flags = ctx->flags;
+    a.spin_limit = ctx->spin_limit;
+    return launch_extract<false>(ctx, ctx->tile_elems, a, st, cast);
+}
+}  // namespace
+
+namespace {
+int extract_multi(srs_ctx *ctx, srs_plan *plan, const srs_tensor_pair *t,
+                  int32_t *I, uint16_t *V, uint32_t *counts, uint64_t cap, void *stream, bool cast) {
+    if (!ctx || !plan || cap == 0 || plan->device != ctx->device) return SRS_ERR_INVALID;
+    if (plan->total == 0) return SRS_OK;
+    if (!t || !I || !V || !counts) return SRS_ERR_INVALID;
+    if (((uintptr_t)V & 1u) || (((uintptr_t)I | (uintptr_t)counts) & 3u)) return SRS_ERR_INVALID;
+    // numel is not known here any more, but a tensor with elements has at least one segment
+    for (uint32_t k = 0; k < plan->ntensors; ++k)
+        if (((uintptr_t)t[k].old_snapshot & 1u) || ((uintptr_t)t[k].new_w & (cast ? 3u : 1u))) return SRS_ERR_INVALID;
+    hipStream_t st = (hipStream_t)stream;
+    SRS_HIP(hipSetDevice(ctx->device));
+
+    int rc_up = upload_pair_pointers(plan, t, st);
+    if (rc_up != SRS_OK) return rc_up;
+
+    ExtractArgs a;
+    std::memset(&a, 0, sizeof(a));
+    int rc = prepare_extract(ctx, plan->ntiles, plan->nbuckets, st, &a.epoch, &a.ticket_stride);
+    if (rc != SRS_OK) return rc;
+    a.tiles = plan->d_tiles; a.ptrs = plan->d_pairs; a.ntiles = plan->ntiles;
+    a.wg_bucket = plan->d_wg_bucket; a.bucket_first = plan->d_bucket_first; a.nb = plan->nbuckets;
+    a.I = I; a.V = V; a.counts = counts; a.cap = cap;
+    a.status = ctx->status; a.tickets = ctx->tickets; a.flags = ctx->flags;
+    a.spin_limit = ctx->spin_limit;
+    return launch_extract<true>(ctx, plan->tile_elems, a, st, cast);
+}
+}  // namespace
+
 extern "C" {
 
 int srs_version(void) { return 100; }
@@ -350,42 +417,6 @@ int srs_status(srs_ctx *ctx, uint32_t *flags, void *stream) {
 // single tensor
 // ---------------------------------------------------------------------------------------------
 
-namespace {
-int extract_single(srs_ctx *ctx, void *old_snapshot, const void *new_w, uint64_t n, uint64_t bucket_elems,
-                   int32_t *I, uint16_t *V, uint32_t *counts, uint64_t cap, void *stream, bool cast) {
-    if (!ctx || bucket_elems == 0 || cap == 0 || n > kMaxIndexable || bucket_elems > kMaxIndexable) return SRS_ERR_INVALID;
-    if (n == 0) return SRS_OK;
-    if (!old_snapshot || !new_w || !I || !V || !counts) return SRS_ERR_INVALID;
-    if (((uintptr_t)old_snapshot | (uintptr_t)V) & 1u) return SRS_ERR_INVALID;
-    if ((uintptr_t)new_w & (cast ? 3u : 1u)) return SRS_ERR_INVALID;
-    if (((uintptr_t)I | (uintptr_t)counts) & 3u) return SRS_ERR_INVALID;
-    hipStream_t st = (hipStream_t)stream;
-    SRS_HIP(hipSetDevice(ctx->device));
-
-    const uint64_t T = ctx->tile_elems;
-    const uint64_t nb = (n + bucket_elems - 1) / bucket_elems;
-    const uint64_t tpb = (bucket_elems + T - 1) / T;
-    const uint64_t last_len = n - (nb - 1) * bucket_elems;
-    const uint64_t ntiles = (nb - 1) * tpb + (last_len + T - 1) / T;
-    if (ntiles > 0x7fffffffull) return SRS_ERR_INVALID;
-
-    if (nb > 0x7fffffffull) return SRS_ERR_INVALID;
-    const uint64_t group = ctx->group < nb ? ctx->group : nb;     // group * tpb <= ntiles + tpb
-
-    ExtractArgs a;
-    std::memset(&a, 0, sizeof(a));
-    int rc = prepare_extract(ctx, ntiles, nb, st, &a.epoch, &a.ticket_stride);
-    if (rc != SRS_OK) return rc;
-    a.old_w = (uint16_t *)old_snapshot; a.new_w = new_w; a.n = n;
-    a.be = (uint32_t)bucket_elems; a.tiles_per_bucket = (uint32_t)tpb;
-    a.nb = (uint32_t)nb; a.last_tiles = (uint32_t)((last_len + T - 1) / T); a.group = (uint32_t)group;
-    a.ntiles = (uint32_t)ntiles;
-    a.I = I; a.V = V; a.counts = counts; a.cap = cap;
-    a.status = ctx->status; a.tickets = ctx->tickets; a.flags = ctx->flags;
-    a.spin_limit = ctx->spin_limit;
-    return launch_extract<false>(ctx, ctx->tile_elems, a, st, cast);
-}
-}  // namespace
 
 int srs_extract(srs_ctx *ctx, void *old_snapshot, const void *new_w, uint64_t n, uint64_t bucket_elems,
                 int32_t *I, uint16_t *V, uint32_t *counts, uint64_t cap, void *stream) {
@@ -525,34 +556,6 @@ int srs_plan_destroy(srs_plan *p) {
     return SRS_OK;
 }
 
-namespace {
-int extract_multi(srs_ctx *ctx, srs_plan *plan, const srs_tensor_pair *t,
-                  int32_t *I, uint16_t *V, uint32_t *counts, uint64_t cap, void *stream, bool cast) {
-    if (!ctx || !plan || cap == 0 || plan->device != ctx->device) return SRS_ERR_INVALID;
-    if (plan->total == 0) return SRS_OK;
-    if (!t || !I || !V || !counts) return SRS_ERR_INVALID;
-    if (((uintptr_t)V & 1u) || (((uintptr_t)I | (uintptr_t)counts) & 3u)) return SRS_ERR_INVALID;
-    // numel is not known here any more, but a tensor with elements has at least one segment
-    for (uint32_t k = 0; k < plan->ntensors; ++k)
-        if (((uintptr_t)t[k].old_snapshot & 1u) || ((uintptr_t)t[k].new_w & (cast ? 3u : 1u))) return SRS_ERR_INVALID;
-    hipStream_t st = (hipStream_t)stream;
-    SRS_HIP(hipSetDevice(ctx->device));
-
-    int rc_up = upload_pair_pointers(plan, t, st);
-    if (rc_up != SRS_OK) return rc_up;
-
-    ExtractArgs a;
-    std::memset(&a, 0, sizeof(a));
-    int rc = prepare_extract(ctx, plan->ntiles, plan->nbuckets, st, &a.epoch, &a.ticket_stride);
-    if (rc != SRS_OK) return rc;
-    a.tiles = plan->d_tiles; a.ptrs = plan->d_pairs; a.ntiles = plan->ntiles;
-    a.wg_bucket = plan->d_wg_bucket; a.bucket_first = plan->d_bucket_first; a.nb = plan->nbuckets;
-    a.I = I; a.V = V; a.counts = counts; a.cap = cap;
-    a.status = ctx->status; a.tickets = ctx->tickets; a.flags = ctx->flags;
-    a.spin_limit = ctx->spin_limit;
-    return launch_extract<true>(ctx, plan->tile_elems, a, st, cast);
-}
-}  // namespace
 
 int srs_extract_multi(srs_ctx *ctx, srs_plan *plan, const srs_tensor_pair *t,
                       int32_t *I, uint16_t *V, uint32_t *counts, uint64_t cap, void *stream) {

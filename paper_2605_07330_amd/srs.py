@@ -133,6 +133,10 @@ def plan_layout(numel: Sequence[int], bucket_elems: int, tile_elems: int = 16384
             "wg_bucket": wg_bucket}
 
 
+def stream_probe_sink_words(nbytes: int) -> int:
+    return int(_lib.srs_stream_probe_sink_words(nbytes))
+
+
 def anchor_count(nbuckets: int, cap: int) -> int:
     return int(_lib.srs_anchor_count(nbuckets, cap))
 
