@@ -152,6 +152,29 @@ int srs_extract_cast_multi(srs_ctx *ctx, srs_plan *plan, const srs_tensor_pair *
                            int32_t *I, uint16_t *V, uint32_t *counts, uint64_t cap, void *stream);
 
 /*
+ * Cumulative changed-index set: Alg. 1 as printed.  Between two synchronisations the Trainer takes T optimizer
+ * steps; after each cast it forms I_t = { i : W[i] != W_prev[i] } and accumulates I_cum <- I_cum U I_t; at the
+ * synchronisation Alg. 2 sends V = W[I_cum] with the CURRENT values.  I_cum is a superset of the exact delta
+ * (an element that changed and changed back stays in it), which costs payload but not correctness: the receiver
+ * ends bit-identical.  No snapshot of the last synchronised state is kept in this mode.
+ *
+ * The set is a device bitmap over the packed positions g of the plan's tensor list: bit (g & 31) of 32-bit word
+ * g >> 5, srs_bitmap_words(total) words, cleared by the caller (e.g. hipMemsetAsync) after each synchronisation.
+ *   srs_mark_multi       bitmap |= (t[k].new_w != t[k].old_snapshot), both BF16: one step, two versions at hand.
+ *   srs_cast_mark_multi  the Trainer's own step without the clone: t[k].old_snapshot is the BF16 model parameters
+ *                        (in/out), t[k].new_w the FP32 master weights; parameters <- round_BF16(master) and every
+ *                        element whose pattern changed is marked.
+ *   srs_extract_marked_multi  the payload of the marked positions, ascending per bucket, with the current values
+ *                        of t[k].weights; layout, capacity rule and flags as srs_extract_multi.  Reads the bitmap
+ *                        and only those weights whose bit is set.
+ */
+uint64_t srs_bitmap_words(uint64_t total_elems);
+int srs_mark_multi(srs_ctx *ctx, srs_plan *plan, const srs_tensor_pair *t, uint32_t *bitmap, void *stream);
+int srs_cast_mark_multi(srs_ctx *ctx, srs_plan *plan, const srs_tensor_pair *t, uint32_t *bitmap, void *stream);
+int srs_extract_marked_multi(srs_ctx *ctx, srs_plan *plan, const srs_tensor *t, const uint32_t *bitmap,
+                             int32_t *I, uint16_t *V, uint32_t *counts, uint64_t cap, void *stream);
+
+/*
  * Lossless index coding (Sec. 3.3, "Index delta encoding"): the indices of a payload are sorted, so their
  * first differences (with a zero prepended) are stored instead; when every difference of a bucket is below
  * 2^15 they fit 16 bits (b_i = 2 B instead of 4 B), otherwise the bucket keeps its 32-bit indices.

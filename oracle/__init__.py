@@ -73,6 +73,13 @@ def _load():
         lib.srs_oracle_extract_cast_multi.restype = C.c_int
         lib.srs_oracle_extract_cast_multi.argtypes = [pp, C.POINTER(u32p), u64p, C.c_uint32, C.c_uint64,
                                                       i32p, u16p_, u32p, C.c_uint64]
+        lib.srs_oracle_mark_multi.restype = C.c_int
+        lib.srs_oracle_mark_multi.argtypes = [pp, pp, u64p, C.c_uint32, u32p]
+        lib.srs_oracle_cast_mark_multi.restype = C.c_int
+        lib.srs_oracle_cast_mark_multi.argtypes = [pp, C.POINTER(u32p), u64p, C.c_uint32, u32p]
+        lib.srs_oracle_extract_marked_multi.restype = C.c_int
+        lib.srs_oracle_extract_marked_multi.argtypes = [pp, u64p, C.c_uint32, C.c_uint64, u32p, i32p, u16p_, u32p,
+                                                        C.c_uint64]
         lib.srs_oracle_num_buckets.restype = C.c_uint64
         lib.srs_oracle_num_buckets.argtypes = [u64p, C.c_uint32, C.c_uint64]
         _lib = lib
@@ -321,4 +328,58 @@ def extract_cast_multi(w: Sequence[np.ndarray], master: Sequence[np.ndarray], nu
                                            _p(V, C.c_uint16), _p(counts, C.c_uint32), cap)
     if rc < 0:
         raise ValueError(f"srs_oracle_extract_cast_multi: bad argument ({rc})")
+    return I, V, counts, rc
+
+
+def bitmap_words(total: int) -> int:
+    return (total + 31) // 32
+
+
+def _master_ptrs(ms):
+    T = C.POINTER(C.c_uint32)
+    mp = (T * max(len(ms), 1))()
+    for k, a in enumerate(ms):
+        mp[k] = _p(a, C.c_uint32)
+    return mp
+
+
+def mark_multi(prev: Sequence[np.ndarray], cur: Sequence[np.ndarray], numel: Sequence[int], bitmap: np.ndarray) -> None:
+    """bitmap |= (cur != prev): one optimizer step of Alg. 1's index accumulation."""
+    lib = _load()
+    for a in list(prev) + list(cur):
+        _u16(a)
+    ne = np.asarray(list(numel), np.uint64)
+    if bitmap.dtype != np.uint32 or bitmap.size < bitmap_words(int(ne.sum())):
+        raise TypeError("bitmap: uint32 array of ceil(total/32) words")
+    lib.srs_oracle_mark_multi(_ptr_array(prev), _ptr_array(cur), _p(ne, C.c_uint64), len(numel), _p(bitmap, C.c_uint32))
+
+
+def cast_mark_multi(w: Sequence[np.ndarray], master: Sequence[np.ndarray], numel: Sequence[int], bitmap: np.ndarray) -> None:
+    """w <- round_bf16(master); bitmap |= changed (Alg. 1 lines 4-7 without the clone)."""
+    lib = _load()
+    for a in w:
+        _u16(a, True)
+    ms = [_f32bits(a) for a in master]
+    ne = np.asarray(list(numel), np.uint64)
+    if bitmap.dtype != np.uint32 or bitmap.size < bitmap_words(int(ne.sum())):
+        raise TypeError("bitmap: uint32 array of ceil(total/32) words")
+    lib.srs_oracle_cast_mark_multi(_ptr_array(w), _master_ptrs(ms), _p(ne, C.c_uint64), len(numel), _p(bitmap, C.c_uint32))
+
+
+def extract_marked_multi(w: Sequence[np.ndarray], numel: Sequence[int], be: int, bitmap: np.ndarray,
+                         cap: int | None = None) -> Tuple[np.ndarray, np.ndarray, np.ndarray, int]:
+    """Per-bucket payload of the marked positions with the current values (Alg. 2 over the cumulative set)."""
+    lib = _load()
+    for a in w:
+        _u16(a)
+    ne = np.asarray(list(numel), np.uint64)
+    nb = num_buckets(int(ne.sum()), be) if be else 0
+    cap = be if cap is None else cap
+    I = np.full((nb, max(cap, 0)), -1, np.int32)
+    V = np.full((nb, max(cap, 0)), 0xFFFF, np.uint16)
+    counts = np.zeros(nb, np.uint32)
+    rc = lib.srs_oracle_extract_marked_multi(_ptr_array(w), _p(ne, C.c_uint64), len(numel), be, _p(bitmap, C.c_uint32),
+                                             _p(I, C.c_int32), _p(V, C.c_uint16), _p(counts, C.c_uint32), cap)
+    if rc < 0:
+        raise ValueError("srs_oracle_extract_marked_multi: bad argument")
     return I, V, counts, rc

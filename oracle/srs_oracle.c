@@ -398,3 +398,64 @@ int srs_oracle_extract_cast_multi(uint16_t *const *w, const uint32_t *const *mas
     for (uint64_t b = 0; b < nb; ++b) if (counts[b] > cap) overflowed += 1;
     return overflowed;
 }
+
+/* ------------------------------------------------------------------------------------------------
+ * Cumulative changed-index set (Alg. 1 as printed): over the optimizer steps t = 1..T between two
+ * synchronisations, I_t = { i : W[i] != W_prev[i] } is formed after every cast and accumulated,
+ * I_cum <- I_cum U I_t; at the synchronisation Alg. 2 sends V = W[I_cum] with the CURRENT values.  I_cum is
+ * a superset of the exact delta against the last synchronised state (an element that changed and changed
+ * back stays in it); the receiver still ends bit-identical because the values sent are the current ones.
+ *
+ * The set is kept as one bit per packed position g of the tensor list: bit (g & 31) of word g >> 5.
+ * ------------------------------------------------------------------------------------------------ */
+
+/* One step with both parameter versions at hand: bitmap |= (cur != prev), element by element. */
+int srs_oracle_mark_multi(const uint16_t *const *prev, const uint16_t *const *cur, const uint64_t *numel,
+                          uint32_t ntensors, uint32_t *bitmap)
+{
+    uint64_t g = 0;
+    for (uint32_t k = 0; k < ntensors; ++k) {
+        for (uint64_t j = 0; j < numel[k]; ++j, ++g)
+            if (prev[k][j] != cur[k][j]) bitmap[g >> 5] |= 1u << (g & 31);
+    }
+    return SRS_ORACLE_OK;
+}
+
+/* One step as the Trainer runs it (lines 4-7 of Alg. 1 without the clone): w <- round_BF16(master), and
+ * every element whose pattern changed is added to the set. */
+int srs_oracle_cast_mark_multi(uint16_t *const *w, const uint32_t *const *master_bits, const uint64_t *numel,
+                               uint32_t ntensors, uint32_t *bitmap)
+{
+    uint64_t g = 0;
+    for (uint32_t k = 0; k < ntensors; ++k) {
+        for (uint64_t j = 0; j < numel[k]; ++j, ++g) {
+            uint16_t r = srs_oracle_round_bf16(master_bits[k][j]);
+            if (r != w[k][j]) { bitmap[g >> 5] |= 1u << (g & 31); w[k][j] = r; }
+        }
+    }
+    return SRS_ORACLE_OK;
+}
+
+/* The synchronisation: per bucket, the marked positions in ascending order with the current values
+ * (Alg. 2, V = W[I]).  Same payload layout and capacity rule as srs_oracle_extract_multi. */
+int srs_oracle_extract_marked_multi(const uint16_t *const *w, const uint64_t *numel, uint32_t ntensors, uint64_t be,
+                                    const uint32_t *bitmap, int32_t *I, uint16_t *V, uint32_t *counts, uint64_t cap)
+{
+    if (be == 0 || cap == 0 || be > 0x7fffffffULL) return SRS_ORACLE_BAD_ARG;
+    uint64_t total = 0;
+    for (uint32_t k = 0; k < ntensors; ++k) total += numel[k];
+    uint64_t nb = (total + be - 1) / be;
+    for (uint64_t b = 0; b < nb; ++b) counts[b] = 0;
+    uint64_t g = 0;
+    for (uint32_t k = 0; k < ntensors; ++k) {
+        for (uint64_t j = 0; j < numel[k]; ++j, ++g) {
+            if (!((bitmap[g >> 5] >> (g & 31)) & 1u)) continue;
+            uint64_t b = g / be, c = counts[b];
+            if (c < cap) { I[b * cap + c] = (int32_t)(g - b * be); V[b * cap + c] = w[k][j]; }
+            counts[b] = (uint32_t)(c + 1);
+        }
+    }
+    int overflowed = 0;
+    for (uint64_t b = 0; b < nb; ++b) if (counts[b] > cap) overflowed += 1;
+    return overflowed;
+}

@@ -45,6 +45,7 @@ struct srs_plan {
     uint32_t ntensors = 0, nbuckets = 0, nsegments = 0, ntiles = 0, tile_elems = 0;
     uint32_t max_bucket_tiles = 0;          // most tiles in any one bucket
     TileDesc *d_tiles = nullptr;
+    uint64_t *d_tensor_base = nullptr;      // [ntensors] packed position of each tensor's element 0
     uint32_t *d_wg_bucket = nullptr;        // [ntiles] bucket served by each workgroup of extract
     uint32_t *d_bucket_first = nullptr;     // [nbuckets+1] first tile of each bucket
     SegDesc *d_segs = nullptr;
@@ -111,11 +112,12 @@ int prepare_extract(srs_ctx *ctx, uint64_t ntiles, uint64_t nb, hipStream_t st, 
 }
 
 template <bool MULTI>
-int launch_extract(const srs_ctx *ctx, uint32_t tile_elems, const ExtractArgs &a, hipStream_t st, bool cast) {
+int launch_extract(const srs_ctx *ctx, uint32_t tile_elems, const ExtractArgs &a, hipStream_t st, int src) {
     const dim3 grid(a.ntiles), block(kThreads);
 #define SRS_LAUNCH(VV)                                                                                                \
     do {                                                                                                              \
-        if (cast) hipLaunchKernelGGL((extract_kernel<VV, MULTI, 4, true>), grid, block, 0, st, a);                    \
+        if (src == kSrcFp32) hipLaunchKernelGGL((extract_kernel<VV, MULTI, 4, kSrcFp32>), grid, block, 0, st, a);     \
+        else if (src == kSrcBitmap) hipLaunchKernelGGL((extract_kernel<VV, MULTI, 0, kSrcBitmap>), grid, block, 0, st, a); \
         else if (ctx->refresh_group == 8) hipLaunchKernelGGL((extract_kernel<VV, MULTI, 8>), grid, block, 0, st, a);  \
         else if (ctx->refresh_group == 4) hipLaunchKernelGGL((extract_kernel<VV, MULTI, 4>), grid, block, 0, st, a);  \
         else hipLaunchKernelGGL((extract_kernel<VV, MULTI, 0>), grid, block, 0, st, a);                               \
@@ -304,13 +306,16 @@ int extract_single(srs_ctx *ctx, void *old_snapshot, const void *new_w, uint64_t
     a.I = I; a.V = V; a.counts = counts; a.cap = cap;
     a.status = ctx->status; a.tickets = ctx->tickets; a.flags = ctx->flags;
     a.spin_limit = ctx->spin_limit;
-    return launch_extract<false>(ctx, ctx->tile_elems, a, st, cast);
+    return launch_extract<false>(ctx, ctx->tile_elems, a, st, cast ? kSrcFp32 : kSrcBf16);
 }
 }  // namespace
 
 namespace {
 int extract_multi(srs_ctx *ctx, srs_plan *plan, const srs_tensor_pair *t,
-                  int32_t *I, uint16_t *V, uint32_t *counts, uint64_t cap, void *stream, bool cast) {
+                  int32_t *I, uint16_t *V, uint32_t *counts, uint64_t cap, void *stream, int src,
+                  const uint32_t *bitmap = nullptr) {
+    const bool cast = (src == kSrcFp32);
+    if (src == kSrcBitmap && (!bitmap || ((uintptr_t)bitmap & 3u))) return SRS_ERR_INVALID;
     if (!ctx || !plan || cap == 0 || plan->device != ctx->device) return SRS_ERR_INVALID;
     if (plan->total == 0) return SRS_OK;
     if (!t || !I || !V || !counts) return SRS_ERR_INVALID;
@@ -333,7 +338,8 @@ int extract_multi(srs_ctx *ctx, srs_plan *plan, const srs_tensor_pair *t,
     a.I = I; a.V = V; a.counts = counts; a.cap = cap;
     a.status = ctx->status; a.tickets = ctx->tickets; a.flags = ctx->flags;
     a.spin_limit = ctx->spin_limit;
-    return launch_extract<true>(ctx, plan->tile_elems, a, st, cast);
+    a.bitmap = const_cast<uint32_t *>(bitmap); a.bitmap_words = (plan->total + 31) / 32; a.tensor_base = plan->d_tensor_base;
+    return launch_extract<true>(ctx, plan->tile_elems, a, st, src);
 }
 }  // namespace
 
@@ -504,6 +510,9 @@ int srs_plan_create(srs_ctx *ctx, const uint64_t *numel, uint32_t ntensors, uint
     ok = ok && upload((void **)&p->d_seg_begin, seg_begin.data(), seg_begin.size() * sizeof(uint32_t));
     ok = ok && upload((void **)&p->d_bucket_first, bucket_first.data(), bucket_first.size() * sizeof(uint32_t));
     ok = ok && upload((void **)&p->d_wg_bucket, wg_bucket.empty() ? nullptr : wg_bucket.data(), wg_bucket.size() * sizeof(uint32_t));
+    std::vector<uint64_t> tensor_base((size_t)ntensors + 1, 0);
+    for (uint32_t k = 0; k < ntensors; ++k) tensor_base[k + 1] = tensor_base[k] + numel[k];
+    ok = ok && upload((void **)&p->d_tensor_base, tensor_base.data(), tensor_base.size() * sizeof(uint64_t));
     ok = ok && upload((void **)&p->d_pairs, nullptr, (size_t)ntensors * sizeof(PtrPair));
     ok = ok && upload((void **)&p->d_wptrs, nullptr, (size_t)ntensors * sizeof(uint16_t *));
     ok = ok && hipDeviceSynchronize() == hipSuccess;
@@ -550,6 +559,7 @@ int srs_plan_destroy(srs_plan *p) {
     if (p->d_seg_begin) (void)hipFree(p->d_seg_begin);
     if (p->d_bucket_first) (void)hipFree(p->d_bucket_first);
     if (p->d_wg_bucket) (void)hipFree(p->d_wg_bucket);
+    if (p->d_tensor_base) (void)hipFree(p->d_tensor_base);
     if (p->d_pairs) (void)hipFree(p->d_pairs);
     if (p->d_wptrs) (void)hipFree(p->d_wptrs);
     delete p;
@@ -559,12 +569,12 @@ int srs_plan_destroy(srs_plan *p) {
 
 int srs_extract_multi(srs_ctx *ctx, srs_plan *plan, const srs_tensor_pair *t,
                       int32_t *I, uint16_t *V, uint32_t *counts, uint64_t cap, void *stream) {
-    return extract_multi(ctx, plan, t, I, V, counts, cap, stream, false);
+    return extract_multi(ctx, plan, t, I, V, counts, cap, stream, kSrcBf16);
 }
 
 int srs_extract_cast_multi(srs_ctx *ctx, srs_plan *plan, const srs_tensor_pair *t,
                            int32_t *I, uint16_t *V, uint32_t *counts, uint64_t cap, void *stream) {
-    return extract_multi(ctx, plan, t, I, V, counts, cap, stream, true);
+    return extract_multi(ctx, plan, t, I, V, counts, cap, stream, kSrcFp32);
 }
 
 int srs_apply_multi(srs_ctx *ctx, srs_plan *plan, const srs_tensor *t,
@@ -592,6 +602,68 @@ int srs_apply_multi(srs_ctx *ctx, srs_plan *plan, const srs_tensor *t,
     hipLaunchKernelGGL((apply_kernel<true>), dim3((uint32_t)((uint64_t)plan->nbuckets * cpb)), dim3(kThreads), 0, st, a);
     SRS_HIP(hipGetLastError());
     return SRS_OK;
+}
+
+// ---------------------------------------------------------------------------------------------
+// cumulative changed-index set (Alg. 1 as printed)
+// ---------------------------------------------------------------------------------------------
+
+uint64_t srs_bitmap_words(uint64_t total_elems) { return (total_elems + 31) / 32; }
+
+static int mark_common(srs_ctx *ctx, srs_plan *plan, const srs_tensor_pair *t, uint32_t *bitmap, void *stream, bool cast) {
+    if (!ctx || !plan || plan->device != ctx->device) return SRS_ERR_INVALID;
+    if (plan->total == 0) return SRS_OK;
+    if (!t || !bitmap || ((uintptr_t)bitmap & 3u)) return SRS_ERR_INVALID;
+    for (uint32_t k = 0; k < plan->ntensors; ++k)
+        if (((uintptr_t)t[k].old_snapshot & 1u) || ((uintptr_t)t[k].new_w & (cast ? 3u : 1u))) return SRS_ERR_INVALID;
+    hipStream_t st = (hipStream_t)stream;
+    SRS_HIP(hipSetDevice(ctx->device));
+    int rc = upload_pair_pointers(plan, t, st);
+    if (rc != SRS_OK) return rc;
+    ExtractArgs a;
+    std::memset(&a, 0, sizeof(a));
+    a.tiles = plan->d_tiles; a.ptrs = plan->d_pairs; a.ntiles = plan->ntiles;
+    a.bitmap = bitmap; a.bitmap_words = (plan->total + 31) / 32; a.tensor_base = plan->d_tensor_base;
+    const dim3 grid(plan->ntiles), block(kThreads);
+#define SRS_MARK(VV)                                                                   \
+    do {                                                                               \
+        if (cast) hipLaunchKernelGGL((mark_kernel<VV, true>), grid, block, 0, st, a);  \
+        else hipLaunchKernelGGL((mark_kernel<VV, false>), grid, block, 0, st, a);      \
+    } while (0)
+    switch (plan->tile_elems) {
+        case 4096: SRS_MARK(2); break;
+        case 8192: SRS_MARK(4); break;
+        case 16384: SRS_MARK(8); break;
+        case 32768: SRS_MARK(16); break;
+        default: return SRS_ERR_INVALID;
+    }
+#undef SRS_MARK
+    SRS_HIP(hipGetLastError());
+    return SRS_OK;
+}
+
+int srs_mark_multi(srs_ctx *ctx, srs_plan *plan, const srs_tensor_pair *t, uint32_t *bitmap, void *stream) {
+    return mark_common(ctx, plan, t, bitmap, stream, false);
+}
+
+int srs_cast_mark_multi(srs_ctx *ctx, srs_plan *plan, const srs_tensor_pair *t, uint32_t *bitmap, void *stream) {
+    return mark_common(ctx, plan, t, bitmap, stream, true);
+}
+
+int srs_extract_marked_multi(srs_ctx *ctx, srs_plan *plan, const srs_tensor *t, const uint32_t *bitmap,
+                             int32_t *I, uint16_t *V, uint32_t *counts, uint64_t cap, void *stream) {
+    if (!ctx || !plan || cap == 0) return SRS_ERR_INVALID;
+    if (plan->total == 0) return SRS_OK;
+    if (!t) return SRS_ERR_INVALID;
+    // the weights go in as the "new" side of a pair table; there is no snapshot in this mode
+    std::vector<srs_tensor_pair> pairs;
+    try {
+        pairs.resize(plan->ntensors);
+    } catch (const std::bad_alloc &) {
+        return SRS_ERR_NOMEM;
+    }
+    for (uint32_t k = 0; k < plan->ntensors; ++k) { pairs[k].old_snapshot = nullptr; pairs[k].new_w = t[k].weights; }
+    return extract_multi(ctx, plan, pairs.data(), I, V, counts, cap, stream, kSrcBitmap, bitmap);
 }
 
 // ---------------------------------------------------------------------------------------------

@@ -65,6 +65,8 @@ struct ExtractArgs {
     uint32_t ticket_stride;
     uint32_t *flags;
     uint32_t epoch; uint32_t spin_limit;
+    // cumulative changed-index set: one bit per packed position (bit g&31 of word g>>5)
+    uint32_t *bitmap; uint64_t bitmap_words; const uint64_t *tensor_base;   // packed position of each tensor's element 0
 };
 
 struct ApplyArgs {
@@ -243,9 +245,26 @@ __device__ __forceinline__ uint32_t look_back(const ExtractArgs &a, uint32_t til
 // CAST: `new` is not a BF16 buffer but the FP32 master weights; each element is rounded to BF16
 // (nearest even, NaN -> 0x7FC0) on the fly and `old` is the model-parameter buffer itself: the cast-and-
 // copy of Alg. 1 fused with its diff, so that no snapshot exists at all.
-template <int V, bool MULTI, int RG, bool CAST = false>
+// SRC = kSrcBitmap: there is no `old` at all; the change masks are read from the cumulative bitmap of
+// Alg. 1 (mark_kernel builds it step by step) and `new` is the current weights, loaded only where a bit
+// is set: Alg. 2's V = W[I] over the accumulated index set.
+constexpr int kSrcBf16 = 0, kSrcFp32 = 1, kSrcBitmap = 2;
+
+// the 8 mask bits of packed positions g .. g+7, of which only the first `nbits` exist
+__device__ __forceinline__ uint32_t bitmap_bits8(const uint32_t *bitmap, uint64_t words, uint64_t g, uint32_t nbits) {
+    const uint64_t w = g >> 5;
+    const uint32_t sh = (uint32_t)(g & 31u);
+    const uint32_t lo = bitmap[w];
+    const uint32_t hi = (sh > 24u && w + 1 < words) ? bitmap[w + 1] : 0u;
+    const uint32_t bits = (uint32_t)((((unsigned long long)hi << 32) | lo) >> sh) & 0xFFu;
+    return nbits >= 8u ? bits : (bits & ((1u << nbits) - 1u));
+}
+
+template <int V, bool MULTI, int RG, int SRC = kSrcBf16>
 __global__ __launch_bounds__(kThreads) void extract_kernel(const ExtractArgs a) {
     constexpr bool NT = false;
+    constexpr bool CAST = (SRC == kSrcFp32);
+    constexpr bool MARKED = (SRC == kSrcBitmap);
     static_assert(V % 2 == 0, "counts are scanned in packed pairs");
     constexpr uint32_t TILE = (uint32_t)V * kUnit;
     __shared__ uint32_t s_ticket;
@@ -290,12 +309,14 @@ __global__ __launch_bounds__(kThreads) void extract_kernel(const ExtractArgs a) 
     // ---- where this tile lives
     uint32_t bucket_off, len, idx_base;
     uint16_t *po; const void *pn_raw; uint64_t pn_off;      // new weights: base pointer and element offset
+    uint64_t g0 = 0;                                        // packed position of the tile's first element (MARKED)
     if (MULTI) {
         const TileDesc d = a.tiles[tile];
         const PtrPair p = a.ptrs[d.tensor];
         po = p.old_w + d.tensor_off; pn_raw = p.new_w; pn_off = d.tensor_off;
         bucket_off = d.bucket_off; len = d.len;
         idx_base = bucket_off;                          // index = position inside the bucket
+        if (MARKED) g0 = a.tensor_base[d.tensor] + d.tensor_off;
     } else {
         const uint64_t b0 = (uint64_t)bucket * a.be;
         const uint32_t blen = (uint32_t)((a.n - b0 < a.be) ? (a.n - b0) : a.be);
@@ -303,6 +324,7 @@ __global__ __launch_bounds__(kThreads) void extract_kernel(const ExtractArgs a) 
         len = (blen - bucket_off < TILE) ? (blen - bucket_off) : TILE;
         po = a.old_w + b0 + bucket_off; pn_raw = a.new_w; pn_off = b0 + bucket_off;
         idx_base = (uint32_t)(b0 + bucket_off);         // index = tensor-flat position
+        if (MARKED) g0 = b0 + bucket_off;
     }
 
     // ---- stream the tile.  Layout: wave w owns elements [w*V*512, (w+1)*V*512); inside it vector j
@@ -313,8 +335,24 @@ __global__ __launch_bounds__(kThreads) void extract_kernel(const ExtractArgs a) 
     const uint32_t *const pf = reinterpret_cast<const uint32_t *>(pn_raw) + pn_off;
     const uint16_t *const pn = reinterpret_cast<const uint16_t *>(pn_raw) + pn_off;
     const bool aligned = CAST ? (((((uintptr_t)po) | ((uintptr_t)pf)) & 15u) == 0)
+                     : MARKED ? ((((uintptr_t)pn) & 15u) == 0)
                               : (((((uintptr_t)po) | ((uintptr_t)pn)) & 15u) == 0);
-    if (aligned && len == TILE) {
+    uint32_t m[V];
+    if (MARKED) {
+        // masks from the bitmap; weights are fetched only where a bit is set
+#pragma unroll
+        for (int j = 0; j < V; ++j) {
+            const uint32_t e = e0 + j * 512;
+            m[j] = (e < len) ? bitmap_bits8(a.bitmap, a.bitmap_words, g0 + e, len - e) : 0u;
+        }
+#pragma unroll
+        for (int j = 0; j < V; ++j) {
+            const uint32_t e = e0 + j * 512;
+            const u32x4 zero = {0, 0, 0, 0};
+            xn[j] = zero; xo[j] = zero;
+            if (m[j]) xn[j] = (aligned && e + 8 <= len) ? load16<false>(pn + e) : load8_guarded(pn, e, len);
+        }
+    } else if (aligned && len == TILE) {
         if (CAST) {
             u32x4 f0[V], f1[V];
 #pragma unroll
@@ -348,13 +386,14 @@ __global__ __launch_bounds__(kThreads) void extract_kernel(const ExtractArgs a) 
     }
 
     // ---- change masks and their counts
-    uint32_t m[V];
     uint32_t pk[V / 2];
+    if (!MARKED) {
 #pragma unroll
-    for (int j = 0; j < V; ++j) m[j] = diff_mask8(xo[j], xn[j]);
+        for (int j = 0; j < V; ++j) m[j] = diff_mask8(xo[j], xn[j]);
+    }
 
     // ---- snapshot refresh of full tiles, RG lanes (RG*16 bytes) at a time
-    const bool group_refresh = (RG > 0) && aligned && len == TILE;      // uniform
+    const bool group_refresh = !MARKED && (RG > 0) && aligned && len == TILE;      // uniform
     if (group_refresh) {
 #pragma unroll
         for (int j = 0; j < V; ++j) {
@@ -438,12 +477,74 @@ __global__ __launch_bounds__(kThreads) void extract_kernel(const ExtractArgs a) 
             const uint64_t r = (uint64_t)excl + r0 + k;
             if (local < len) {                      // always true for a correct scan; keeps stores in bounds
                 if (r < a.cap) { Ib[r] = (int32_t)(idx_base + local); Vb[r] = val; }
-                if (!group_refresh) po[local] = val;    // snapshot refresh: W_prev <- W at changed positions
+                if (!MARKED && !group_refresh) po[local] = val;   // snapshot refresh: W_prev <- W at changed positions
             }
         }
         __syncthreads();
     }
 
+}
+
+// ---------------------------------------------------------------------------------------------
+// mark_kernel: one optimizer step of Alg. 1's index accumulation, I_cum <- I_cum U { i : W[i] != W_prev[i] },
+// kept as a bitmap over packed positions.  CAST = false compares two BF16 versions; CAST = true is the
+// Trainer's own sequence without the clone: W <- round_BF16(master) and the elements whose pattern changed
+// are marked.  One workgroup per tile of the plan; no chain, no ticket: tiles are independent here.
+// ---------------------------------------------------------------------------------------------
+template <int V, bool CAST>
+__global__ __launch_bounds__(kThreads) void mark_kernel(const ExtractArgs a) {
+    constexpr uint32_t TILE = (uint32_t)V * kUnit;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    if (blockIdx.x >= a.ntiles) return;
+    const TileDesc d = a.tiles[blockIdx.x];
+    const PtrPair p = a.ptrs[d.tensor];
+    uint16_t *const po = p.old_w + d.tensor_off;
+    const uint32_t *const pf = reinterpret_cast<const uint32_t *>(p.new_w) + d.tensor_off;
+    const uint16_t *const pn = reinterpret_cast<const uint16_t *>(p.new_w) + d.tensor_off;
+    const uint32_t len = d.len;
+    const uint64_t g0 = a.tensor_base[d.tensor] + d.tensor_off;
+    const uint32_t e0 = (uint32_t)wave * (V * 512u) + (uint32_t)lane * 8u;
+    const bool aligned = CAST ? (((((uintptr_t)po) | ((uintptr_t)pf)) & 15u) == 0)
+                              : (((((uintptr_t)po) | ((uintptr_t)pn)) & 15u) == 0);
+    const bool full = aligned && len == TILE;
+    u32x4 xo[V], xn[V];
+#pragma unroll
+    for (int j = 0; j < V; ++j) {
+        const uint32_t e = e0 + j * 512;
+        if (full || (aligned && e + 8 <= len)) {
+            xo[j] = load16<false>(po + e);
+            if (CAST) xn[j] = round8_bf16(*reinterpret_cast<const u32x4 *>(pf + e), *reinterpret_cast<const u32x4 *>(pf + e + 4));
+            else xn[j] = load16<false>(pn + e);
+        } else {
+            xo[j] = load8_guarded(po, e, len);
+            xn[j] = CAST ? load8_guarded_cast(pf, e, len) : load8_guarded(pn, e, len);
+        }
+    }
+#pragma unroll
+    for (int j = 0; j < V; ++j) {
+        const uint32_t e = e0 + j * 512;
+        const uint32_t m = diff_mask8(xo[j], xn[j]);
+        if (CAST) {                                           // write the cast back where it changed something
+            if (full) {
+                const unsigned long long changed = __ballot(m != 0);
+                if ((uint32_t)(changed >> (lane & ~3)) & 0xFu) *reinterpret_cast<u32x4 *>(po + e) = xn[j];
+            } else if (m) {
+                uint32_t mm = m;
+                while (mm) {
+                    const uint32_t k = (uint32_t)__builtin_ctz(mm);
+                    mm &= mm - 1u;
+                    po[e + k] = (uint16_t)pattern_at(xn[j], k);       // k < len - e: guarded loads read 0 == 0 beyond len
+                }
+            }
+        }
+        if (m) {
+            const uint64_t g = g0 + e;
+            const uint32_t sh = (uint32_t)(g & 31u);
+            atomicOr(a.bitmap + (g >> 5), m << sh);
+            const uint32_t spill = (sh > 24u) ? (m >> (32u - sh)) : 0u;       // bits that belong to the next word
+            if (spill) atomicOr(a.bitmap + (g >> 5) + 1, spill);
+        }
+    }
 }
 
 // ---------------------------------------------------------------------------------------------

@@ -35,6 +35,7 @@ EXPORTS = [
     "srs_anchor_count", "srs_encode_indices", "srs_apply_encoded", "srs_apply_multi_encoded",
     "srs_route", "srs_pack_dense_multi", "srs_unpack_dense_multi",
     "srs_extract_cast", "srs_extract_cast_multi", "srs_plan_layout",
+    "srs_bitmap_words", "srs_mark_multi", "srs_cast_mark_multi", "srs_extract_marked_multi",
 ]
 
 
@@ -73,11 +74,16 @@ _lib.srs_extract_cast.argtypes = [_vp, _vp, _vp, _u64, _u64, _vp, _vp, _vp, _u64
 _lib.srs_extract_cast_multi.argtypes = [_vp, _vp, C.POINTER(TensorPair), _vp, _vp, _vp, _u64, _vp]
 _lib.srs_plan_layout.argtypes = [C.POINTER(_u64), C.c_uint32, _u64, C.c_uint32, C.c_uint32, _u32p, _u32p, _u32p,
                                  _vp, _vp, _vp, _vp, _vp]
+_lib.srs_bitmap_words.argtypes = [_u64]
+_lib.srs_bitmap_words.restype = _u64
+_lib.srs_mark_multi.argtypes = [_vp, _vp, C.POINTER(TensorPair), _vp, _vp]
+_lib.srs_cast_mark_multi.argtypes = [_vp, _vp, C.POINTER(TensorPair), _vp, _vp]
+_lib.srs_extract_marked_multi.argtypes = [_vp, _vp, C.POINTER(Tensor), _vp, _vp, _vp, _vp, _u64, _vp]
 _lib.srs_route.argtypes = [_vp, _vp, C.c_uint32, _u64, _u64, _u64, C.c_uint32, C.c_uint32, _vp, _vp, _vp, _vp, _vp]
 _lib.srs_pack_dense_multi.argtypes = [_vp, _vp, C.POINTER(TensorPair), _vp, _vp, C.c_uint32, _vp, _vp]
 _lib.srs_unpack_dense_multi.argtypes = [_vp, _vp, C.POINTER(Tensor), _vp, _vp, C.c_uint32, _vp, _vp]
 for _n in EXPORTS:
-    if _n not in ("srs_strerror", "srs_stream_probe_sink_words", "srs_anchor_count"):
+    if _n not in ("srs_strerror", "srs_stream_probe_sink_words", "srs_anchor_count", "srs_bitmap_words"):
         getattr(_lib, _n).restype = C.c_int
 
 
@@ -131,6 +137,10 @@ def plan_layout(numel: Sequence[int], bucket_elems: int, tile_elems: int = 16384
                                 wg_bucket.ctypes.data), "srs_plan_layout")
     return {"nbuckets": nb.value, "tiles": tiles, "segs": segs, "seg_begin": seg_begin, "bucket_first": bucket_first,
             "wg_bucket": wg_bucket}
+
+
+def bitmap_words(total_elems: int) -> int:
+    return int(_lib.srs_bitmap_words(total_elems))
 
 
 def stream_probe_sink_words(nbytes: int) -> int:
@@ -309,6 +319,40 @@ class Context:
             _payload_ok(I, V, counts, plan.nbuckets, cap)
         _check(_lib.srs_extract_cast_multi(self._h, plan._h, pairs, I.data_ptr(), V.data_ptr(), counts.data_ptr(), cap,
                                            _stream_ptr(stream)), "srs_extract_cast_multi")
+
+    # ---- cumulative changed-index set (Alg. 1 as printed) ----------------------------------
+    @staticmethod
+    def _bitmap_ok(plan: Plan, bitmap: torch.Tensor) -> None:
+        if not (bitmap.is_cuda and bitmap.element_size() == 4 and bitmap.is_contiguous()
+                and bitmap.numel() >= bitmap_words(plan.total)):
+            raise TypeError("bitmap: expected contiguous 32-bit GPU tensor of srs_bitmap_words(total) words")
+
+    def mark_multi(self, plan: Plan, prev: Optional[Sequence[torch.Tensor]], cur: Optional[Sequence[torch.Tensor]],
+                   bitmap: torch.Tensor, stream: Optional[torch.cuda.Stream] = None, pairs=None) -> None:
+        if pairs is None:
+            pairs = self.bind_pairs(plan, prev, cur)
+        self._bitmap_ok(plan, bitmap)
+        _check(_lib.srs_mark_multi(self._h, plan._h, pairs, bitmap.data_ptr(), _stream_ptr(stream)), "srs_mark_multi")
+
+    def cast_mark_multi(self, plan: Plan, weights: Optional[Sequence[torch.Tensor]],
+                        master: Optional[Sequence[torch.Tensor]], bitmap: torch.Tensor,
+                        stream: Optional[torch.cuda.Stream] = None, pairs=None) -> None:
+        if pairs is None:
+            pairs = self.bind_cast_pairs(plan, weights, master)
+        self._bitmap_ok(plan, bitmap)
+        _check(_lib.srs_cast_mark_multi(self._h, plan._h, pairs, bitmap.data_ptr(), _stream_ptr(stream)),
+               "srs_cast_mark_multi")
+
+    def extract_marked_multi(self, plan: Plan, weights: Optional[Sequence[torch.Tensor]], bitmap: torch.Tensor,
+                             I: torch.Tensor, V: torch.Tensor, counts: torch.Tensor, cap: int,
+                             stream: Optional[torch.cuda.Stream] = None, tensors=None) -> None:
+        if tensors is None:
+            tensors = self.bind_weights(plan, weights)
+        self._bitmap_ok(plan, bitmap)
+        if cap > 0:
+            _payload_ok(I, V, counts, plan.nbuckets, cap)
+        _check(_lib.srs_extract_marked_multi(self._h, plan._h, tensors, bitmap.data_ptr(), I.data_ptr(), V.data_ptr(),
+                                             counts.data_ptr(), cap, _stream_ptr(stream)), "srs_extract_marked_multi")
 
     # ---- 16-bit index coding --------------------------------------------------------------
     def encode_indices(self, I: torch.Tensor, counts: torch.Tensor, nbuckets: int, cap: int, base_stride: int,
