@@ -149,6 +149,69 @@ def bench_cast(args, torch, srs, synth, wl, dev) -> int:
     return 0
 
 
+def bench_cumulative(args, torch, srs, synth, wl, dev) -> int:
+    """Alg. 1 as printed, one optimizer step per synchronisation: mark (diff of two resident versions OR-ed into
+    the bitmap), extract from the bitmap with the current values, apply.  The two versions swap roles every cycle."""
+    N = wl.numel
+    A = synth.WeightSet(wl, dev); B = synth.WeightSet(wl, dev); R = synth.WeightSet(wl, dev)
+    synth.fill_base(A, args.seed)
+    nchanged, _ = synth.make_update(B, A, args.seed)
+    R.copy_from(A)
+    rho = nchanged / N
+    ctx = srs.Context(0)
+    if args.tile:
+        ctx.set_option(srs.OPT_TILE_ELEMS, args.tile)
+    plans = [ctx.plan(A.numels, wl.bucket_elems), ctx.plan(A.numels, wl.bucket_elems)]
+    cap = (synth.payload_capacity(wl) + 7) // 8 * 8
+    nb = plans[0].nbuckets
+    I = torch.empty((nb, cap), dtype=torch.int32, device=dev)
+    V = torch.empty((nb, cap), dtype=torch.int16, device=dev)
+    counts = torch.zeros(nb, dtype=torch.int32, device=dev)
+    bitmap = torch.zeros(srs.bitmap_words(N), dtype=torch.int32, device=dev)
+    vers = [(A, B), (B, A)]
+    pairs = [ctx.bind_pairs(plans[d], vers[d][0].tensors, vers[d][1].tensors) for d in (0, 1)]
+    curs = [ctx.bind_weights(plans[d], vers[d][1].tensors) for d in (0, 1)]
+    rolls = ctx.bind_weights(plans[0], R.tensors)
+    tm, te, ta = [], [], []
+    for i in range(args.warmup + args.steps):
+        d = i % 2
+        bitmap.zero_()
+        e = [torch.cuda.Event(enable_timing=True) for _ in range(4)]
+        e[0].record()
+        ctx.mark_multi(plans[d], None, None, bitmap, pairs=pairs[d])
+        e[1].record()
+        ctx.extract_marked_multi(plans[d], None, bitmap, I, V, counts, cap, tensors=curs[d])
+        e[2].record()
+        ctx.apply_multi(plans[0], None, I, V, counts, cap, tensors=rolls)
+        e[3].record()
+        torch.cuda.synchronize()
+        flags = ctx.status()
+        total = int(counts.to(torch.int64).sum().item())
+        if flags or total != nchanged or not torch.equal(R.flat.view(torch.int16), vers[d][1].flat.view(torch.int16)):
+            raise SystemExit(f"bench self-check failed (cumulative): flags={flags} counts={total} expected={nchanged}")
+        if i >= args.warmup:
+            tm.append(e[0].elapsed_time(e[1])); te.append(e[1].elapsed_time(e[2])); ta.append(e[2].elapsed_time(e[3]))
+    am, ae, aa = (sum(x) / len(x) for x in (tm, te, ta))
+    bytes_mark = (4.0 + 0.25) * N          # read both versions; read-modify-write of one bit per element
+    log(f"cumulative: mark {am:.3f} ms ({bytes_mark / (am * 1e-3) / 1e9:.0f} GB/s on 4.25 N bytes), "
+        f"extract_marked {ae:.3f} ms, apply {aa:.3f} ms")
+    out = {"metric": "Alg. 1 cumulative set: mark + extract_marked + apply, dense GB/s scanned",
+           "value": round(4.0 * N / ((am + ae + aa) * 1e-3) / 1e9, 1), "unit": "GB/s", "n_gpus": 1, "steps": args.steps,
+           "warmup": args.warmup, "ms_per_step": round(am + ae + aa, 4), "higher_is_better": True, "scaling": "weak",
+           "vs_baseline": None, "dtype": "u16", "data": "synthetic",
+           "config": {"workload": wl.name + "+cumulative-bitmap", "elements": N, "changed_fraction": round(rho, 6)},
+           "mark_ms": round(am, 4), "extract_marked_ms": round(ae, 4), "apply_ms": round(aa, 4),
+           "roofline": {"bound": "hbm", "kernel": "mark_kernel", "achieved": round(bytes_mark / (am * 1e-3) / 1e9, 1),
+                        "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(bytes_mark / (am * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+                        "traffic": None},
+           "cpu_baseline": None}
+    print(json.dumps(out), flush=True)
+    for pl in plans:
+        pl.close()
+    ctx.close()
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -174,6 +237,9 @@ def main() -> int:
                     help="time the fused cast + diff instead (srs_extract_cast_multi on FP32 master weights that are "
                          "rebuilt, untimed, before every step; implies 3 resident sets: master, model parameters, "
                          "rollout copy) -- not the headline path")
+    ap.add_argument("--cumulative", action="store_true",
+                    help="time Alg. 1 as printed instead: srs_mark_multi (one optimizer step's diff OR-ed into the bitmap), "
+                         "srs_extract_marked_multi, srs_apply_multi -- not the headline path")
     ap.add_argument("--regen", action="store_true",
                     help="keep one new-weights version and rebuild it (untimed) before every step instead of "
                          "alternating two resident versions: 3 weight sets instead of 4, for workloads that do not "
@@ -203,6 +269,8 @@ def main() -> int:
 
     if args.cast:
         return bench_cast(args, torch, srs, synth, wl, dev)
+    if args.cumulative:
+        return bench_cumulative(args, torch, srs, synth, wl, dev)
 
     t0 = time.perf_counter()
     if args.regen:
