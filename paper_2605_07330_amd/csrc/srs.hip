@@ -15,7 +15,6 @@ using namespace srs;
 namespace {
 
 constexpr uint64_t kMaxIndexable = 0x7fffffffull;   // int32 indices (Sec. 3.2: tensors below 2^31 elements)
-constexpr uint32_t kEpochMax = (1u << 30) - 1u;
 
 #define SRS_HIP(expr)                                   \
     do {                                                \
@@ -32,7 +31,6 @@ struct srs_ctx {
     uint32_t *tickets = nullptr;            // per-bucket ticket counters
     uint64_t tickets_cap = 0;               // in words
     uint32_t *flags = nullptr;              // device flag word (own 256-byte allocation)
-    uint32_t epoch = 1;
     uint32_t spin_limit = 1u << 24;
     uint32_t tile_elems = 16384;
     uint32_t group = 1024;                  // buckets whose tiles are interleaved over consecutive workgroups
@@ -59,22 +57,12 @@ struct srs_plan {
 
 namespace {
 
-int fill_status(srs_ctx *ctx, hipStream_t st) {
-    if (ctx->status_cap == 0) return SRS_OK;
-    const uint32_t threads = 256;
-    const uint64_t blocks = (ctx->status_cap + threads - 1) / threads;
-    hipLaunchKernelGGL(fill_u64_kernel, dim3((uint32_t)blocks), dim3(threads), 0, st, ctx->status, ctx->status_cap, 0ull);
-    SRS_HIP(hipGetLastError());
-    return SRS_OK;
-}
-
 // ticket counters sit 256 bytes apart (atomics on one cache line serialise) unless there are very
 // many buckets, which only happens with bucket sizes far below a tile
 uint32_t ticket_stride_for(uint64_t nb) { return nb <= 65536 ? 64u : 1u; }
 
-// make room for ntiles status words and nb ticket counters, rewind the counters and hand out this
-// launch's epoch
-int prepare_extract(srs_ctx *ctx, uint64_t ntiles, uint64_t nb, hipStream_t st, uint32_t *epoch, uint32_t *stride) {
+// make room for ntiles status words and nb ticket counters, then clear both on the stream
+int prepare_extract(srs_ctx *ctx, uint64_t ntiles, uint64_t nb, hipStream_t st, uint32_t *stride) {
     *stride = ticket_stride_for(nb);
     const uint64_t words = nb * (*stride);
     if (words > ctx->tickets_cap) {
@@ -85,29 +73,19 @@ int prepare_extract(srs_ctx *ctx, uint64_t ntiles, uint64_t nb, hipStream_t st, 
         SRS_HIP(hipMalloc((void **)&ctx->tickets, cap * sizeof(uint32_t)));
         ctx->tickets_cap = cap;
     }
-    {
-        const uint32_t threads = 256;
-        hipLaunchKernelGGL(zero_strided_kernel, dim3((uint32_t)((nb + threads - 1) / threads)), dim3(threads), 0, st,
-                           ctx->tickets, nb, *stride);
-        SRS_HIP(hipGetLastError());
-    }
     if (ntiles > ctx->status_cap) {
         SRS_HIP(hipDeviceSynchronize());
         if (ctx->status) SRS_HIP(hipFree(ctx->status));
         ctx->status = nullptr; ctx->status_cap = 0;
-        uint64_t cap = ntiles + ntiles / 4 + 1024;
+        const uint64_t cap = ntiles + ntiles / 4 + 1024;
         SRS_HIP(hipMalloc((void **)&ctx->status, cap * sizeof(unsigned long long)));
         ctx->status_cap = cap;
-        int rc = fill_status(ctx, st);
-        if (rc != SRS_OK) return rc;
-        ctx->epoch = 1;
     }
-    if (ctx->epoch >= kEpochMax) {          // epoch field is 30 bits: start over with cleared words
-        int rc = fill_status(ctx, st);
-        if (rc != SRS_OK) return rc;
-        ctx->epoch = 1;
-    }
-    *epoch = ctx->epoch++;
+    const uint64_t n = ntiles > nb ? ntiles : nb;
+    const uint32_t threads = 256;
+    hipLaunchKernelGGL(prepare_extract_kernel, dim3((uint32_t)((n + threads - 1) / threads)), dim3(threads), 0, st,
+                       ctx->tickets, nb, *stride, ctx->status, ntiles);
+    SRS_HIP(hipGetLastError());
     return SRS_OK;
 }
 
@@ -297,7 +275,7 @@ int extract_single(srs_ctx *ctx, void *old_snapshot, const void *new_w, uint64_t
 
     ExtractArgs a;
     std::memset(&a, 0, sizeof(a));
-    int rc = prepare_extract(ctx, ntiles, nb, st, &a.epoch, &a.ticket_stride);
+    int rc = prepare_extract(ctx, ntiles, nb, st, &a.ticket_stride);
     if (rc != SRS_OK) return rc;
     a.old_w = (uint16_t *)old_snapshot; a.new_w = new_w; a.n = n;
     a.be = (uint32_t)bucket_elems; a.tiles_per_bucket = (uint32_t)tpb;
@@ -331,7 +309,7 @@ int extract_multi(srs_ctx *ctx, srs_plan *plan, const srs_tensor_pair *t,
 
     ExtractArgs a;
     std::memset(&a, 0, sizeof(a));
-    int rc = prepare_extract(ctx, plan->ntiles, plan->nbuckets, st, &a.epoch, &a.ticket_stride);
+    int rc = prepare_extract(ctx, plan->ntiles, plan->nbuckets, st, &a.ticket_stride);
     if (rc != SRS_OK) return rc;
     a.tiles = plan->d_tiles; a.ptrs = plan->d_pairs; a.ntiles = plan->ntiles;
     a.wg_bucket = plan->d_wg_bucket; a.bucket_first = plan->d_bucket_first; a.nb = plan->nbuckets;

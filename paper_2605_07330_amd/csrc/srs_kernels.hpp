@@ -10,7 +10,7 @@
 //   both inputs with 16-byte loads, forms per-lane change masks by XOR of the 16-bit patterns
 //   (Alg. 1: I = { i : W[i] != W_prev[i] }), ranks the changed elements with a packed DPP wave
 //   scan + an LDS combine across the four waves, chains tiles of the same bucket with a
-//   decoupled look-back on one 64-bit {epoch|flag, value} status word per tile, stages the
+//   decoupled look-back on one 64-bit {flag, value} status word per tile, stages the
 //   (index, value) pairs of the tile in LDS in rank order and writes them out coalesced
 //   (Alg. 2: V = W[I], I int32 ascending), refreshing the snapshot at the same positions.
 // apply_kernel: the scatter of Alg. 3, W[I] <- V, one workgroup per (bucket, payload chunk).
@@ -60,11 +60,11 @@ struct ExtractArgs {
     const uint32_t *bucket_first;   // [nb+1] id of each bucket's first tile
     uint32_t ntiles;
     int32_t *I; uint16_t *V; uint32_t *counts; uint64_t cap;
-    unsigned long long *status;     // [>= ntiles] {(epoch<<2|flag) : value}
+    unsigned long long *status;     // [>= ntiles] {flag : value}, zeroed before every launch
     uint32_t *tickets;              // per-bucket ticket counters, ticket_stride words apart, zeroed per launch
     uint32_t ticket_stride;
     uint32_t *flags;
-    uint32_t epoch; uint32_t spin_limit;
+    uint32_t spin_limit;
     // cumulative changed-index set: one bit per packed position (bit g&31 of word g>>5)
     uint32_t *bitmap; uint64_t bitmap_words; const uint64_t *tensor_base;   // packed position of each tensor's element 0
 };
@@ -181,8 +181,8 @@ __device__ __forceinline__ unsigned long long status_load(const unsigned long lo
 __device__ __forceinline__ void status_store(unsigned long long *p, unsigned long long v) {
     __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
-__device__ __forceinline__ unsigned long long status_word(uint32_t epoch, uint32_t flag, uint32_t value) {
-    return ((unsigned long long)((epoch << 2) | flag) << 32) | value;
+__device__ __forceinline__ unsigned long long status_word(uint32_t flag, uint32_t value) {
+    return ((unsigned long long)flag << 32) | value;
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -206,7 +206,7 @@ __device__ __forceinline__ uint32_t look_back(const ExtractArgs &a, uint32_t til
             if (in_bucket) {
                 const unsigned long long w = status_load(a.status + idx);
                 const uint32_t hi = (uint32_t)(w >> 32);
-                flag = ((hi >> 2) == a.epoch) ? (hi & 3u) : 0u;
+                flag = hi & 3u;
                 value = (uint32_t)w;
             }
             const unsigned long long valid = __ballot(in_bucket);            // a low run of lanes
@@ -449,11 +449,11 @@ __global__ __launch_bounds__(kThreads) void extract_kernel(const ExtractArgs a) 
     if (wave == 0) {
         uint32_t excl = 0;
         if (tile == first_tile) {
-            if (lane == 0) status_store(a.status + tile, status_word(a.epoch, kStPrefix, tile_total));
+            if (lane == 0) status_store(a.status + tile, status_word(kStPrefix, tile_total));
         } else {
-            if (lane == 0) status_store(a.status + tile, status_word(a.epoch, kStAgg, tile_total));
+            if (lane == 0) status_store(a.status + tile, status_word(kStAgg, tile_total));
             excl = look_back(a, tile, first_tile, lane);
-            if (lane == 0) status_store(a.status + tile, status_word(a.epoch, kStPrefix, excl + tile_total));
+            if (lane == 0) status_store(a.status + tile, status_word(kStPrefix, excl + tile_total));
         }
         if (lane == 0) {
             s_excl = excl;
@@ -871,10 +871,19 @@ __global__ void fill_u64_kernel(unsigned long long *p, uint64_t n, unsigned long
     if (i < n) p[i] = v;
 }
 
-// p[i*stride] = 0 for i < n: rewinds the per-bucket ticket counters before a launch
+// p[i*stride] = 0 for i < n
 __global__ void zero_strided_kernel(uint32_t *p, uint64_t n, uint32_t stride) {
     const uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (i < n) p[i * stride] = 0u;
+}
+
+// Before every extract launch: rewinds the per-bucket ticket counters and clears the tile status words.
+// Part of the stream's work (not of host state), so a captured graph replays correctly.
+__global__ void prepare_extract_kernel(uint32_t *tickets, uint64_t nb, uint32_t stride, unsigned long long *status,
+                                       uint64_t ntiles) {
+    const uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < nb) tickets[i * stride] = 0u;
+    if (i < ntiles) status[i] = 0ull;
 }
 
 // two-stream read probe with extract's load shape; the XOR-reduction keeps the loads alive
