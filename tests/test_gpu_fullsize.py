@@ -170,3 +170,48 @@ def test_full_size_qwen3_32b_density_sweep(srs):
     finally:
         del S, W1, R
         free_all()
+
+
+def test_largest_single_tensor(srs):
+    """n = 2^31 - 1 elements, the largest tensor int32 indexing admits (Sec. 3.2): one bucket of the whole
+    tensor (indices up to 2^31 - 2), then 37 ragged buckets.  The oracle runs on the full tensor."""
+    n = (1 << 31) - 1
+    g = torch.Generator(device=DEV); g.manual_seed(77)
+    old = torch.empty(n, dtype=torch.bfloat16, device=DEV)
+    synth.fill_base_(old, 77)
+    new = torch.empty_like(old)
+    nchanged, _ = synth.iid_update_(new, old, 0.002, 77)
+    # make sure the very first and the very last element change
+    for pos in (0, n - 1):
+        new.view(torch.int16)[pos] = old.view(torch.int16)[pos] ^ 1
+    old_h = old.view(torch.int16).cpu().numpy().view(np.uint16)
+    new_h = new.view(torch.int16).cpu().numpy().view(np.uint16)
+    ctx = srs.Context(0)
+    try:
+        for be, cap in ((n, 5_000_000), (58_000_001, 200_000)):
+            print(f"case largest tensor be={be}", flush=True)
+            snap = old.clone(); roll = old.clone()
+            nb = (n + be - 1) // be
+            I, V, counts = srs.alloc_payload(nb, cap, DEV)
+            ctx.extract(snap, new, be, I, V, counts, cap)
+            ctx.apply(roll, be, I, V, counts, cap)
+            assert ctx.status() == 0
+            wI, wV, wc, ovf = oracle.extract(old_h.copy(), new_h, be, cap=cap)
+            assert ovf == 0
+            gc_ = counts.cpu().numpy().view(np.uint32)
+            assert np.array_equal(gc_, wc)
+            gI, gV = I.cpu().numpy(), V.cpu().numpy().view(np.uint16)
+            for b in range(nb):
+                c = int(wc[b])
+                assert np.array_equal(gI[b, :c], wI[b, :c]) and np.array_equal(gV[b, :c], wV[b, :c]), f"bucket {b}"
+            assert int(gI[nb - 1, int(wc[nb - 1]) - 1]) == n - 1 and int(gI[0, 0]) == 0
+            assert torch.equal(snap.view(torch.int16), new.view(torch.int16))
+            assert torch.equal(roll.view(torch.int16), new.view(torch.int16))
+            del snap, roll, I, V, counts
+        # one element more is rejected before anything is launched
+        with pytest.raises(srs.SrsError):
+            srs._check(srs._lib.srs_extract(ctx._h, old.data_ptr(), new.data_ptr(), n + 1, n + 1, 8, 8, 8, 16, None), "srs_extract")
+    finally:
+        ctx.close()
+        del old, new
+        free_all()
