@@ -386,3 +386,37 @@ def test_bounded_look_back_exits_when_starved(srs):
         assert np.array_equal(u16(d_old), new_h)        # the refresh does not depend on the chain
     finally:
         c.close()
+
+
+def test_two_contexts_on_two_streams_run_concurrently(srs):
+    """Two extracts in flight at once compete for workgroup slots.  A tile only ever waits for tiles that are
+    already running (ticket order inside a bucket is start order), so neither launch can starve the other;
+    the bounded wait would raise SRS_FLAG_TIMEOUT instead of hanging if that reasoning were wrong."""
+    n, be, cap = 24_000_011, 3_000_007, 60_000
+    cases = []
+    for s in range(2):
+        old_h, new_h = make_pair(n, 0.01, seed=100 + s)
+        cases.append((old_h, new_h, oracle.extract(old_h.copy(), new_h, be, cap=cap)[:3]))
+    ctxs = [srs.Context(0), srs.Context(0)]
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    nb = (n + be - 1) // be
+    try:
+        for c in ctxs:
+            c.set_option(srs.OPT_SPIN_LIMIT, 1 << 20)
+            c.set_option(srs.OPT_TILE_ELEMS, 4096)          # many small tiles: more chain traffic, more waiting
+        d_new = [from_u16(c[1], DEV) for c in cases]
+        for rep in range(10):
+            d_old = [from_u16(c[0], DEV) for c in cases]
+            bufs = [srs.alloc_payload(nb, cap, DEV) for _ in cases]
+            torch.cuda.synchronize()
+            for k in range(2):
+                with torch.cuda.stream(streams[k]):
+                    ctxs[k].extract(d_old[k], d_new[k], be, *bufs[k], cap)
+            torch.cuda.synchronize()
+            for k in range(2):
+                assert ctxs[k].status(streams[k]) == 0, f"rep {rep} stream {k}"
+                assert_payload_equal(payload_to_host(*bufs[k]), cases[k][2], f"rep {rep} stream {k}")
+                assert np.array_equal(u16(d_old[k]), cases[k][1])
+    finally:
+        for c in ctxs:
+            c.close()
