@@ -13,9 +13,15 @@
 //   decoupled look-back on one 64-bit {flag, value} status word per tile, stages the
 //   (index, value) pairs of the tile in LDS in rank order and writes them out coalesced
 //   (Alg. 2: V = W[I], I int32 ascending), refreshing the snapshot at the same positions.
+//   Template flavours of the same kernel: SRC = FP32 master weights rounded to BF16 on the fly (the
+//   cast-and-copy of Alg. 1 fused with its diff), SRC = bitmap (masks come from the cumulative index set).
+// mark_kernel: one optimizer step of Alg. 1's index accumulation, OR-ed into a bitmap.
 // apply_kernel: the scatter of Alg. 3, W[I] <- V, one workgroup per (bucket, payload chunk).
+// apply_encoded_kernel / encode_indices_kernel: the 16-bit index delta coding of Sec. 3.3.
+// route_kernel / dense_copy_kernel: the per-bucket sparse / dense routing of Sec. 3.4 and its full-copy route.
 //
-// No arithmetic is done on weight values anywhere; the path is HBM-bandwidth bound.
+// No arithmetic is done on weight values anywhere (the cast flavour rounds, nothing more); every kernel here
+// is HBM-bandwidth bound and there is no contraction, hence no MFMA.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
