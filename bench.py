@@ -373,6 +373,7 @@ def main() -> int:
     value = 4.0 * N / (ms_per_step * 1e-3) / 1e9
     ach = bytes_extract / (ext_avg * 1e-3) / 1e9
     combined = (bytes_extract + bytes_apply) / (ms_per_step * 1e-3) / 1e9
+    log("per-step extract ms: " + " ".join(f"{x:.2f}" for x in ext_ms))
     log(f"extract {ext_avg:.3f} ms (min {min(ext_ms):.3f}), apply {app_avg:.3f} ms (min {min(app_ms):.3f}), "
         f"step {ms_per_step:.3f} ms; extract {ach:.0f} GB/s = {100 * ach / HBM_PEAK_GBS:.1f}% of peak; "
         f"combined {combined:.0f} GB/s = {100 * combined / HBM_PEAK_GBS:.1f}%")
