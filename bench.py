@@ -217,7 +217,7 @@ def main() -> int:
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=4)
-    ap.add_argument("--config", type=int, default=2, help="workload id (BASELINE configs); 2 = Qwen3-30B-A3B-shaped")
+    ap.add_argument("--config", type=int, default=2, help="workload id 0..4 (synth.workload); 2 = Qwen3-30B-A3B-shaped, the headline workload")
     ap.add_argument("--density", type=float, default=None)
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--tile", type=int, default=0, help="extract tile elements (0 = library default)")
