@@ -203,6 +203,39 @@ int srs_apply_multi_encoded(srs_ctx *ctx, srs_plan *plan, const srs_tensor *t, c
                             const int32_t *anchors, uint64_t cap, void *stream);
 
 /*
+ * Lossless value coding (Sec. 3.3, "Value entropy coding"): the BF16 values of a payload cluster in a few binades,
+ * so the value stream compresses under a standard entropy coder; the paper names none and reports that the stream
+ * shrinks to 0.60-0.70 of its size.  The coder here is a static Huffman code on the part of a value that carries
+ * the redundancy: each value is split into its high byte (sign, upper seven exponent bits) and its low byte (lowest
+ * exponent bit, mantissa); low bytes are kept as they are, the high bytes of one bucket are coded with a code built
+ * from that bucket's own histogram.
+ *
+ * Code construction (fixed, so that independent implementations agree bit for bit):
+ *   1. hist[s] over the high bytes of the bucket's min(counts[b], cap) values.
+ *   2. Huffman lengths: repeatedly merge the two live nodes of smallest weight, ties to the smaller id; leaves have
+ *      id = symbol, the k-th merged node id 256 + k.  A lone symbol gets length 1, an absent one length 0.
+ *   3. While some length exceeds 12: every non-zero weight w becomes (w + 1) / 2 and step 2 is repeated.
+ *   4. Canonical codes as in DEFLATE: symbols ordered by (length, symbol) take consecutive code values.
+ * Stream layout per bucket, chunks of 2048 values, nchunk = srs_value_chunks(cap):
+ *   lens[b*256 + s]                       code lengths (the code follows from them)
+ *   low[b*cap + r]                        low bytes
+ *   bits[(b*nchunk + k)*768 ...]          chunk k's code bits, most significant code bit first, bit i of the chunk =
+ *                                         bit (i & 31) of word i >> 5; chunk_words[b*nchunk + k] words are used
+ *                                         (0 for a chunk without values); words beyond that are unspecified
+ *   sub[(b*nchunk + k)*32 + j]            bit position inside the chunk where its value j*64 starts
+ * Wire size of a bucket = 256 + count + 4*sum(chunk_words) + 64 per started chunk bytes, against 2*count raw.
+ * srs_decode_values is the inverse (V_out[b*cap + r] for r < min(counts[b], cap)); a stream that does not decode
+ * under its own table raises SRS_FLAG_BAD_INDEX.  All pointers are device pointers; asynchronous on `stream`
+ * (the first encode at a larger bucket count grows a small scratch array: allocation + synchronisation).
+ */
+uint64_t srs_value_chunks(uint64_t cap);
+int srs_encode_values(srs_ctx *ctx, const uint16_t *V, const uint32_t *counts, uint32_t nbuckets, uint64_t cap,
+                      uint8_t *lens, uint8_t *low, uint32_t *bits, uint32_t *chunk_words, uint16_t *sub, void *stream);
+int srs_decode_values(srs_ctx *ctx, const uint8_t *lens, const uint8_t *low, const uint32_t *bits,
+                      const uint32_t *chunk_words, const uint16_t *sub, const uint32_t *counts, uint32_t nbuckets,
+                      uint64_t cap, uint16_t *V_out, void *stream);
+
+/*
  * Density routing (Sec. 3.4, WeightUpdater): parameters that are highly sparse take the (I, V) route, those
  * that change on nearly every element are sent as a full copy.  The unit here is the bucket and the rule is
  * the break-even of the cost model, Eq. (1): bucket b of len_b elements goes dense when

@@ -80,6 +80,13 @@ def _load():
         lib.srs_oracle_extract_marked_multi.restype = C.c_int
         lib.srs_oracle_extract_marked_multi.argtypes = [pp, u64p, C.c_uint32, C.c_uint64, u32p, i32p, u16p_, u32p,
                                                         C.c_uint64]
+        u8p = C.POINTER(C.c_uint8)
+        lib.srs_oracle_vc_chunks.restype = C.c_uint64
+        lib.srs_oracle_vc_chunks.argtypes = [C.c_uint64]
+        lib.srs_oracle_encode_values.restype = C.c_int
+        lib.srs_oracle_encode_values.argtypes = [u16p_, u32p, C.c_uint64, C.c_uint64, u8p, u8p, u32p, u32p, u16p_]
+        lib.srs_oracle_decode_values.restype = C.c_int
+        lib.srs_oracle_decode_values.argtypes = [u8p, u8p, u32p, u32p, C.c_uint64, C.c_uint64, u16p_]
         lib.srs_oracle_num_buckets.restype = C.c_uint64
         lib.srs_oracle_num_buckets.argtypes = [u64p, C.c_uint32, C.c_uint64]
         _lib = lib
@@ -383,3 +390,38 @@ def extract_marked_multi(w: Sequence[np.ndarray], numel: Sequence[int], be: int,
     if rc < 0:
         raise ValueError("srs_oracle_extract_marked_multi: bad argument")
     return I, V, counts, rc
+
+
+VC_CHUNK, VC_SLOT_WORDS, VC_SUB, VC_MAXLEN = 2048, 768, 64, 12
+
+
+def encode_values(V: np.ndarray, counts: np.ndarray):
+    """Huffman coding of the high bytes of each bucket's values (Sec. 3.3, value entropy coding).
+    Returns dict(lens[nb,256] u8, low[nb,cap] u8, bits[nb,nchunk,768] u32, chunk_words[nb,nchunk] u32,
+    sub[nb,nchunk,32] u16); unused entries hold 0xFF / 0xFFFFFFFF / 0xFFFF fill."""
+    lib = _load()
+    V = np.ascontiguousarray(V, np.uint16)
+    counts = np.ascontiguousarray(counts, np.uint32)
+    nb, cap = V.shape
+    nchunk = (cap + VC_CHUNK - 1) // VC_CHUNK
+    out = {"lens": np.full((nb, 256), 0xFF, np.uint8), "low": np.full((nb, cap), 0xFF, np.uint8),
+           "bits": np.full((nb, nchunk, VC_SLOT_WORDS), 0xFFFFFFFF, np.uint32),
+           "chunk_words": np.full((nb, nchunk), 0xFFFFFFFF, np.uint32), "sub": np.full((nb, nchunk, 32), 0xFFFF, np.uint16)}
+    rc = lib.srs_oracle_encode_values(_p(V, C.c_uint16), _p(counts, C.c_uint32), nb, cap, _p(out["lens"], C.c_uint8),
+                                      _p(out["low"], C.c_uint8), _p(out["bits"], C.c_uint32),
+                                      _p(out["chunk_words"], C.c_uint32), _p(out["sub"], C.c_uint16))
+    if rc != OK:
+        raise ValueError("srs_oracle_encode_values: bad argument")
+    return out
+
+
+def decode_values(enc: dict, counts: np.ndarray) -> np.ndarray:
+    lib = _load()
+    counts = np.ascontiguousarray(counts, np.uint32)
+    nb, cap = enc["low"].shape
+    V = np.full((nb, cap), 0xFFFF, np.uint16)
+    rc = lib.srs_oracle_decode_values(_p(enc["lens"], C.c_uint8), _p(enc["low"], C.c_uint8), _p(enc["bits"], C.c_uint32),
+                                      _p(counts, C.c_uint32), nb, cap, _p(V, C.c_uint16))
+    if rc != OK:
+        raise ValueError(f"srs_oracle_decode_values: {rc}")
+    return V

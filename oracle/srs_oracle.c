@@ -459,3 +459,154 @@ int srs_oracle_extract_marked_multi(const uint16_t *const *w, const uint64_t *nu
     for (uint64_t b = 0; b < nb; ++b) if (counts[b] > cap) overflowed += 1;
     return overflowed;
 }
+
+/* ------------------------------------------------------------------------------------------------
+ * Value entropy coding (Sec. 3.3, "Value entropy coding"): the BF16 values of a payload cluster in a few
+ * binades, so their stream compresses under a standard lossless entropy coder; the paper names none and
+ * reports the result only (the stream shrinks to 0.60-0.70 of its size).  The coder taken here is the
+ * textbook one, a static Huffman code, applied where the redundancy is: each 16-bit value is split into
+ * its high byte (sign and the upper seven exponent bits) and its low byte (lowest exponent bit and the
+ * mantissa); the low bytes are kept as they are, the high bytes of one bucket are Huffman coded with a
+ * code built from that bucket's own histogram.
+ *
+ * Code construction (fixed so that two independent implementations give the same bits):
+ *   1. hist[s], s = 0..255, over the bucket's c = min(counts[b], cap) high bytes.
+ *   2. Huffman code lengths by repeatedly merging the two live nodes of smallest weight; ties go to the
+ *      node with the smaller id; leaves have id = symbol, the k-th merged node has id 256 + k and weight
+ *      the sum.  A lone symbol gets length 1.  Symbols that do not occur get length 0.
+ *   3. If a length exceeds 12, every non-zero weight w is replaced by (w + 1) / 2 (integer division) and
+ *      step 2 is repeated, until no length exceeds 12.
+ *   4. Canonical codes: symbols ordered by (length, symbol) receive consecutive code values, the first 0,
+ *      shifted left whenever the length grows (as in DEFLATE).
+ * Stream layout per bucket, in chunks of 2048 values (chunk k holds values k*2048 ..):
+ *   - a chunk's bits are written most significant code bit first into 32-bit words, bit i of the chunk
+ *     being bit (i & 31) of word i >> 5; every chunk starts on a word of its own slot
+ *     bits[(b*nchunk + k) * 768 ...] (768 words hold 2048 codes of 12 bits) and chunk_words[b*nchunk + k]
+ *     says how many of them are used;
+ *   - sub[(b*nchunk + k)*32 + j] is the bit position inside the chunk where value k*2048 + j*64 starts, so
+ *     that 32 decoders can work on a chunk side by side;
+ *   - lens[b*256 + s] are the code lengths (the whole code follows from them), low[b*cap + r] the low bytes.
+ * ------------------------------------------------------------------------------------------------ */
+#define SRS_VC_CHUNK 2048u
+#define SRS_VC_SLOT_WORDS 768u
+#define SRS_VC_SUB 64u
+#define SRS_VC_MAXLEN 12u
+
+static void srs_oracle_huffman_lengths(const uint32_t *hist, uint8_t *len /* [256] */)
+{
+    uint64_t w[256];
+    int used = 0;
+    for (int s = 0; s < 256; ++s) { w[s] = hist[s]; len[s] = 0; if (hist[s]) used += 1; }
+    if (used == 0) return;
+    for (;;) {
+        uint64_t weight[511];
+        int parent[511], alive[511];
+        int nnodes = 256;
+        for (int s = 0; s < 256; ++s) { weight[s] = w[s]; alive[s] = w[s] != 0; parent[s] = -1; }
+        int live = used;
+        while (live > 1) {
+            int a = -1, b = -1;                                  /* the two smallest live nodes, ties by id */
+            for (int i = 0; i < nnodes; ++i) {
+                if (!alive[i]) continue;
+                if (a < 0 || weight[i] < weight[a]) { b = a; a = i; }
+                else if (b < 0 || weight[i] < weight[b]) { b = i; }
+            }
+            weight[nnodes] = weight[a] + weight[b];
+            alive[nnodes] = 1; parent[nnodes] = -1;
+            alive[a] = alive[b] = 0; parent[a] = parent[b] = nnodes;
+            nnodes += 1; live -= 1;
+        }
+        unsigned maxlen = 0;
+        for (int s = 0; s < 256; ++s) {
+            if (!w[s]) { len[s] = 0; continue; }
+            unsigned d = 0;
+            for (int i = s; parent[i] >= 0; i = parent[i]) d += 1;
+            if (used == 1) d = 1;
+            len[s] = (uint8_t)d;
+            if (d > maxlen) maxlen = d;
+        }
+        if (maxlen <= SRS_VC_MAXLEN) return;
+        for (int s = 0; s < 256; ++s) if (w[s]) w[s] = (w[s] + 1) / 2;
+    }
+}
+
+static void srs_oracle_canonical_codes(const uint8_t *len, uint32_t *code /* [256] */)
+{
+    uint32_t next = 0;
+    for (unsigned l = 1; l <= SRS_VC_MAXLEN; ++l) {
+        for (int s = 0; s < 256; ++s) if (len[s] == l) code[s] = next++;
+        next <<= 1;
+    }
+}
+
+uint64_t srs_oracle_vc_chunks(uint64_t cap) { return (cap + SRS_VC_CHUNK - 1) / SRS_VC_CHUNK; }
+
+int srs_oracle_encode_values(const uint16_t *V, const uint32_t *counts, uint64_t nb, uint64_t cap,
+                             uint8_t *lens, uint8_t *low, uint32_t *bits, uint32_t *chunk_words, uint16_t *sub)
+{
+    if (cap == 0) return SRS_ORACLE_BAD_ARG;
+    uint64_t nchunk = srs_oracle_vc_chunks(cap);
+    for (uint64_t b = 0; b < nb; ++b) {
+        uint64_t c = counts[b] < cap ? counts[b] : cap;
+        uint32_t hist[256];
+        for (int s = 0; s < 256; ++s) hist[s] = 0;
+        for (uint64_t r = 0; r < c; ++r) hist[V[b * cap + r] >> 8] += 1;
+        uint8_t *len = lens + b * 256;
+        uint32_t code[256];
+        srs_oracle_huffman_lengths(hist, len);
+        srs_oracle_canonical_codes(len, code);
+        for (uint64_t k = 0; k < nchunk; ++k) {
+            uint64_t r0 = k * SRS_VC_CHUNK;
+            uint32_t *words = bits + (b * nchunk + k) * SRS_VC_SLOT_WORDS;
+            if (r0 >= c) { chunk_words[b * nchunk + k] = 0; continue; }
+            uint64_t r1 = r0 + SRS_VC_CHUNK < c ? r0 + SRS_VC_CHUNK : c;
+            uint32_t pos = 0;
+            for (uint32_t i = 0; i < SRS_VC_SLOT_WORDS; ++i) words[i] = 0;
+            for (uint64_t r = r0; r < r1; ++r) {
+                if ((r - r0) % SRS_VC_SUB == 0) sub[(b * nchunk + k) * 32 + (r - r0) / SRS_VC_SUB] = (uint16_t)pos;
+                uint16_t v = V[b * cap + r];
+                low[b * cap + r] = (uint8_t)(v & 0xFF);
+                unsigned s = v >> 8, l = len[s];
+                for (unsigned j = 0; j < l; ++j) {                /* most significant code bit first */
+                    uint32_t bit = (code[s] >> (l - 1 - j)) & 1u;
+                    words[pos >> 5] |= bit << (pos & 31);
+                    pos += 1;
+                }
+            }
+            chunk_words[b * nchunk + k] = (pos + 31) / 32;
+        }
+    }
+    return SRS_ORACLE_OK;
+}
+
+/* Inverse, bit by bit: walks the canonical code as a decoder without tables does. */
+int srs_oracle_decode_values(const uint8_t *lens, const uint8_t *low, const uint32_t *bits, const uint32_t *counts,
+                             uint64_t nb, uint64_t cap, uint16_t *V_out)
+{
+    if (cap == 0) return SRS_ORACLE_BAD_ARG;
+    uint64_t nchunk = srs_oracle_vc_chunks(cap);
+    for (uint64_t b = 0; b < nb; ++b) {
+        uint64_t c = counts[b] < cap ? counts[b] : cap;
+        const uint8_t *len = lens + b * 256;
+        uint32_t code[256];
+        srs_oracle_canonical_codes(len, code);
+        for (uint64_t k = 0; k * SRS_VC_CHUNK < c; ++k) {
+            const uint32_t *words = bits + (b * nchunk + k) * SRS_VC_SLOT_WORDS;
+            uint64_t r0 = k * SRS_VC_CHUNK;
+            uint64_t r1 = r0 + SRS_VC_CHUNK < c ? r0 + SRS_VC_CHUNK : c;
+            uint32_t pos = 0;                                      /* bit cursor inside the chunk */
+            for (uint64_t r = r0; r < r1; ++r) {
+                uint32_t acc = 0;
+                int found = -1;
+                for (unsigned l = 1; l <= SRS_VC_MAXLEN && found < 0; ++l) {
+                    acc = (acc << 1) | ((words[pos >> 5] >> (pos & 31)) & 1u);
+                    pos += 1;
+                    for (int s = 0; s < 256; ++s) if (len[s] == l && code[s] == acc) { found = s; break; }
+                }
+                if (found < 0) return SRS_ORACLE_BAD_INDEX;
+                V_out[b * cap + r] = (uint16_t)((found << 8) | low[b * cap + r]);
+            }
+        }
+    }
+    return SRS_ORACLE_OK;
+}

@@ -31,6 +31,8 @@ struct srs_ctx {
     uint32_t *tickets = nullptr;            // per-bucket ticket counters
     uint64_t tickets_cap = 0;               // in words
     uint32_t *flags = nullptr;              // device flag word (own 256-byte allocation)
+    uint32_t *vc_scratch = nullptr;         // value codec: per-bucket histograms and codes
+    uint64_t vc_cap = 0;                    // in words
     uint32_t spin_limit = 1u << 24;
     uint32_t tile_elems = 16384;
     uint32_t group = 1024;                  // buckets whose tiles are interleaved over consecutive workgroups
@@ -362,6 +364,7 @@ int srs_destroy(srs_ctx *ctx) {
     (void)hipDeviceSynchronize();
     if (ctx->status) (void)hipFree(ctx->status);
     if (ctx->tickets) (void)hipFree(ctx->tickets);
+    if (ctx->vc_scratch) (void)hipFree(ctx->vc_scratch);
     if (ctx->flags) (void)hipFree(ctx->flags);
     delete ctx;
     return SRS_OK;
@@ -778,6 +781,71 @@ int srs_unpack_dense_multi(srs_ctx *ctx, srs_plan *plan, const srs_tensor *t, co
     int rc = upload_weight_pointers(plan, t, st);
     if (rc != SRS_OK) return rc;
     return launch_dense_copy<false>(ctx, plan, dense_bucket, n_dense, max_dense, const_cast<uint16_t *>(dense), st);
+}
+
+// ---------------------------------------------------------------------------------------------
+// value entropy coding
+// ---------------------------------------------------------------------------------------------
+
+uint64_t srs_value_chunks(uint64_t cap) { return (cap + kVcChunk - 1) / kVcChunk; }
+
+int srs_encode_values(srs_ctx *ctx, const uint16_t *V, const uint32_t *counts, uint32_t nbuckets, uint64_t cap,
+                      uint8_t *lens, uint8_t *low, uint32_t *bits, uint32_t *chunk_words, uint16_t *sub, void *stream) {
+    if (!ctx || cap == 0) return SRS_ERR_INVALID;
+    if (nbuckets == 0) return SRS_OK;
+    if (!V || !counts || !lens || !low || !bits || !chunk_words || !sub) return SRS_ERR_INVALID;
+    if ((((uintptr_t)V | (uintptr_t)sub) & 1u) || (((uintptr_t)counts | (uintptr_t)bits | (uintptr_t)chunk_words) & 3u))
+        return SRS_ERR_INVALID;
+    hipStream_t st = (hipStream_t)stream;
+    SRS_HIP(hipSetDevice(ctx->device));
+    const uint64_t nchunk = (cap + kVcChunk - 1) / kVcChunk;
+    if ((uint64_t)nbuckets * nchunk > 0x7fffffffull) return SRS_ERR_INVALID;
+    const uint64_t words = (uint64_t)nbuckets * 512;
+    if (words > ctx->vc_cap) {
+        SRS_HIP(hipDeviceSynchronize());
+        if (ctx->vc_scratch) SRS_HIP(hipFree(ctx->vc_scratch));
+        ctx->vc_scratch = nullptr; ctx->vc_cap = 0;
+        SRS_HIP(hipMalloc((void **)&ctx->vc_scratch, words * sizeof(uint32_t)));
+        ctx->vc_cap = words;
+    }
+    ValueCodecArgs a;
+    std::memset(&a, 0, sizeof(a));
+    a.V = V; a.counts = counts; a.nb = nbuckets; a.cap = cap; a.nchunk = (uint32_t)nchunk;
+    a.lens = lens; a.low = low; a.bits = bits; a.chunk_words = chunk_words; a.sub = sub;
+    a.hist = ctx->vc_scratch; a.rcode = ctx->vc_scratch + (uint64_t)nbuckets * 256; a.flags = ctx->flags;
+    const uint64_t nh = (uint64_t)nbuckets * 256;
+    hipLaunchKernelGGL(zero_strided_kernel, dim3((uint32_t)((nh + 255) / 256)), dim3(256), 0, st, a.hist, nh, 1u);
+    SRS_HIP(hipGetLastError());
+    const dim3 grid((uint32_t)((uint64_t)nbuckets * nchunk));
+    hipLaunchKernelGGL(vc_hist_kernel, grid, dim3(kThreads), 0, st, a);
+    SRS_HIP(hipGetLastError());
+    hipLaunchKernelGGL(vc_build_kernel, dim3(nbuckets), dim3(kThreads), 0, st, a);
+    SRS_HIP(hipGetLastError());
+    hipLaunchKernelGGL(vc_encode_kernel, grid, dim3(kThreads), 0, st, a);
+    SRS_HIP(hipGetLastError());
+    return SRS_OK;
+}
+
+int srs_decode_values(srs_ctx *ctx, const uint8_t *lens, const uint8_t *low, const uint32_t *bits,
+                      const uint32_t *chunk_words, const uint16_t *sub, const uint32_t *counts, uint32_t nbuckets,
+                      uint64_t cap, uint16_t *V_out, void *stream) {
+    if (!ctx || cap == 0) return SRS_ERR_INVALID;
+    if (nbuckets == 0) return SRS_OK;
+    if (!lens || !low || !bits || !chunk_words || !sub || !counts || !V_out) return SRS_ERR_INVALID;
+    if ((((uintptr_t)V_out | (uintptr_t)sub) & 1u) || (((uintptr_t)counts | (uintptr_t)bits | (uintptr_t)chunk_words) & 3u))
+        return SRS_ERR_INVALID;
+    hipStream_t st = (hipStream_t)stream;
+    SRS_HIP(hipSetDevice(ctx->device));
+    const uint64_t nchunk = (cap + kVcChunk - 1) / kVcChunk;
+    if ((uint64_t)nbuckets * nchunk > 0x7fffffffull) return SRS_ERR_INVALID;
+    ValueCodecArgs a;
+    std::memset(&a, 0, sizeof(a));
+    a.V_out = V_out; a.counts = counts; a.nb = nbuckets; a.cap = cap; a.nchunk = (uint32_t)nchunk;
+    a.lens = const_cast<uint8_t *>(lens); a.low = const_cast<uint8_t *>(low); a.bits = const_cast<uint32_t *>(bits);
+    a.chunk_words = const_cast<uint32_t *>(chunk_words); a.sub = const_cast<uint16_t *>(sub); a.flags = ctx->flags;
+    hipLaunchKernelGGL(vc_decode_kernel, dim3((uint32_t)((uint64_t)nbuckets * nchunk)), dim3(kThreads), 0, st, a);
+    SRS_HIP(hipGetLastError());
+    return SRS_OK;
 }
 
 // ---------------------------------------------------------------------------------------------

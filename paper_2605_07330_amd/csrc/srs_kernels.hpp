@@ -870,6 +870,215 @@ __global__ __launch_bounds__(kThreads) void dense_copy_kernel(const DenseCopyArg
 }
 
 // ---------------------------------------------------------------------------------------------
+// value entropy coding (Sec. 3.3): static Huffman code over the high bytes of one bucket's values, low
+// bytes raw.  Chunks of 2048 values, each chunk's bit stream in a slot of its own, a bit offset every 64
+// values so that 32 lanes decode a chunk side by side.  Layout and code construction are those of the
+// library header; the bit order is: most significant code bit first, stream bit i = bit (i & 31) of word i >> 5.
+// ---------------------------------------------------------------------------------------------
+constexpr uint32_t kVcChunk = 2048, kVcSlotWords = 768, kVcSub = 64, kVcMaxLen = 12;
+
+struct ValueCodecArgs {
+    const uint16_t *V; uint16_t *V_out; const uint32_t *counts; uint32_t nb; uint64_t cap; uint32_t nchunk;
+    uint8_t *lens; uint8_t *low; uint32_t *bits; uint32_t *chunk_words; uint16_t *sub;
+    uint32_t *hist;        // [nb*256] scratch
+    uint32_t *rcode;       // [nb*256] scratch: bit-reversed canonical code of each symbol
+    uint32_t *flags;
+};
+
+// per (bucket, chunk): histogram of the high bytes, accumulated per bucket
+__global__ __launch_bounds__(kThreads) void vc_hist_kernel(const ValueCodecArgs a) {
+    __shared__ uint32_t h[256];
+    const uint32_t b = blockIdx.x / a.nchunk, k = blockIdx.x - b * a.nchunk;
+    const uint64_t cnt = ((uint64_t)a.counts[b] < a.cap) ? a.counts[b] : a.cap;
+    const uint64_t r0 = (uint64_t)k * kVcChunk;
+    if (r0 >= cnt) return;
+    h[threadIdx.x] = 0;
+    __syncthreads();
+    const uint32_t n = (uint32_t)((cnt - r0 < kVcChunk) ? (cnt - r0) : kVcChunk);
+    const uint16_t *v = a.V + (uint64_t)b * a.cap + r0;
+    for (uint32_t i = threadIdx.x; i < n; i += kThreads) atomicAdd(&h[v[i] >> 8], 1u);
+    __syncthreads();
+    if (h[threadIdx.x]) atomicAdd(a.hist + (uint64_t)b * 256 + threadIdx.x, h[threadIdx.x]);
+}
+
+// one workgroup per bucket; lane 0 builds the Huffman lengths exactly as the header specifies (two smallest
+// live nodes, ties to the smaller id; weights halved until no length exceeds 12), then all threads derive
+// the canonical codes.  At most 256 leaves: the sequential part is a few ten thousand steps at worst.
+__global__ __launch_bounds__(kThreads) void vc_build_kernel(const ValueCodecArgs a) {
+    __shared__ unsigned long long weight[511];
+    __shared__ int parent[511];
+    __shared__ uint8_t alive[511];
+    __shared__ uint32_t w0[256];
+    __shared__ uint8_t len[256];
+    __shared__ uint32_t count_l[kVcMaxLen + 2];
+    const uint32_t b = blockIdx.x, s = threadIdx.x;
+    w0[s] = a.hist[(uint64_t)b * 256 + s];
+    len[s] = 0;
+    if (s < kVcMaxLen + 2) count_l[s] = 0;
+    __syncthreads();
+    if (s == 0) {
+        int used = 0;
+        for (int i = 0; i < 256; ++i) used += w0[i] != 0;
+        while (used > 0) {
+            int nnodes = 256;
+            for (int i = 0; i < 256; ++i) { weight[i] = w0[i]; alive[i] = w0[i] != 0; parent[i] = -1; }
+            int live = used;
+            while (live > 1) {
+                int x = -1, y = -1;
+                for (int i = 0; i < nnodes; ++i) {
+                    if (!alive[i]) continue;
+                    if (x < 0 || weight[i] < weight[x]) { y = x; x = i; }
+                    else if (y < 0 || weight[i] < weight[y]) { y = i; }
+                }
+                weight[nnodes] = weight[x] + weight[y];
+                alive[nnodes] = 1; parent[nnodes] = -1;
+                alive[x] = alive[y] = 0; parent[x] = parent[y] = nnodes;
+                ++nnodes; --live;
+            }
+            uint32_t maxlen = 0;
+            for (int i = 0; i < 256; ++i) {
+                if (!w0[i]) { len[i] = 0; continue; }
+                uint32_t d = 0;
+                for (int j = i; parent[j] >= 0; j = parent[j]) ++d;
+                if (used == 1) d = 1;
+                len[i] = (uint8_t)d;
+                maxlen = d > maxlen ? d : maxlen;
+            }
+            if (maxlen <= kVcMaxLen) break;
+            for (int i = 0; i < 256; ++i) if (w0[i]) w0[i] = (w0[i] + 1) / 2;
+        }
+    }
+    __syncthreads();
+    const uint32_t l = len[s];
+    a.lens[(uint64_t)b * 256 + s] = (uint8_t)l;
+    if (l) atomicAdd(&count_l[l], 1u);
+    __syncthreads();
+    // canonical code = first code of its length + number of smaller symbols of the same length
+    uint32_t first = 0, code = 0;
+    for (uint32_t j = 1; j <= kVcMaxLen; ++j) { if (j == l) first = code; code = (code + count_l[j]) << 1; }
+    uint32_t rank = 0;
+    for (uint32_t i = 0; i < s; ++i) rank += (len[i] == l) ? 1u : 0u;
+    const uint32_t c = first + rank;
+    a.rcode[(uint64_t)b * 256 + s] = l ? (__brev(c) >> (32 - l)) : 0u;
+}
+
+// per (bucket, chunk): codes of 8 consecutive values per thread, assembled in a 128-bit buffer, placed in
+// the chunk's LDS bit array at the offset a workgroup scan of the bit counts gives, then stored coalesced
+__global__ __launch_bounds__(kThreads) void vc_encode_kernel(const ValueCodecArgs a) {
+    __shared__ uint32_t s_rcode[256];
+    __shared__ uint8_t s_len[256];
+    __shared__ uint32_t s_words[kVcSlotWords + 4];
+    __shared__ uint32_t s_wave[kWaves];
+    const uint32_t b = blockIdx.x / a.nchunk, k = blockIdx.x - b * a.nchunk;
+    const uint64_t cnt = ((uint64_t)a.counts[b] < a.cap) ? a.counts[b] : a.cap;
+    const uint64_t r0 = (uint64_t)k * kVcChunk;
+    const uint64_t slot = (uint64_t)b * a.nchunk + k;
+    if (r0 >= cnt) { if (threadIdx.x == 0) a.chunk_words[slot] = 0; return; }
+    const uint32_t n = (uint32_t)((cnt - r0 < kVcChunk) ? (cnt - r0) : kVcChunk);
+    s_rcode[threadIdx.x] = a.rcode[(uint64_t)b * 256 + threadIdx.x];
+    s_len[threadIdx.x] = a.lens[(uint64_t)b * 256 + threadIdx.x];
+    for (uint32_t i = threadIdx.x; i < kVcSlotWords + 4; i += kThreads) s_words[i] = 0;
+    __syncthreads();
+    const uint16_t *v = a.V + (uint64_t)b * a.cap + r0;
+    uint8_t *lo = a.low + (uint64_t)b * a.cap + r0;
+    const uint32_t k0 = threadIdx.x * 8;
+    unsigned long long buf0 = 0, buf1 = 0;          // 128-bit bit buffer, stream order = ascending bit index
+    uint32_t nbits = 0;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+        if (k0 + j < n) {
+            const uint32_t x = v[k0 + j];
+            lo[k0 + j] = (uint8_t)(x & 0xFFu);
+            const uint32_t sym = x >> 8, l = s_len[sym];
+            const unsigned long long rc = s_rcode[sym];
+            if (nbits < 64) { buf0 |= rc << nbits; if (nbits + l > 64) buf1 |= rc >> (64 - nbits); }
+            else buf1 |= rc << (nbits - 64);
+            nbits += l;
+        }
+    }
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const uint32_t inc = wave_inclusive_scan(nbits);
+    if (lane == 63) s_wave[wave] = inc;
+    __syncthreads();
+    uint32_t start = inc - nbits, total = 0;
+#pragma unroll
+    for (int w = 0; w < kWaves; ++w) { start += (w < wave) ? s_wave[w] : 0u; total += s_wave[w]; }
+    if ((threadIdx.x & 7) == 0 && k0 < n) a.sub[slot * 32 + (threadIdx.x >> 3)] = (uint16_t)start;
+    if (nbits) {
+        const uint32_t w = start >> 5, sh = start & 31;
+        // the thread's bits shifted to their place: up to 96 + 31 bits -> four words
+        const uint32_t p0 = (uint32_t)buf0, p1 = (uint32_t)(buf0 >> 32), p2 = (uint32_t)buf1, p3 = (uint32_t)(buf1 >> 32);
+        atomicOr(&s_words[w], p0 << sh);
+        atomicOr(&s_words[w + 1], sh ? ((p0 >> (32 - sh)) | (p1 << sh)) : p1);
+        atomicOr(&s_words[w + 2], sh ? ((p1 >> (32 - sh)) | (p2 << sh)) : p2);
+        atomicOr(&s_words[w + 3], sh ? ((p2 >> (32 - sh)) | (p3 << sh)) : p3);
+        if (sh && (p3 >> (32 - sh))) atomicOr(&s_words[w + 4], p3 >> (32 - sh));
+    }
+    __syncthreads();
+    const uint32_t used = (total + 31) / 32;
+    uint32_t *out = a.bits + slot * kVcSlotWords;
+    for (uint32_t i = threadIdx.x; i < used; i += kThreads) out[i] = s_words[i];
+    if (threadIdx.x == 0) a.chunk_words[slot] = used;
+}
+
+// per (bucket, chunk): rebuild the code from its lengths, fill a 4096-entry table indexed by the next 12
+// stream bits, let 32 lanes decode 64 values each, write the values coalesced
+__global__ __launch_bounds__(kThreads) void vc_decode_kernel(const ValueCodecArgs a) {
+    __shared__ uint16_t s_lut[1u << kVcMaxLen];      // symbol << 4 | length
+    __shared__ uint8_t s_len[256];
+    __shared__ uint32_t count_l[kVcMaxLen + 2];
+    __shared__ uint32_t s_words[kVcSlotWords + 1];
+    __shared__ uint16_t s_out[kVcChunk];
+    const uint32_t b = blockIdx.x / a.nchunk, k = blockIdx.x - b * a.nchunk;
+    const uint64_t cnt = ((uint64_t)a.counts[b] < a.cap) ? a.counts[b] : a.cap;
+    const uint64_t r0 = (uint64_t)k * kVcChunk;
+    if (r0 >= cnt) return;
+    const uint32_t n = (uint32_t)((cnt - r0 < kVcChunk) ? (cnt - r0) : kVcChunk);
+    const uint64_t slot = (uint64_t)b * a.nchunk + k;
+    const uint32_t s = threadIdx.x;
+    const uint32_t l = a.lens[(uint64_t)b * 256 + s];
+    s_len[s] = (uint8_t)l;
+    if (s < kVcMaxLen + 2) count_l[s] = 0;
+    for (uint32_t i = s; i < (1u << kVcMaxLen); i += kThreads) s_lut[i] = 0;
+    uint32_t used = a.chunk_words[slot];
+    used = used > kVcSlotWords ? kVcSlotWords : used;
+    const uint32_t *in = a.bits + slot * kVcSlotWords;
+    for (uint32_t i = s; i < kVcSlotWords + 1; i += kThreads) s_words[i] = (i < used) ? in[i] : 0u;
+    __syncthreads();
+    if (l && l <= kVcMaxLen) atomicAdd(&count_l[l], 1u);
+    __syncthreads();
+    if (l && l <= kVcMaxLen) {
+        uint32_t first = 0, code = 0;
+        for (uint32_t j = 1; j <= kVcMaxLen; ++j) { if (j == l) first = code; code = (code + count_l[j]) << 1; }
+        uint32_t rank = 0;
+        for (uint32_t i = 0; i < s; ++i) rank += (s_len[i] == l) ? 1u : 0u;
+        const uint32_t rc = __brev(first + rank) >> (32 - l);
+        if (rc < (1u << l))                                        // a malformed length table cannot write outside
+            for (uint32_t hi = 0; hi < (1u << (kVcMaxLen - l)); ++hi) s_lut[rc | (hi << l)] = (uint16_t)((s << 4) | l);
+    }
+    __syncthreads();
+    bool bad = false;
+    if (s < 32 && s * kVcSub < n) {
+        uint32_t pos = a.sub[slot * 32 + s];
+        const uint8_t *lo = a.low + (uint64_t)b * a.cap + r0;
+        const uint32_t i1 = ((s + 1) * kVcSub < n) ? (s + 1) * kVcSub : n;
+        for (uint32_t i = s * kVcSub; i < i1; ++i) {
+            const uint32_t w = pos >> 5, sh = pos & 31;
+            uint32_t x = 0;
+            if (w < kVcSlotWords) x = (uint32_t)((((unsigned long long)s_words[w + 1] << 32) | s_words[w]) >> sh);
+            const uint32_t e = s_lut[x & ((1u << kVcMaxLen) - 1u)];
+            if ((e & 15u) == 0) { bad = true; break; }            // not a code of this table
+            pos += e & 15u;
+            s_out[i] = (uint16_t)(((e >> 4) << 8) | lo[i]);
+        }
+    }
+    __syncthreads();
+    uint16_t *out = a.V_out + (uint64_t)b * a.cap + r0;
+    for (uint32_t i = s; i < n; i += kThreads) out[i] = s_out[i];
+    if (bad) atomicOr(a.flags, kFlagBadIndex);
+}
+
+// ---------------------------------------------------------------------------------------------
 // small utilities
 // ---------------------------------------------------------------------------------------------
 __global__ void fill_u64_kernel(unsigned long long *p, uint64_t n, unsigned long long v) {

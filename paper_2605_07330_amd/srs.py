@@ -36,6 +36,7 @@ EXPORTS = [
     "srs_route", "srs_pack_dense_multi", "srs_unpack_dense_multi",
     "srs_extract_cast", "srs_extract_cast_multi", "srs_plan_layout",
     "srs_bitmap_words", "srs_mark_multi", "srs_cast_mark_multi", "srs_extract_marked_multi",
+    "srs_value_chunks", "srs_encode_values", "srs_decode_values",
 ]
 
 
@@ -79,11 +80,16 @@ _lib.srs_bitmap_words.restype = _u64
 _lib.srs_mark_multi.argtypes = [_vp, _vp, C.POINTER(TensorPair), _vp, _vp]
 _lib.srs_cast_mark_multi.argtypes = [_vp, _vp, C.POINTER(TensorPair), _vp, _vp]
 _lib.srs_extract_marked_multi.argtypes = [_vp, _vp, C.POINTER(Tensor), _vp, _vp, _vp, _vp, _u64, _vp]
+_lib.srs_value_chunks.argtypes = [_u64]
+_lib.srs_value_chunks.restype = _u64
+_lib.srs_encode_values.argtypes = [_vp, _vp, _vp, C.c_uint32, _u64, _vp, _vp, _vp, _vp, _vp, _vp]
+_lib.srs_decode_values.argtypes = [_vp, _vp, _vp, _vp, _vp, _vp, _vp, C.c_uint32, _u64, _vp, _vp]
 _lib.srs_route.argtypes = [_vp, _vp, C.c_uint32, _u64, _u64, _u64, C.c_uint32, C.c_uint32, _vp, _vp, _vp, _vp, _vp]
 _lib.srs_pack_dense_multi.argtypes = [_vp, _vp, C.POINTER(TensorPair), _vp, _vp, C.c_uint32, _vp, _vp]
 _lib.srs_unpack_dense_multi.argtypes = [_vp, _vp, C.POINTER(Tensor), _vp, _vp, C.c_uint32, _vp, _vp]
 for _n in EXPORTS:
-    if _n not in ("srs_strerror", "srs_stream_probe_sink_words", "srs_anchor_count", "srs_bitmap_words"):
+    if _n not in ("srs_strerror", "srs_stream_probe_sink_words", "srs_anchor_count", "srs_bitmap_words",
+                  "srs_value_chunks"):
         getattr(_lib, _n).restype = C.c_int
 
 
@@ -354,6 +360,26 @@ class Context:
         _check(_lib.srs_extract_marked_multi(self._h, plan._h, tensors, bitmap.data_ptr(), I.data_ptr(), V.data_ptr(),
                                              counts.data_ptr(), cap, _stream_ptr(stream)), "srs_extract_marked_multi")
 
+    # ---- value entropy coding -------------------------------------------------------------
+    def encode_values(self, V: torch.Tensor, counts: torch.Tensor, nbuckets: int, cap: int, enc: dict,
+                      stream: Optional[torch.cuda.Stream] = None) -> None:
+        """enc: the dict alloc_value_stream() returns."""
+        if not (V.is_cuda and V.element_size() == 2 and V.is_contiguous() and V.numel() >= nbuckets * cap):
+            raise TypeError("V: expected contiguous 16-bit GPU tensor of at least nb*cap elements")
+        _value_stream_ok(enc, nbuckets, cap)
+        _check(_lib.srs_encode_values(self._h, V.data_ptr(), counts.data_ptr(), nbuckets, cap, enc["lens"].data_ptr(),
+                                      enc["low"].data_ptr(), enc["bits"].data_ptr(), enc["chunk_words"].data_ptr(),
+                                      enc["sub"].data_ptr(), _stream_ptr(stream)), "srs_encode_values")
+
+    def decode_values(self, enc: dict, counts: torch.Tensor, nbuckets: int, cap: int, V_out: torch.Tensor,
+                      stream: Optional[torch.cuda.Stream] = None) -> None:
+        if not (V_out.is_cuda and V_out.element_size() == 2 and V_out.is_contiguous() and V_out.numel() >= nbuckets * cap):
+            raise TypeError("V_out: expected contiguous 16-bit GPU tensor of at least nb*cap elements")
+        _value_stream_ok(enc, nbuckets, cap)
+        _check(_lib.srs_decode_values(self._h, enc["lens"].data_ptr(), enc["low"].data_ptr(), enc["bits"].data_ptr(),
+                                      enc["chunk_words"].data_ptr(), enc["sub"].data_ptr(), counts.data_ptr(), nbuckets,
+                                      cap, V_out.data_ptr(), _stream_ptr(stream)), "srs_decode_values")
+
     # ---- 16-bit index coding --------------------------------------------------------------
     def encode_indices(self, I: torch.Tensor, counts: torch.Tensor, nbuckets: int, cap: int, base_stride: int,
                        D: torch.Tensor, max_gap: torch.Tensor, anchors: torch.Tensor,
@@ -442,6 +468,30 @@ class Context:
             raise ValueError("sink too small")
         _check(_lib.srs_stream_probe(self._h, a.data_ptr(), b.data_ptr(), nbytes, sink.data_ptr(), _stream_ptr(stream)),
                "srs_stream_probe")
+
+
+def value_chunks(cap: int) -> int:
+    return int(_lib.srs_value_chunks(cap))
+
+
+def alloc_value_stream(nbuckets: int, cap: int, device) -> dict:
+    """Device buffers of srs_encode_values' output, filled with 0xFF bytes so that tests see untouched entries."""
+    nchunk = value_chunks(cap)
+    return {"lens": torch.full((nbuckets, 256), -1, dtype=torch.int8, device=device).view(torch.uint8),
+            "low": torch.full((nbuckets, cap), -1, dtype=torch.int8, device=device).view(torch.uint8),
+            "bits": torch.full((nbuckets, nchunk, 768), -1, dtype=torch.int32, device=device),
+            "chunk_words": torch.full((nbuckets, nchunk), -1, dtype=torch.int32, device=device),
+            "sub": torch.full((nbuckets, nchunk, 32), -1, dtype=torch.int16, device=device)}
+
+
+def _value_stream_ok(enc: dict, nb: int, cap: int) -> None:
+    nchunk = value_chunks(cap)
+    need = {"lens": (1, nb * 256), "low": (1, nb * cap), "bits": (4, nb * nchunk * 768), "chunk_words": (4, nb * nchunk),
+            "sub": (2, nb * nchunk * 32)}
+    for name, (esize, n) in need.items():
+        t = enc[name]
+        if not (t.is_cuda and t.element_size() == esize and t.is_contiguous() and t.numel() >= n):
+            raise TypeError(f"{name}: expected contiguous GPU tensor of {n} elements of {esize} byte(s)")
 
 
 def alloc_encoded(nbuckets: int, cap: int, device) -> tuple:
