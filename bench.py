@@ -233,6 +233,9 @@ def main() -> int:
     ap.add_argument("--index-coding", action="store_true",
                     help="also run the 16-bit index coding of Sec. 3.3: extract, srs_encode_indices, then "
                          "srs_apply_multi_encoded instead of srs_apply_multi (not the headline path)")
+    ap.add_argument("--value-coding", action="store_true",
+                    help="also run the value entropy coding of Sec. 3.3: srs_encode_values after extract and "
+                         "srs_decode_values before apply (not the headline path)")
     ap.add_argument("--cast", action="store_true",
                     help="time the fused cast + diff instead (srs_extract_cast_multi on FP32 master weights that are "
                          "rebuilt, untimed, before every step; implies 3 resident sets: master, model parameters, "
@@ -313,6 +316,10 @@ def main() -> int:
 
     if args.index_coding:
         D, max_gap, anchors = srs.alloc_encoded(plan.nbuckets, cap, dev)
+    if args.value_coding:
+        venc = srs.alloc_value_stream(plan.nbuckets, cap, dev)
+        V2 = torch.empty_like(V)
+        vc_events = []
 
     def step(i, ev=None):
         d = i % 2
@@ -321,12 +328,22 @@ def main() -> int:
         ctx.extract_multi(plans[d], None, None, I, V, counts, cap, pairs=pairs[d])
         if args.index_coding:
             ctx.encode_indices(I, counts, plan.nbuckets, cap, 0, D, max_gap, anchors)
+        Vr = V
+        if args.value_coding:
+            q = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+            q[0].record()
+            ctx.encode_values(V, counts, plan.nbuckets, cap, venc)
+            q[1].record()
+            ctx.decode_values(venc, counts, plan.nbuckets, cap, V2)
+            q[2].record()
+            vc_events.append(q)
+            Vr = V2
         if ev:
             ev[1].record()
         if args.index_coding:
-            ctx.apply_multi_encoded(plans[d], None, D, I, V, counts, max_gap, anchors, cap, tensors=rolls[d])
+            ctx.apply_multi_encoded(plans[d], None, D, I, Vr, counts, max_gap, anchors, cap, tensors=rolls[d])
         else:
-            ctx.apply_multi(plans[d], None, I, V, counts, cap, tensors=rolls[d])
+            ctx.apply_multi(plans[d], None, I, Vr, counts, cap, tensors=rolls[d])
         if ev:
             ev[2].record()
 
@@ -378,6 +395,15 @@ def main() -> int:
         f"step {ms_per_step:.3f} ms; extract {ach:.0f} GB/s = {100 * ach / HBM_PEAK_GBS:.1f}% of peak; "
         f"combined {combined:.0f} GB/s = {100 * combined / HBM_PEAK_GBS:.1f}%")
 
+    if args.value_coding:
+        enc_ms = sum(q[0].elapsed_time(q[1]) for q in vc_events[-args.steps:]) / args.steps
+        dec_ms = sum(q[1].elapsed_time(q[2]) for q in vc_events[-args.steps:]) / args.steps
+        cw = venc["chunk_words"].to(torch.int64)
+        started = int((cw > 0).sum().item())
+        wire = 256 * plan.nbuckets + nchanged + 4 * int(cw.sum().item()) + 64 * started
+        log(f"value coding: encode {enc_ms:.3f} ms, decode {dec_ms:.3f} ms (both inside the extract figure above); "
+            f"value stream {wire / 1e9:.3f} GB against {2 * nchanged / 1e9:.3f} GB raw: alpha = {wire / (2 * nchanged):.4f}")
+
     probe_gbs = None
     if args.probe:
         nbytes = min(2 * N, 16 << 30) // 32768 * 32768
@@ -410,7 +436,7 @@ def main() -> int:
                          f"over the set; oracle extract {te:.2f}s + apply {ta:.2f}s, compute only"}
 
     default_run = not (args.tiny or args.density or args.tile or args.interleave or args.refresh_group >= 0
-                       or args.index_coding)
+                       or args.index_coding or args.value_coding)
     out = {
         "metric": "extract+apply dense GB/s scanned",
         "value": round(value, 1),

@@ -843,7 +843,8 @@ int srs_decode_values(srs_ctx *ctx, const uint8_t *lens, const uint8_t *low, con
     a.V_out = V_out; a.counts = counts; a.nb = nbuckets; a.cap = cap; a.nchunk = (uint32_t)nchunk;
     a.lens = const_cast<uint8_t *>(lens); a.low = const_cast<uint8_t *>(low); a.bits = const_cast<uint32_t *>(bits);
     a.chunk_words = const_cast<uint32_t *>(chunk_words); a.sub = const_cast<uint16_t *>(sub); a.flags = ctx->flags;
-    hipLaunchKernelGGL(vc_decode_kernel, dim3((uint32_t)((uint64_t)nbuckets * nchunk)), dim3(kThreads), 0, st, a);
+    const uint64_t groups = (nchunk + kVcDecodeChunks - 1) / kVcDecodeChunks;
+    hipLaunchKernelGGL(vc_decode_kernel, dim3((uint32_t)((uint64_t)nbuckets * groups)), dim3(kThreads), 0, st, a);
     SRS_HIP(hipGetLastError());
     return SRS_OK;
 }

@@ -907,7 +907,7 @@ __global__ __launch_bounds__(kThreads) void vc_hist_kernel(const ValueCodecArgs 
 __global__ __launch_bounds__(kThreads) void vc_build_kernel(const ValueCodecArgs a) {
     __shared__ unsigned long long weight[511];
     __shared__ int parent[511];
-    __shared__ uint8_t alive[511];
+    __shared__ uint16_t live[256];
     __shared__ uint32_t w0[256];
     __shared__ uint8_t len[256];
     __shared__ uint32_t count_l[kVcMaxLen + 2];
@@ -920,20 +920,25 @@ __global__ __launch_bounds__(kThreads) void vc_build_kernel(const ValueCodecArgs
         int used = 0;
         for (int i = 0; i < 256; ++i) used += w0[i] != 0;
         while (used > 0) {
-            int nnodes = 256;
-            for (int i = 0; i < 256; ++i) { weight[i] = w0[i]; alive[i] = w0[i] != 0; parent[i] = -1; }
-            int live = used;
-            while (live > 1) {
-                int x = -1, y = -1;
-                for (int i = 0; i < nnodes; ++i) {
-                    if (!alive[i]) continue;
-                    if (x < 0 || weight[i] < weight[x]) { y = x; x = i; }
-                    else if (y < 0 || weight[i] < weight[y]) { y = i; }
+            // live[]: ids of the nodes not merged yet (unordered); the two smallest by (weight, id) are merged
+            int nlive = 0, nnodes = 256;
+            for (int i = 0; i < 256; ++i) {
+                parent[i] = -1;
+                if (w0[i]) { weight[i] = w0[i]; live[nlive++] = (uint16_t)i; }
+            }
+            while (nlive > 1) {
+                int px = -1, py = -1;                                // positions in live[] of the smallest, second smallest
+                for (int p = 0; p < nlive; ++p) {
+                    const int i = live[p];
+                    if (px < 0 || weight[i] < weight[live[px]] || (weight[i] == weight[live[px]] && i < live[px])) { py = px; px = p; }
+                    else if (py < 0 || weight[i] < weight[live[py]] || (weight[i] == weight[live[py]] && i < live[py])) { py = p; }
                 }
+                const int x = live[px], y = live[py];
                 weight[nnodes] = weight[x] + weight[y];
-                alive[nnodes] = 1; parent[nnodes] = -1;
-                alive[x] = alive[y] = 0; parent[x] = parent[y] = nnodes;
-                ++nnodes; --live;
+                parent[nnodes] = -1; parent[x] = parent[y] = nnodes;
+                live[px] = (uint16_t)nnodes;                         // the merged node takes one slot, the last entry the other
+                live[py] = live[nlive - 1];
+                --nlive; ++nnodes;
             }
             uint32_t maxlen = 0;
             for (int i = 0; i < 256; ++i) {
@@ -1021,60 +1026,77 @@ __global__ __launch_bounds__(kThreads) void vc_encode_kernel(const ValueCodecArg
     if (threadIdx.x == 0) a.chunk_words[slot] = used;
 }
 
-// per (bucket, chunk): rebuild the code from its lengths, fill a 4096-entry table indexed by the next 12
-// stream bits, let 32 lanes decode 64 values each, write the values coalesced
+// per (bucket, group of kVcDecodeChunks chunks): rebuild the code from its lengths, fill a 4096-entry table
+// indexed by the next 12 stream bits, then for each chunk let 32 lanes decode 64 values each and write the values
+// (decoded high byte | stored low byte) coalesced
+constexpr uint32_t kVcDecodeChunks = 8;
+
 __global__ __launch_bounds__(kThreads) void vc_decode_kernel(const ValueCodecArgs a) {
     __shared__ uint16_t s_lut[1u << kVcMaxLen];      // symbol << 4 | length
-    __shared__ uint8_t s_len[256];
-    __shared__ uint32_t count_l[kVcMaxLen + 2];
+    __shared__ uint32_t s_cnt[kVcMaxLen + 1][kWaves];
     __shared__ uint32_t s_words[kVcSlotWords + 1];
-    __shared__ uint16_t s_out[kVcChunk];
-    const uint32_t b = blockIdx.x / a.nchunk, k = blockIdx.x - b * a.nchunk;
+    __shared__ uint8_t s_sym[kVcChunk];
+    const uint32_t groups = (a.nchunk + kVcDecodeChunks - 1) / kVcDecodeChunks;
+    const uint32_t b = blockIdx.x / groups, g = blockIdx.x - b * groups;
     const uint64_t cnt = ((uint64_t)a.counts[b] < a.cap) ? a.counts[b] : a.cap;
-    const uint64_t r0 = (uint64_t)k * kVcChunk;
-    if (r0 >= cnt) return;
-    const uint32_t n = (uint32_t)((cnt - r0 < kVcChunk) ? (cnt - r0) : kVcChunk);
-    const uint64_t slot = (uint64_t)b * a.nchunk + k;
+    if ((uint64_t)g * kVcDecodeChunks * kVcChunk >= cnt) return;
     const uint32_t s = threadIdx.x;
-    const uint32_t l = a.lens[(uint64_t)b * 256 + s];
-    s_len[s] = (uint8_t)l;
-    if (s < kVcMaxLen + 2) count_l[s] = 0;
+    const int lane = s & 63, wave = s >> 6;
+    uint32_t l = a.lens[(uint64_t)b * 256 + s];
+    if (l > kVcMaxLen) l = 0;                        // not a length this format can hold: treated as absent
     for (uint32_t i = s; i < (1u << kVcMaxLen); i += kThreads) s_lut[i] = 0;
-    uint32_t used = a.chunk_words[slot];
-    used = used > kVcSlotWords ? kVcSlotWords : used;
-    const uint32_t *in = a.bits + slot * kVcSlotWords;
-    for (uint32_t i = s; i < kVcSlotWords + 1; i += kThreads) s_words[i] = (i < used) ? in[i] : 0u;
+    // canonical code of symbol s = first code of its length + number of smaller symbols of that length
+    uint32_t rank = 0;
+    for (uint32_t j = 1; j <= kVcMaxLen; ++j) {
+        const unsigned long long m = __ballot(l == j);
+        if (l == j) rank = __builtin_popcountll(m & ((1ull << lane) - 1ull));
+        if (lane == 0) s_cnt[j][wave] = (uint32_t)__builtin_popcountll(m);
+    }
     __syncthreads();
-    if (l && l <= kVcMaxLen) atomicAdd(&count_l[l], 1u);
-    __syncthreads();
-    if (l && l <= kVcMaxLen) {
+    if (l) {
         uint32_t first = 0, code = 0;
-        for (uint32_t j = 1; j <= kVcMaxLen; ++j) { if (j == l) first = code; code = (code + count_l[j]) << 1; }
-        uint32_t rank = 0;
-        for (uint32_t i = 0; i < s; ++i) rank += (s_len[i] == l) ? 1u : 0u;
+        for (uint32_t j = 1; j <= kVcMaxLen; ++j) {
+            uint32_t cj = 0;
+#pragma unroll
+            for (int w = 0; w < kWaves; ++w) { cj += s_cnt[j][w]; if (j == l && w < wave) rank += s_cnt[j][w]; }
+            if (j == l) first = code;
+            code = (code + cj) << 1;
+        }
         const uint32_t rc = __brev(first + rank) >> (32 - l);
-        if (rc < (1u << l))                                        // a malformed length table cannot write outside
+        if (rc < (1u << l))                          // a malformed length table cannot write outside the table
             for (uint32_t hi = 0; hi < (1u << (kVcMaxLen - l)); ++hi) s_lut[rc | (hi << l)] = (uint16_t)((s << 4) | l);
     }
-    __syncthreads();
     bool bad = false;
-    if (s < 32 && s * kVcSub < n) {
-        uint32_t pos = a.sub[slot * 32 + s];
-        const uint8_t *lo = a.low + (uint64_t)b * a.cap + r0;
-        const uint32_t i1 = ((s + 1) * kVcSub < n) ? (s + 1) * kVcSub : n;
-        for (uint32_t i = s * kVcSub; i < i1; ++i) {
-            const uint32_t w = pos >> 5, sh = pos & 31;
-            uint32_t x = 0;
-            if (w < kVcSlotWords) x = (uint32_t)((((unsigned long long)s_words[w + 1] << 32) | s_words[w]) >> sh);
-            const uint32_t e = s_lut[x & ((1u << kVcMaxLen) - 1u)];
-            if ((e & 15u) == 0) { bad = true; break; }            // not a code of this table
-            pos += e & 15u;
-            s_out[i] = (uint16_t)(((e >> 4) << 8) | lo[i]);
+    for (uint32_t kk = 0; kk < kVcDecodeChunks; ++kk) {
+        const uint32_t k = g * kVcDecodeChunks + kk;
+        const uint64_t r0 = (uint64_t)k * kVcChunk;
+        if (k >= a.nchunk || r0 >= cnt) break;       // uniform
+        const uint32_t n = (uint32_t)((cnt - r0 < kVcChunk) ? (cnt - r0) : kVcChunk);
+        const uint64_t slot = (uint64_t)b * a.nchunk + k;
+        uint32_t used = a.chunk_words[slot];
+        used = used > kVcSlotWords ? kVcSlotWords : used;
+        const uint32_t *in = a.bits + slot * kVcSlotWords;
+        __syncthreads();                             // table ready / previous chunk's buffers free
+        for (uint32_t i = s; i < kVcSlotWords + 1; i += kThreads) s_words[i] = (i < used) ? in[i] : 0u;
+        __syncthreads();
+        if (s < 32 && s * kVcSub < n) {
+            uint32_t pos = a.sub[slot * 32 + s];
+            const uint32_t i1 = ((s + 1) * kVcSub < n) ? (s + 1) * kVcSub : n;
+            for (uint32_t i = s * kVcSub; i < i1; ++i) {
+                const uint32_t w = pos >> 5, sh = pos & 31;
+                uint32_t x = 0;
+                if (w < kVcSlotWords) x = (uint32_t)((((unsigned long long)s_words[w + 1] << 32) | s_words[w]) >> sh);
+                const uint32_t e = s_lut[x & ((1u << kVcMaxLen) - 1u)];
+                if ((e & 15u) == 0) { bad = true; break; }        // not a code of this table
+                pos += e & 15u;
+                s_sym[i] = (uint8_t)(e >> 4);
+            }
         }
+        __syncthreads();
+        const uint8_t *lo = a.low + (uint64_t)b * a.cap + r0;
+        uint16_t *out = a.V_out + (uint64_t)b * a.cap + r0;
+        for (uint32_t i = s; i < n; i += kThreads) out[i] = (uint16_t)(((uint32_t)s_sym[i] << 8) | lo[i]);
     }
-    __syncthreads();
-    uint16_t *out = a.V_out + (uint64_t)b * a.cap + r0;
-    for (uint32_t i = s; i < n; i += kThreads) out[i] = s_out[i];
     if (bad) atomicOr(a.flags, kFlagBadIndex);
 }
 
