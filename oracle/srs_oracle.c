@@ -44,7 +44,10 @@
  * Further down: index delta coding (pinned to numpy diff / cumsum, the 2^15
  * width rule, the paper's 3.2 B per changed element), density routing (brute
  * force of the Eq. (1) break-even), fused cast + diff (rounding pinned to a
- * library cast on every non-NaN class of input; fused == cast then extract).
+ * library cast on every non-NaN class of input; fused == cast then extract),
+ * the cumulative index set of Alg. 1 (brute-force unions), value entropy coding
+ * (prefix-free, optimal cost, entropy bound, the construction rule restated
+ * independently, alpha against the paper's printed range).
  * parity unpinned: only the BF16 pattern a NaN master weight rounds to (0x7FC0
  * here) -- the paper is silent and library casts disagree on it.
  */
