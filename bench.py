@@ -31,7 +31,7 @@ HBM_PEAK_GBS = 8000.0
 # HBM traffic per extract launch measured with rocprofv3 --pmc (FETCH_SIZE x 2.00 + WRITE_SIZE x 1.00, the
 # factors from a 61.06 GB copy in the same runs): profiles/extract_apply_qwen3-30b-a3b.md.  Only the workload
 # that was profiled has a figure.
-MEASURED_TRAFFIC_BYTES = {"qwen3-30b-a3b": 142.8e9}
+MEASURED_TRAFFIC_BYTES = {"qwen3-30b-a3b": 133.3e9}
 
 
 def log(msg: str) -> None:
@@ -100,6 +100,8 @@ def bench_cast(args, torch, srs, synth, wl, dev) -> int:
     ctx = srs.Context(0)
     if args.tile:
         ctx.set_option(srs.OPT_TILE_ELEMS, args.tile)
+    if args.interleave:
+        ctx.set_option(srs.OPT_INTERLEAVE, args.interleave)
     plan = ctx.plan(W.numels, wl.bucket_elems)
     cap = (synth.payload_capacity(wl) + 7) // 8 * 8
     I = torch.empty((plan.nbuckets, cap), dtype=torch.int32, device=dev)
@@ -159,8 +161,10 @@ def bench_cumulative(args, torch, srs, synth, wl, dev) -> int:
     R.copy_from(A)
     rho = nchanged / N
     ctx = srs.Context(0)
-    if args.tile:
-        ctx.set_option(srs.OPT_TILE_ELEMS, args.tile)
+    # extract from the bitmap streams half the bytes per element of the snapshot form and measures best with
+    # smaller tiles spread over more buckets (14.0 ms against 16.7 ms at the library defaults)
+    ctx.set_option(srs.OPT_TILE_ELEMS, args.tile or 16384)
+    ctx.set_option(srs.OPT_INTERLEAVE, args.interleave or 1024)
     plans = [ctx.plan(A.numels, wl.bucket_elems), ctx.plan(A.numels, wl.bucket_elems)]
     cap = (synth.payload_capacity(wl) + 7) // 8 * 8
     nb = plans[0].nbuckets
@@ -451,7 +455,7 @@ def main() -> int:
         "dtype": "u16",
         "data": "synthetic",
         "config": {"workload": wl.name, "elements": N, "buckets": plan.nbuckets, "bucket_elems": wl.bucket_elems,
-                   "changed_fraction": round(rho, 6), "payload_cap": cap, "tile_elems": args.tile or 16384,
+                   "changed_fraction": round(rho, 6), "payload_cap": cap, "tile_elems": args.tile or 32768,
                    "index_coding": bool(args.index_coding)},
         "sync_ms": round(ms_per_step, 4),
         "extract_ms": round(ext_avg, 4),

@@ -57,12 +57,12 @@ typedef enum {
 
 /* options for srs_set_option() */
 #define SRS_OPT_SPIN_LIMIT 1   /* max polls of a predecessor tile before SRS_FLAG_TIMEOUT (default 1<<24) */
-#define SRS_OPT_TILE_ELEMS 2   /* elements per extract tile: 4096, 8192, 16384 or 32768 (tuning; affects
+#define SRS_OPT_TILE_ELEMS 2   /* elements per extract tile: 4096, 8192, 16384 or 32768 (default; tuning; affects
                                   plans created afterwards) */
-#define SRS_OPT_REFRESH_GROUP 3 /* snapshot refresh granularity in 16-byte lanes: 0 = element-wise 2-byte stores,
-                                  4 = whole aligned 64 bytes around a change, 8 = 128 bytes (tuning) */
+#define SRS_OPT_REFRESH_GROUP 3 /* snapshot refresh granularity in 16-byte lanes: 0 = element-wise 2-byte stores
+                                  (default), 4 = whole aligned 64 bytes around a change, 8 = 128 bytes (tuning) */
 #define SRS_OPT_INTERLEAVE 4   /* buckets whose tiles are interleaved over consecutive workgroups, 1..4096
-                                  (tuning; affects plans created afterwards) */
+                                  (default 64; tuning; affects plans created afterwards) */
 
 typedef struct srs_ctx srs_ctx;    /* per-stream scratch: tile status words, per-bucket ticket counters, flag word */
 typedef struct srs_plan srs_plan;  /* immutable bucket / segment / tile tables of one tensor list */

@@ -34,9 +34,9 @@ struct srs_ctx {
     uint32_t *vc_scratch = nullptr;         // value codec: per-bucket histograms and codes
     uint64_t vc_cap = 0;                    // in words
     uint32_t spin_limit = 1u << 24;
-    uint32_t tile_elems = 16384;
-    uint32_t group = 1024;                  // buckets whose tiles are interleaved over consecutive workgroups
-    uint32_t refresh_group = 4;             // lanes (x16 bytes) rewritten around a change by the snapshot refresh
+    uint32_t tile_elems = 32768;
+    uint32_t group = 64;                    // buckets whose tiles are interleaved over consecutive workgroups
+    uint32_t refresh_group = 0;             // 0: element-wise refresh; 4 / 8: lanes (x16 bytes) rewritten around a change
 };
 
 struct srs_plan {

@@ -127,7 +127,7 @@ def _payload_ok(I: torch.Tensor, V: torch.Tensor, counts: torch.Tensor, nb: int,
         raise TypeError("counts: expected contiguous 32-bit GPU tensor of at least nb elements")
 
 
-def plan_layout(numel: Sequence[int], bucket_elems: int, tile_elems: int = 16384, interleave: int = 1024) -> dict:
+def plan_layout(numel: Sequence[int], bucket_elems: int, tile_elems: int = 32768, interleave: int = 64) -> dict:
     """Host-only view of the tables a plan holds (numpy arrays); needs no GPU."""
     import numpy as np
     numel = [int(x) for x in numel]

@@ -69,9 +69,11 @@ def test_tables_partition_the_packed_space(numel, be, tile, il):
 def test_benchmark_workload_counts():
     wl = synth.workload(2)
     L = srs.plan_layout([t.numel for t in wl.tensors], wl.bucket_elems)
-    assert L["nbuckets"] == 910 and len(L["tiles"]) == 1863520 and len(L["segs"]) == 19438
+    assert L["nbuckets"] == 910 and len(L["tiles"]) == 931760 and len(L["segs"]) == 19438
     assert int(L["tiles"][:, 3].astype(np.int64).sum()) == wl.numel
-    assert np.all(L["tiles"][:, 3] == 16384)                  # every tensor of the set is a multiple of a tile
+    assert np.all(L["tiles"][:, 3] == 32768)                  # every tensor of the set is a multiple of a tile
+    L2 = srs.plan_layout([t.numel for t in wl.tensors], wl.bucket_elems, tile_elems=16384, interleave=1024)
+    assert len(L2["tiles"]) == 1863520 and np.array_equal(L2["segs"], L["segs"])
     assert np.all(L["tiles"][:, 1] % 8 == 0)                  # 16-byte aligned tile starts: the vector path
 
 
