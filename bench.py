@@ -151,6 +151,51 @@ def bench_cast(args, torch, srs, synth, wl, dev) -> int:
     return 0
 
 
+def chunked_sum(torch, flat) -> int:
+    """Sum of the 16-bit patterns of a weight slab, in pieces that keep the temporaries small."""
+    v = flat.view(torch.int16)
+    return sum(int(v[i:i + (1 << 28)].sum(dtype=torch.int64).item()) for i in range(0, v.numel(), 1 << 28))
+
+
+def rotating_leg(args, torch, srs, wl, versions, R, payload, cap, i0, nchanged, rho, N):
+    """Extract + apply with SRS_OPT_SNAPSHOT = 1: each version is diffed, read-only, against the other one."""
+    I, V, counts = payload
+    ctx = srs.Context(0)
+    ctx.set_option(srs.OPT_SNAPSHOT, srs.SNAPSHOT_ROTATE)
+    ctx.set_option(srs.OPT_TILE_ELEMS, 16384)        # with no stores into the weights this mode measures best with
+    ctx.set_option(srs.OPT_INTERLEAVE, 1024)         # smaller tiles spread over all buckets
+    plans = [ctx.plan(R.numels, wl.bucket_elems) for _ in (0, 1)]
+    pairs = [ctx.bind_pairs(plans[d], versions[1 - d].tensors, versions[d].tensors) for d in (0, 1)]
+    rolls = [ctx.bind_weights(plans[d], R.tensors) for d in (0, 1)]
+    steps = max(2, args.steps // 2 * 2)
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(steps + 2)]
+    for k in range(steps + 2):                       # the first two are warm-up
+        d = (i0 + k) % 2
+        ev[k][0].record()
+        ctx.extract_multi(plans[d], None, None, I, V, counts, cap, pairs=pairs[d])
+        ev[k][1].record()
+        ctx.apply_multi(plans[d], None, I, V, counts, cap, tensors=rolls[d])
+        ev[k][2].record()
+    torch.cuda.synchronize()
+    flags = ctx.status()
+    last = versions[(i0 + steps + 1) % 2]
+    total = int(counts.to(torch.int64).sum().item())
+    if not args.no_check and (flags or total != nchanged or not torch.equal(R.flat.view(torch.int16), last.flat.view(torch.int16))):
+        raise SystemExit(f"bench self-check failed (rotating snapshot): flags={flags} counts={total} expected={nchanged}")
+    ext = sum(e[0].elapsed_time(e[1]) for e in ev[2:]) / steps
+    app = sum(e[1].elapsed_time(e[2]) for e in ev[2:]) / steps
+    ach = (4.0 + 6.0 * rho) * N / (ext * 1e-3) / 1e9
+    log(f"rotating snapshot: extract {ext:.3f} ms = {ach:.0f} GB/s on (4 + 6 rho) N bytes = {100 * ach / HBM_PEAK_GBS:.1f}% "
+        f"of peak, apply {app:.3f} ms")
+    for pl in plans:
+        pl.close()
+    ctx.close()
+    return {"extract_ms": round(ext, 4), "apply_ms": round(app, 4), "sync_ms": round(ext + app, 4),
+            "achieved": round(ach, 1), "frac": round(ach / HBM_PEAK_GBS, 4), "steps": steps,
+            "value": round(4.0 * N / ((ext + app) * 1e-3) / 1e9, 1),
+            "note": "extract leaves the snapshot untouched; the two resident BF16 versions swap roles every step"}
+
+
 def bench_cumulative(args, torch, srs, synth, wl, dev) -> int:
     """Alg. 1 as printed, one optimizer step per synchronisation: mark (diff of two resident versions OR-ed into
     the bitmap), extract from the bitmap with the current values, apply.  The two versions swap roles every cycle."""
@@ -247,6 +292,10 @@ def main() -> int:
     ap.add_argument("--cumulative", action="store_true",
                     help="time Alg. 1 as printed instead: srs_mark_multi (one optimizer step's diff OR-ed into the bitmap), "
                          "srs_extract_marked_multi, srs_apply_multi -- not the headline path")
+    ap.add_argument("--rotate-snapshot", action="store_true",
+                    help="SRS_OPT_SNAPSHOT = 1: extract leaves the snapshot alone and the two resident BF16 versions "
+                         "swap roles every step (the new weights of one step are the snapshot of the next) -- "
+                         "not the headline contract, which refreshes the snapshot in place")
     ap.add_argument("--regen", action="store_true",
                     help="keep one new-weights version and rebuild it (untimed) before every step instead of "
                          "alternating two resident versions: 3 weight sets instead of 4, for workloads that do not "
@@ -279,8 +328,18 @@ def main() -> int:
     if args.cumulative:
         return bench_cumulative(args, torch, srs, synth, wl, dev)
 
+    if args.rotate_snapshot and args.regen:
+        print("bench.py: --rotate-snapshot alternates two resident versions; it cannot be combined with --regen",
+              file=sys.stderr)
+        return 2
     t0 = time.perf_counter()
-    if args.regen:
+    if args.rotate_snapshot:
+        W0 = synth.WeightSet(wl, dev); W1 = synth.WeightSet(wl, dev); R = synth.WeightSet(wl, dev)
+        synth.fill_base(W0, args.seed)
+        nchanged, _ = synth.make_update(W1, W0, args.seed)
+        R.copy_from(W0)
+        S = W0                                   # only for its shape list below; never bound as a snapshot
+    elif args.regen:
         S = synth.WeightSet(wl, dev); W1 = synth.WeightSet(wl, dev); R = synth.WeightSet(wl, dev)
         synth.fill_base(S, args.seed)
         nchanged, _ = synth.make_update(W1, S, args.seed)
@@ -302,6 +361,11 @@ def main() -> int:
     if args.refresh_group >= 0:
         ctx.set_option(srs.OPT_REFRESH_GROUP, args.refresh_group)
     ctx.set_option(srs.OPT_INTERLEAVE, args.interleave) if args.interleave else None
+    if args.rotate_snapshot:
+        ctx.set_option(srs.OPT_SNAPSHOT, srs.SNAPSHOT_ROTATE)
+        # with no stores into the weights this mode measures best with smaller tiles spread over all buckets
+        ctx.set_option(srs.OPT_TILE_ELEMS, args.tile or 16384)
+        ctx.set_option(srs.OPT_INTERLEAVE, args.interleave or 1024)
     # one plan per direction: each keeps its own device copy of the pointer table, so alternating the
     # `new` version does not re-upload it every step
     plans = [ctx.plan(S.numels, wl.bucket_elems), ctx.plan(S.numels, wl.bucket_elems)]
@@ -315,7 +379,11 @@ def main() -> int:
         f"({plan.nbuckets * cap * 6 / 1e9:.2f} GB payload buffers)")
 
     versions = [W1, W0]
-    pairs = [ctx.bind_pairs(plans[d], S.tensors, versions[d].tensors) for d in (0, 1)]
+    if args.rotate_snapshot:                     # step d diffs versions[d] against the other version, read-only
+        pairs = [ctx.bind_pairs(plans[d], versions[1 - d].tensors, versions[d].tensors) for d in (0, 1)]
+        sums_before = [chunked_sum(torch, w.flat) for w in versions]
+    else:
+        pairs = [ctx.bind_pairs(plans[d], S.tensors, versions[d].tensors) for d in (0, 1)]
     rolls = [ctx.bind_weights(plans[d], R.tensors) for d in (0, 1)]
 
     if args.index_coding:
@@ -380,7 +448,11 @@ def main() -> int:
     flags = ctx.status()
     last_new = W1 if args.regen else versions[(args.warmup + args.steps - 1) % 2]
     total_counts = int(counts.to(torch.int64).sum().item())
-    ok = flags == 0 and total_counts == nchanged and torch.equal(S.flat.view(torch.int16), last_new.flat.view(torch.int16)) \
+    if args.rotate_snapshot:                     # neither version may have been written
+        snap_ok = sums_before == [chunked_sum(torch, w.flat) for w in versions]
+    else:
+        snap_ok = torch.equal(S.flat.view(torch.int16), last_new.flat.view(torch.int16))
+    ok = flags == 0 and total_counts == nchanged and snap_ok \
         and torch.equal(R.flat.view(torch.int16), last_new.flat.view(torch.int16))
     if not ok and not args.no_check:
         raise SystemExit(f"bench self-check failed: flags={flags} counts={total_counts} expected={nchanged}")
@@ -389,7 +461,8 @@ def main() -> int:
     app_ms = [e[1].elapsed_time(e[2]) for e in events]
     ext_avg, app_avg = sum(ext_ms) / len(ext_ms), sum(app_ms) / len(app_ms)
     ms_per_step = (ext_avg + app_avg) if args.regen else wall * 1e3 / args.steps
-    bytes_extract = (4.0 + 8.0 * rho) * N          # read old+new; write I(4)+V(2) and snapshot(2) per changed element
+    # read old+new; write I(4)+V(2) and, unless the caller rotates buffers, snapshot(2) per changed element
+    bytes_extract = (4.0 + (6.0 if args.rotate_snapshot else 8.0) * rho) * N
     bytes_apply = 8.0 * rho * N                    # read I+V, write 2 per changed element
     value = 4.0 * N / (ms_per_step * 1e-3) / 1e9
     ach = bytes_extract / (ext_avg * 1e-3) / 1e9
@@ -423,6 +496,13 @@ def main() -> int:
         probe_gbs = 2 * nbytes * 5 / (e0.elapsed_time(e1) * 1e-3) / 1e9
         log(f"two-stream read probe: {probe_gbs:.0f} GB/s")
 
+    # the same workload under the rotating-snapshot contract (SRS_OPT_SNAPSHOT = 1), reported beside the
+    # headline: an even number of steps, so that the rollout copy ends where it started
+    rotating = None
+    if not (args.regen or args.rotate_snapshot or args.index_coding or args.value_coding or args.tiny):
+        rotating = rotating_leg(args, torch, srs, wl, versions, R, (I, V, counts), cap, args.warmup + args.steps,
+                                nchanged, rho, N)
+
     cpu = None
     if not args.no_cpu_baseline and not args.regen:
         import oracle
@@ -440,7 +520,7 @@ def main() -> int:
                          f"over the set; oracle extract {te:.2f}s + apply {ta:.2f}s, compute only"}
 
     default_run = not (args.tiny or args.density or args.tile or args.interleave or args.refresh_group >= 0
-                       or args.index_coding or args.value_coding)
+                       or args.index_coding or args.value_coding or args.rotate_snapshot)
     out = {
         "metric": "extract+apply dense GB/s scanned",
         "value": round(value, 1),
@@ -455,8 +535,9 @@ def main() -> int:
         "dtype": "u16",
         "data": "synthetic",
         "config": {"workload": wl.name, "elements": N, "buckets": plan.nbuckets, "bucket_elems": wl.bucket_elems,
-                   "changed_fraction": round(rho, 6), "payload_cap": cap, "tile_elems": args.tile or 32768,
-                   "index_coding": bool(args.index_coding)},
+                   "changed_fraction": round(rho, 6), "payload_cap": cap, "tile_elems": args.tile or (16384 if args.rotate_snapshot else 32768),
+                   "index_coding": bool(args.index_coding),
+                   "snapshot": "rotate" if args.rotate_snapshot else "refresh-in-place"},
         "sync_ms": round(ms_per_step, 4),
         "extract_ms": round(ext_avg, 4),
         "apply_ms": round(app_avg, 4),
@@ -468,6 +549,7 @@ def main() -> int:
                      "unit": "GB/s", "frac": round(ach / HBM_PEAK_GBS, 4),
                      "traffic": MEASURED_TRAFFIC_BYTES.get(wl.name) if default_run else None},
         "cpu_baseline": cpu,
+        "rotating_snapshot": rotating,
         "checked": not args.no_check,
     }
     print(json.dumps(out), flush=True)

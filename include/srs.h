@@ -63,6 +63,12 @@ typedef enum {
                                   (default), 4 = whole aligned 64 bytes around a change, 8 = 128 bytes (tuning) */
 #define SRS_OPT_INTERLEAVE 4   /* buckets whose tiles are interleaved over consecutive workgroups, 1..4096
                                   (default 64; tuning; affects plans created afterwards) */
+#define SRS_OPT_SNAPSHOT 5     /* what srs_extract / srs_extract_multi do with the snapshot:
+                                  0 (default) refresh it in place, so that old_snapshot == new_w afterwards;
+                                  1 leave it untouched: the caller rotates buffers instead, i.e. new_w IS the
+                                  snapshot of the next call and the Trainer's next cast writes into the buffer
+                                  that held old_snapshot (same two resident BF16 copies, no scattered stores
+                                  into the weights; Alg. 1's W_prev without the clone).  Payload identical. */
 
 typedef struct srs_ctx srs_ctx;    /* per-stream scratch: tile status words, per-bucket ticket counters, flag word */
 typedef struct srs_plan srs_plan;  /* immutable bucket / segment / tile tables of one tensor list */

@@ -37,6 +37,7 @@ struct srs_ctx {
     uint32_t tile_elems = 32768;
     uint32_t group = 64;                    // buckets whose tiles are interleaved over consecutive workgroups
     uint32_t refresh_group = 0;             // 0: element-wise refresh; 4 / 8: lanes (x16 bytes) rewritten around a change
+    bool rotate_snapshot = false;           // true: extract leaves the snapshot alone, the caller swaps buffers
 };
 
 struct srs_plan {
@@ -98,6 +99,7 @@ int launch_extract(const srs_ctx *ctx, uint32_t tile_elems, const ExtractArgs &a
     do {                                                                                                              \
         if (src == kSrcFp32) hipLaunchKernelGGL((extract_kernel<VV, MULTI, 4, kSrcFp32>), grid, block, 0, st, a);     \
         else if (src == kSrcBitmap) hipLaunchKernelGGL((extract_kernel<VV, MULTI, 0, kSrcBitmap>), grid, block, 0, st, a); \
+        else if (ctx->rotate_snapshot) hipLaunchKernelGGL((extract_kernel<VV, MULTI, -1>), grid, block, 0, st, a);    \
         else if (ctx->refresh_group == 8) hipLaunchKernelGGL((extract_kernel<VV, MULTI, 8>), grid, block, 0, st, a);  \
         else if (ctx->refresh_group == 4) hipLaunchKernelGGL((extract_kernel<VV, MULTI, 4>), grid, block, 0, st, a);  \
         else hipLaunchKernelGGL((extract_kernel<VV, MULTI, 0>), grid, block, 0, st, a);                               \
@@ -385,6 +387,9 @@ int srs_set_option(srs_ctx *ctx, int option, uint64_t value) {
         case SRS_OPT_INTERLEAVE:
             if (value == 0 || value > 4096) return SRS_ERR_INVALID;
             ctx->group = (uint32_t)value; return SRS_OK;
+        case SRS_OPT_SNAPSHOT:
+            if (value > 1) return SRS_ERR_INVALID;
+            ctx->rotate_snapshot = value == 1; return SRS_OK;
         default: return SRS_ERR_INVALID;
     }
 }

@@ -247,7 +247,8 @@ __device__ __forceinline__ uint32_t look_back(const ExtractArgs &a, uint32_t til
 // ---------------------------------------------------------------------------------------------
 // RG = lanes per snapshot-refresh group: 0 refreshes element by element (2-byte stores); 4 / 8 rewrite
 // the whole aligned 64 / 128 bytes around a change from the new weights (unchanged elements get the
-// value they already hold), so that the memory system sees full-sector writes instead of masked ones.
+// value they already hold), so that the memory system sees full-sector writes instead of masked ones;
+// -1 does not touch the snapshot at all (the caller rotates buffers: `new` is the next call's `old`).
 // CAST: `new` is not a BF16 buffer but the FP32 master weights; each element is rounded to BF16
 // (nearest even, NaN -> 0x7FC0) on the fly and `old` is the model-parameter buffer itself: the cast-and-
 // copy of Alg. 1 fused with its diff, so that no snapshot exists at all.
@@ -499,7 +500,7 @@ __global__ __launch_bounds__(kThreads) void extract_kernel(const ExtractArgs a) 
             const uint64_t r = (uint64_t)excl + r0 + k;
             if (local < len) {                      // always true for a correct scan; keeps stores in bounds
                 if (r < a.cap) { Ib[r] = (int32_t)(idx_base + local); Vb[r] = val; }
-                if (!MARKED && !group_refresh) po[local] = val;   // snapshot refresh: W_prev <- W at changed positions
+                if (!MARKED && RG >= 0 && !group_refresh) po[local] = val;   // snapshot refresh: W_prev <- W at changed positions
             }
         }
         __syncthreads();
