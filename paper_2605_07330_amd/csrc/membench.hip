@@ -6,7 +6,9 @@
 //   3. the cost of writing a sparse subset of 64-byte blocks, as 2-byte stores or as full 64-byte
 //      stores, alone and mixed with a streaming read (what the snapshot refresh and the scatter
 //      apply cost, and why they cost the same whatever the store width: the memory side pays per
-//      128-byte line touched).
+//      128-byte line touched);
+//   4. the same sparse blocks updated by an explicit read-modify-write of the whole 64-byte block or 128-byte
+//      line in the kernel (no cheaper than the masked 2-byte store, so the scatter keeps its 2-byte stores).
 // Everything is in bounds by construction; no input, no arguments.
 #include <hip/hip_runtime.h>
 
@@ -66,6 +68,30 @@ __global__ __launch_bounds__(256) void k_mix(uint16_t *dst, const uint16_t *src,
     if (READ && (acc.x ^ acc.y ^ acc.z ^ acc.w) == 0x12345u) sink[0] = 1;
 }
 
+// UNIT = 4: read, change and rewrite each chosen 64-byte block (4 lanes x 16 bytes); UNIT = 8: each 128-byte
+// line that holds a chosen block; UNIT = 0: only read the chosen blocks.
+template <int UNIT>
+__global__ __launch_bounds__(256) void k_rmw(uint16_t *dst, uint32_t keep, uint32_t *sink) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const uint64_t tile = (uint64_t)blockIdx.x * 16384;
+    const uint32_t e0 = wave * 4096 + lane * 8;
+    uint32_t acc = 0;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+        const uint32_t e = e0 + j * 512;
+        const uint32_t blk = (uint32_t)((tile + e) >> 5);
+        bool hit = ((blk * 2654435761u) >> 8) % keep == 0;
+        if (UNIT == 8) hit = hit || ((((blk ^ 1u) * 2654435761u) >> 8) % keep == 0);
+        if (hit) {
+            u32x4 *p = reinterpret_cast<u32x4 *>(dst + tile + e);
+            u32x4 v = *p;
+            if (UNIT == 0) acc ^= v.x ^ v.w;
+            else { v.x ^= blk; *p = v; }
+        }
+    }
+    if (UNIT == 0 && acc == 0x12345u) sink[0] = 1;
+}
+
 int main() {
     const uint64_t N = 8ull << 30;   // elements per buffer (16 GB)
     const uint32_t nwg = (uint32_t)(N / 16384);
@@ -115,6 +141,20 @@ int main() {
         std::printf("1/%-3u %6.1f M  %6.1f M   | %6.3f ms %5.1f ps/line | %6.3f ms %5.1f ps/line | +%6.3f ms %5.1f ps/line    | +%6.3f ms %5.1f ps/line\n",
                     keep, blocks / 1e6, lines / 1e6, t1, t1 * 1e9 / lines, t2, t2 * 1e9 / lines, t3 - t_read,
                     (t3 - t_read) * 1e9 / lines, t4 - t_read, (t4 - t_read) * 1e9 / lines);
+    }
+    std::printf("## the same sparse blocks by explicit read-modify-write in the kernel (no other traffic)\n");
+    std::printf("%-5s %-10s | %-22s | %-22s | %-22s | %-22s\n", "keep", "128B lines", "2B stores", "RMW of 64B blocks",
+                "RMW of 128B lines", "reads of 64B blocks only");
+    for (uint32_t keep : {2u, 4u, 8u, 16u}) {
+        const double lines = (double)N / 64 * (1.0 - (1.0 - 1.0 / keep) * (1.0 - 1.0 / keep));
+        float t1, t2, t3, t4;
+        TIME(hipLaunchKernelGGL((k_mix<1, false>), dim3(nwg), dim3(256), 0, 0, dst, src, keep, sink)); t1 = ms;
+        TIME(hipLaunchKernelGGL((k_rmw<4>), dim3(nwg), dim3(256), 0, 0, dst, keep, sink)); t2 = ms;
+        TIME(hipLaunchKernelGGL((k_rmw<8>), dim3(nwg), dim3(256), 0, 0, dst, keep, sink)); t3 = ms;
+        TIME(hipLaunchKernelGGL((k_rmw<0>), dim3(nwg), dim3(256), 0, 0, dst, keep, sink)); t4 = ms;
+        std::printf("1/%-3u %6.1f M   | %6.3f ms %5.1f ps/line | %6.3f ms %5.1f ps/line | %6.3f ms %5.1f ps/line | %6.3f ms %5.1f ps/line\n",
+                    keep, lines / 1e6, t1, t1 * 1e9 / lines, t2, t2 * 1e9 / lines, t3, t3 * 1e9 / lines, t4,
+                    t4 * 1e9 / lines);
     }
     CK(hipDeviceSynchronize());
     std::printf("done\n");
