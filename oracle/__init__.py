@@ -87,6 +87,16 @@ def _load():
         lib.srs_oracle_encode_values.argtypes = [u16p_, u32p, C.c_uint64, C.c_uint64, u8p, u8p, u32p, u32p, u16p_]
         lib.srs_oracle_decode_values.restype = C.c_int
         lib.srs_oracle_decode_values.argtypes = [u8p, u8p, u32p, u32p, C.c_uint64, C.c_uint64, u16p_]
+        pp8 = C.POINTER(u8p)
+        lib.srs_oracle_extract_u8.restype = C.c_int
+        lib.srs_oracle_extract_u8.argtypes = [u8p, u8p, C.c_uint64, C.c_uint64, i32p, u8p, u32p, C.c_uint64, C.c_int]
+        lib.srs_oracle_apply_u8.restype = C.c_int
+        lib.srs_oracle_apply_u8.argtypes = [u8p, C.c_uint64, C.c_uint64, i32p, u8p, u32p, C.c_uint64]
+        lib.srs_oracle_extract_multi_u8.restype = C.c_int
+        lib.srs_oracle_extract_multi_u8.argtypes = [pp8, pp8, u64p, C.c_uint32, C.c_uint64, i32p, u8p, u32p, C.c_uint64,
+                                                    C.c_int]
+        lib.srs_oracle_apply_multi_u8.restype = C.c_int
+        lib.srs_oracle_apply_multi_u8.argtypes = [pp8, u64p, C.c_uint32, C.c_uint64, i32p, u8p, u32p, C.c_uint64]
         lib.srs_oracle_num_buckets.restype = C.c_uint64
         lib.srs_oracle_num_buckets.argtypes = [u64p, C.c_uint32, C.c_uint64]
         _lib = lib
@@ -425,3 +435,98 @@ def decode_values(enc: dict, counts: np.ndarray) -> np.ndarray:
     if rc != OK:
         raise ValueError(f"srs_oracle_decode_values: {rc}")
     return V
+
+
+# ---------------------------------------------------------------------------------------------
+# one-byte elements (FP8 synchronisation precision, Sec. 2.1): uint8 patterns, V is uint8
+# ---------------------------------------------------------------------------------------------
+def _u8(a: np.ndarray, writable: bool = False) -> np.ndarray:
+    if not isinstance(a, np.ndarray) or a.dtype != np.uint8 or a.ndim != 1 or not a.flags.c_contiguous:
+        raise TypeError("oracle expects 1-D contiguous numpy uint8 arrays")
+    if writable and not a.flags.writeable:
+        raise TypeError("array must be writable")
+    return a
+
+
+def _ptr_array_u8(arrs: Sequence[np.ndarray]):
+    T = C.POINTER(C.c_uint8)
+    out = (T * max(len(arrs), 1))()
+    for k, a in enumerate(arrs):
+        out[k] = _p(a, C.c_uint8)
+    return out
+
+
+def extract_u8(old: np.ndarray, new: np.ndarray, be: int, cap: int | None = None, refresh: bool = True
+               ) -> Tuple[np.ndarray, np.ndarray, np.ndarray, int]:
+    """Single tensor of one-byte elements.  Returns (I[nb, cap] int32, V[nb, cap] uint8, counts[nb] uint32,
+    n_overflowed); unused slots hold I = -1, V = 0xFF (this wrapper's fill values)."""
+    lib = _load()
+    _u8(old, True), _u8(new)
+    n = old.size
+    if new.size != n:
+        raise ValueError("size mismatch")
+    cap = be if cap is None else cap
+    nb = num_buckets(n, be) if be else 0
+    I = np.full((nb, max(cap, 0)), -1, np.int32)
+    V = np.full((nb, max(cap, 0)), 0xFF, np.uint8)
+    counts = np.zeros(nb, np.uint32)
+    rc = lib.srs_oracle_extract_u8(_p(old, C.c_uint8), _p(new, C.c_uint8), n, be,
+                                   _p(I, C.c_int32), _p(V, C.c_uint8), _p(counts, C.c_uint32), cap, int(refresh))
+    if rc < 0:
+        raise ValueError(f"srs_oracle_extract_u8: bad argument ({rc})")
+    return I, V, counts, rc
+
+
+def apply_u8(w: np.ndarray, be: int, I: np.ndarray, V: np.ndarray, counts: np.ndarray) -> int:
+    lib = _load()
+    _u8(w, True)
+    I = np.ascontiguousarray(I, np.int32)
+    V = np.ascontiguousarray(V, np.uint8)
+    counts = np.ascontiguousarray(counts, np.uint32)
+    cap = I.shape[1] if I.ndim == 2 else (I.size // max(counts.size, 1))
+    rc = lib.srs_oracle_apply_u8(_p(w, C.c_uint8), w.size, be, _p(I, C.c_int32), _p(V, C.c_uint8),
+                                 _p(counts, C.c_uint32), cap)
+    if rc == BAD_ARG:
+        raise ValueError("srs_oracle_apply_u8: bad argument")
+    return rc
+
+
+def extract_multi_u8(old: Sequence[np.ndarray], new: Sequence[np.ndarray], numel: Sequence[int], be: int,
+                     cap: int | None = None, refresh: bool = True) -> Tuple[np.ndarray, np.ndarray, np.ndarray, int]:
+    """Tensor list of one-byte elements laid end to end, all buckets; index = position inside the bucket."""
+    lib = _load()
+    for a in old:
+        _u8(a, True)
+    for a in new:
+        _u8(a)
+    ne = np.asarray(list(numel), np.uint64)
+    for k in range(len(numel)):
+        if old[k].size != ne[k] or new[k].size != ne[k]:
+            raise ValueError("numel mismatch")
+    nb = num_buckets(int(ne.sum()), be) if be else 0
+    cap = be if cap is None else cap
+    I = np.full((nb, max(cap, 0)), -1, np.int32)
+    V = np.full((nb, max(cap, 0)), 0xFF, np.uint8)
+    counts = np.zeros(nb, np.uint32)
+    rc = lib.srs_oracle_extract_multi_u8(_ptr_array_u8(old), _ptr_array_u8(new), _p(ne, C.c_uint64), len(numel), be,
+                                         _p(I, C.c_int32), _p(V, C.c_uint8), _p(counts, C.c_uint32), cap, int(refresh))
+    if rc < 0:
+        raise ValueError(f"srs_oracle_extract_multi_u8: bad argument ({rc})")
+    return I, V, counts, rc
+
+
+def apply_multi_u8(w: Sequence[np.ndarray], numel: Sequence[int], be: int, I: np.ndarray, V: np.ndarray,
+                   counts: np.ndarray) -> int:
+    lib = _load()
+    for a in w:
+        _u8(a, True)
+    ne = np.asarray(list(numel), np.uint64)
+    I = np.ascontiguousarray(I, np.int32)
+    V = np.ascontiguousarray(V, np.uint8)
+    counts = np.ascontiguousarray(counts, np.uint32)
+    cap = I.shape[1] if I.ndim == 2 else (I.size // max(counts.size, 1))
+    rc = lib.srs_oracle_apply_multi_u8(_ptr_array_u8(w), _p(ne, C.c_uint64), len(numel), be,
+                                       _p(I, C.c_int32), _p(V, C.c_uint8), _p(counts, C.c_uint32), cap)
+    if rc == BAD_ARG:
+        raise ValueError("srs_oracle_apply_multi_u8: bad argument")
+    return rc

@@ -48,6 +48,9 @@
  * the cumulative index set of Alg. 1 (brute-force unions), value entropy coding
  * (prefix-free, optimal cost, entropy bound, the construction rule restated
  * independently, alpha against the paper's printed range).
+ * One-byte elements (FP8 synchronisation): the same pins as the 16-bit
+ * functions (tests/test_oracle_u8.py), plus agreement with the 16-bit functions
+ * on byte patterns widened to 16 bits.
  * parity unpinned: only the BF16 pattern a NaN master weight rounds to (0x7FC0
  * here) -- the paper is silent and library casts disagree on it.
  */
@@ -185,6 +188,120 @@ int srs_oracle_apply_multi(uint16_t *const *w, const uint64_t *numel, uint32_t n
             uint64_t start = start0;
             while (p >= start + numel[k]) { start += numel[k]; k += 1; }
             w[k][p - start] = V[(b - b_lo) * cap + r];
+        }
+    }
+    return rc;
+}
+
+/* ------------------------------------------------------------------------------------------------
+ * One-byte elements.  Sec. 2.1 measures the changed-element density at BF16, FP16 and FP8 synchronisation
+ * precision; the definitions of Alg. 1-3 do not depend on the width of an element, only "W[i] != W_prev[i]"
+ * and "V = W[I]" over opaque patterns.  FP16 is the 16-bit functions above unchanged; FP8 (or any other
+ * one-byte format) is the same four functions over 8-bit patterns, written out again here rather than
+ * shared through a macro so that each can be read on its own.  V is u8[nb*cap].
+ * ------------------------------------------------------------------------------------------------ */
+int srs_oracle_extract_u8(uint8_t *old_w, const uint8_t *new_w, uint64_t n, uint64_t be,
+                          int32_t *I, uint8_t *V, uint32_t *counts, uint64_t cap, int refresh)
+{
+    if (be == 0 || cap == 0 || n > 0x7fffffffULL || be > 0x7fffffffULL) return SRS_ORACLE_BAD_ARG;
+    uint64_t nb = (n + be - 1) / be;
+    int overflowed = 0;
+    for (uint64_t b = 0; b < nb; ++b) {
+        uint64_t lo = b * be;
+        uint64_t hi = lo + be < n ? lo + be : n;
+        uint64_t c = 0;
+        for (uint64_t i = lo; i < hi; ++i) {
+            if (old_w[i] != new_w[i]) {
+                if (c < cap) {
+                    I[b * cap + c] = (int32_t)i;
+                    V[b * cap + c] = new_w[i];
+                }
+                c += 1;
+            }
+        }
+        counts[b] = (uint32_t)c;
+        if (c > cap) overflowed += 1;
+    }
+    if (refresh)
+        for (uint64_t i = 0; i < n; ++i) old_w[i] = new_w[i];
+    return overflowed;
+}
+
+int srs_oracle_apply_u8(uint8_t *w, uint64_t n, uint64_t be,
+                        const int32_t *I, const uint8_t *V, const uint32_t *counts, uint64_t cap)
+{
+    if (be == 0 || cap == 0 || n > 0x7fffffffULL || be > 0x7fffffffULL) return SRS_ORACLE_BAD_ARG;
+    uint64_t nb = (n + be - 1) / be;
+    int rc = SRS_ORACLE_OK;
+    for (uint64_t b = 0; b < nb; ++b) {
+        uint64_t lo = b * be;
+        uint64_t hi = lo + be < n ? lo + be : n;
+        uint64_t c = counts[b] < cap ? counts[b] : cap;
+        for (uint64_t r = 0; r < c; ++r) {
+            int64_t i = I[b * cap + r];
+            if (i < (int64_t)lo || i >= (int64_t)hi) { rc = SRS_ORACLE_BAD_INDEX; continue; }
+            w[i] = V[b * cap + r];
+        }
+    }
+    return rc;
+}
+
+/* Tensor list of one-byte elements, all buckets.  The packed position g of element j of tensor k is
+ * (numel[0] + ... + numel[k-1]) + j; its bucket is g / be and the stored index g mod be. */
+int srs_oracle_extract_multi_u8(uint8_t *const *old_w, const uint8_t *const *new_w,
+                                const uint64_t *numel, uint32_t ntensors, uint64_t be,
+                                int32_t *I, uint8_t *V, uint32_t *counts, uint64_t cap, int refresh)
+{
+    if (be == 0 || cap == 0 || be > 0x7fffffffULL) return SRS_ORACLE_BAD_ARG;
+    uint64_t total = 0;
+    for (uint32_t k = 0; k < ntensors; ++k) {
+        if (numel[k] > 0x7fffffffULL) return SRS_ORACLE_BAD_ARG;
+        total += numel[k];
+    }
+    uint64_t nb = (total + be - 1) / be;
+    for (uint64_t b = 0; b < nb; ++b) counts[b] = 0;
+    uint64_t g = 0;
+    for (uint32_t k = 0; k < ntensors; ++k) {
+        for (uint64_t j = 0; j < numel[k]; ++j, ++g) {
+            if (old_w[k][j] == new_w[k][j]) continue;
+            uint64_t b = g / be;
+            uint64_t c = counts[b];
+            if (c < cap) {
+                I[b * cap + c] = (int32_t)(g % be);
+                V[b * cap + c] = new_w[k][j];
+            }
+            counts[b] = (uint32_t)(c + 1);
+            if (refresh) old_w[k][j] = new_w[k][j];
+        }
+    }
+    int overflowed = 0;
+    for (uint64_t b = 0; b < nb; ++b)
+        if (counts[b] > cap) overflowed += 1;
+    return overflowed;
+}
+
+int srs_oracle_apply_multi_u8(uint8_t *const *w, const uint64_t *numel, uint32_t ntensors, uint64_t be,
+                              const int32_t *I, const uint8_t *V, const uint32_t *counts, uint64_t cap)
+{
+    if (be == 0 || cap == 0 || be > 0x7fffffffULL) return SRS_ORACLE_BAD_ARG;
+    uint64_t total = 0;
+    for (uint32_t k = 0; k < ntensors; ++k) {
+        if (numel[k] > 0x7fffffffULL) return SRS_ORACLE_BAD_ARG;
+        total += numel[k];
+    }
+    uint64_t nb = (total + be - 1) / be;
+    int rc = SRS_ORACLE_OK;
+    for (uint64_t b = 0; b < nb; ++b) {
+        uint64_t lo = b * be;
+        uint64_t span = lo + be < total ? be : total - lo;
+        uint64_t c = counts[b] < cap ? counts[b] : cap;
+        for (uint64_t r = 0; r < c; ++r) {
+            int64_t local = I[b * cap + r];
+            if (local < 0 || (uint64_t)local >= span) { rc = SRS_ORACLE_BAD_INDEX; continue; }
+            uint64_t g = lo + (uint64_t)local;      /* packed position -> (tensor, offset) by walking the list */
+            uint32_t k = 0;
+            while (g >= numel[k]) { g -= numel[k]; k += 1; }
+            w[k][g] = V[b * cap + r];
         }
     }
     return rc;
