@@ -141,6 +141,28 @@ int srs_apply_multi(srs_ctx *ctx, srs_plan *plan, const srs_tensor *t,
                     const int32_t *I, const uint16_t *V, const uint32_t *counts, uint64_t cap, void *stream);
 
 /*
+ * One-byte elements.  The changed-element density is measured at BF16, FP16 and FP8 synchronisation precision
+ * (Sec. 2.1); Alg. 1-3 compare and move opaque patterns and do not depend on their width.  FP16 weights go
+ * through the 16-bit calls above unchanged.  These four calls are the same operations on 8-bit patterns (FP8 in
+ * either of its formats, or any other one-byte type): old_snapshot / new_w / weights hold n (or numel[k]) bytes,
+ * V is uint8_t[nb*cap]; indices, counts, capacity rule, flags, snapshot semantics (SRS_OPT_SNAPSHOT included) and
+ * error behaviour are those of the 16-bit calls.  No alignment is required (16-byte aligned tensors take the
+ * vector path).  A plan serves both widths.  Restrictions: SRS_OPT_TILE_ELEMS 4096 is rejected with
+ * SRS_ERR_INVALID (a one-byte tile is at least 8192 elements), and SRS_OPT_REFRESH_GROUP is ignored (the
+ * snapshot is refreshed element by element).  The fused cast, the cumulative set, the index coding of an
+ * existing payload (srs_encode_indices reads I only) and the routing work as they stand or do not apply; an
+ * encoded apply and a value coder for one-byte values are not provided.
+ */
+int srs_extract_u8(srs_ctx *ctx, void *old_snapshot, const void *new_w, uint64_t n, uint64_t bucket_elems,
+                   int32_t *I, uint8_t *V, uint32_t *counts, uint64_t cap, void *stream);
+int srs_apply_u8(srs_ctx *ctx, void *weights, uint64_t n, uint64_t bucket_elems,
+                 const int32_t *I, const uint8_t *V, const uint32_t *counts, uint64_t cap, void *stream);
+int srs_extract_multi_u8(srs_ctx *ctx, srs_plan *plan, const srs_tensor_pair *t,
+                         int32_t *I, uint8_t *V, uint32_t *counts, uint64_t cap, void *stream);
+int srs_apply_multi_u8(srs_ctx *ctx, srs_plan *plan, const srs_tensor *t,
+                       const int32_t *I, const uint8_t *V, const uint32_t *counts, uint64_t cap, void *stream);
+
+/*
  * Fused cast + diff.  The Trainer's hook sits where the FP32 master weights are cast and copied into the BF16
  * model parameters (Alg. 1: CastAndCopy, then I_t = { i : W[i] != W_prev[i] }; Sec. 3.4 "Trainer").  These
  * calls do both at once, so that no snapshot W_prev exists: for every element r = round_BF16(master[i]);

@@ -92,8 +92,31 @@ int prepare_extract(srs_ctx *ctx, uint64_t ntiles, uint64_t nb, hipStream_t st, 
     return SRS_OK;
 }
 
+// One-byte elements: a tile of tile_elems elements is V = tile_elems / 4096 vectors per lane (16 elements each), so
+// the smallest tile (4096) has no kernel (V is even by construction of the packed scan).  The snapshot is refreshed
+// element by element, or not at all under the rotating-snapshot option.
 template <bool MULTI>
-int launch_extract(const srs_ctx *ctx, uint32_t tile_elems, const ExtractArgs &a, hipStream_t st, int src) {
+int launch_extract_u8(const srs_ctx *ctx, uint32_t tile_elems, const ExtractArgs &a, hipStream_t st) {
+    const dim3 grid(a.ntiles), block(kThreads);
+#define SRS_LAUNCH8(VV)                                                                                               \
+    do {                                                                                                              \
+        if (ctx->rotate_snapshot) hipLaunchKernelGGL((extract_kernel<VV, MULTI, -1, kSrcBf16, 1>), grid, block, 0, st, a); \
+        else hipLaunchKernelGGL((extract_kernel<VV, MULTI, 0, kSrcBf16, 1>), grid, block, 0, st, a);                   \
+    } while (0)
+    switch (tile_elems) {
+        case 8192: SRS_LAUNCH8(2); break;
+        case 16384: SRS_LAUNCH8(4); break;
+        case 32768: SRS_LAUNCH8(8); break;
+        default: return SRS_ERR_INVALID;
+    }
+#undef SRS_LAUNCH8
+    SRS_HIP(hipGetLastError());
+    return SRS_OK;
+}
+
+template <bool MULTI>
+int launch_extract(const srs_ctx *ctx, uint32_t tile_elems, const ExtractArgs &a, hipStream_t st, int src, int eb = 2) {
+    if (eb == 1) return launch_extract_u8<MULTI>(ctx, tile_elems, a, st);
     const dim3 grid(a.ntiles), block(kThreads);
 #define SRS_LAUNCH(VV)                                                                                                \
     do {                                                                                                              \
@@ -257,13 +280,15 @@ bool encoded_args_ok(const uint16_t *D, const int32_t *I_wide, const uint16_t *V
 
 namespace {
 int extract_single(srs_ctx *ctx, void *old_snapshot, const void *new_w, uint64_t n, uint64_t bucket_elems,
-                   int32_t *I, uint16_t *V, uint32_t *counts, uint64_t cap, void *stream, bool cast) {
+                   int32_t *I, void *V, uint32_t *counts, uint64_t cap, void *stream, bool cast, int eb = 2) {
     if (!ctx || bucket_elems == 0 || cap == 0 || n > kMaxIndexable || bucket_elems > kMaxIndexable) return SRS_ERR_INVALID;
     if (n == 0) return SRS_OK;
     if (!old_snapshot || !new_w || !I || !V || !counts) return SRS_ERR_INVALID;
-    if (((uintptr_t)old_snapshot | (uintptr_t)V) & 1u) return SRS_ERR_INVALID;
-    if ((uintptr_t)new_w & (cast ? 3u : 1u)) return SRS_ERR_INVALID;
+    const uintptr_t amask = (uintptr_t)eb - 1u;                     // elements are naturally aligned
+    if (((uintptr_t)old_snapshot | (uintptr_t)V) & amask) return SRS_ERR_INVALID;
+    if ((uintptr_t)new_w & (cast ? 3u : amask)) return SRS_ERR_INVALID;
     if (((uintptr_t)I | (uintptr_t)counts) & 3u) return SRS_ERR_INVALID;
+    if (eb == 1 && ctx->tile_elems < 8192) return SRS_ERR_INVALID;
     hipStream_t st = (hipStream_t)stream;
     SRS_HIP(hipSetDevice(ctx->device));
 
@@ -285,26 +310,28 @@ int extract_single(srs_ctx *ctx, void *old_snapshot, const void *new_w, uint64_t
     a.be = (uint32_t)bucket_elems; a.tiles_per_bucket = (uint32_t)tpb;
     a.nb = (uint32_t)nb; a.last_tiles = (uint32_t)((last_len + T - 1) / T); a.group = (uint32_t)group;
     a.ntiles = (uint32_t)ntiles;
-    a.I = I; a.V = V; a.counts = counts; a.cap = cap;
+    a.I = I; a.V = (uint16_t *)V; a.counts = counts; a.cap = cap;
     a.status = ctx->status; a.tickets = ctx->tickets; a.flags = ctx->flags;
     a.spin_limit = ctx->spin_limit;
-    return launch_extract<false>(ctx, ctx->tile_elems, a, st, cast ? kSrcFp32 : kSrcBf16);
+    return launch_extract<false>(ctx, ctx->tile_elems, a, st, cast ? kSrcFp32 : kSrcBf16, eb);
 }
 }  // namespace
 
 namespace {
 int extract_multi(srs_ctx *ctx, srs_plan *plan, const srs_tensor_pair *t,
-                  int32_t *I, uint16_t *V, uint32_t *counts, uint64_t cap, void *stream, int src,
-                  const uint32_t *bitmap = nullptr) {
+                  int32_t *I, void *V, uint32_t *counts, uint64_t cap, void *stream, int src,
+                  const uint32_t *bitmap = nullptr, int eb = 2) {
     const bool cast = (src == kSrcFp32);
     if (src == kSrcBitmap && (!bitmap || ((uintptr_t)bitmap & 3u))) return SRS_ERR_INVALID;
     if (!ctx || !plan || cap == 0 || plan->device != ctx->device) return SRS_ERR_INVALID;
     if (plan->total == 0) return SRS_OK;
     if (!t || !I || !V || !counts) return SRS_ERR_INVALID;
-    if (((uintptr_t)V & 1u) || (((uintptr_t)I | (uintptr_t)counts) & 3u)) return SRS_ERR_INVALID;
+    const uintptr_t amask = (uintptr_t)eb - 1u;
+    if (((uintptr_t)V & amask) || (((uintptr_t)I | (uintptr_t)counts) & 3u)) return SRS_ERR_INVALID;
+    if (eb == 1 && plan->tile_elems < 8192) return SRS_ERR_INVALID;
     // numel is not known here any more, but a tensor with elements has at least one segment
     for (uint32_t k = 0; k < plan->ntensors; ++k)
-        if (((uintptr_t)t[k].old_snapshot & 1u) || ((uintptr_t)t[k].new_w & (cast ? 3u : 1u))) return SRS_ERR_INVALID;
+        if (((uintptr_t)t[k].old_snapshot & amask) || ((uintptr_t)t[k].new_w & (cast ? 3u : amask))) return SRS_ERR_INVALID;
     hipStream_t st = (hipStream_t)stream;
     SRS_HIP(hipSetDevice(ctx->device));
 
@@ -317,11 +344,11 @@ int extract_multi(srs_ctx *ctx, srs_plan *plan, const srs_tensor_pair *t,
     if (rc != SRS_OK) return rc;
     a.tiles = plan->d_tiles; a.ptrs = plan->d_pairs; a.ntiles = plan->ntiles;
     a.wg_bucket = plan->d_wg_bucket; a.bucket_first = plan->d_bucket_first; a.nb = plan->nbuckets;
-    a.I = I; a.V = V; a.counts = counts; a.cap = cap;
+    a.I = I; a.V = (uint16_t *)V; a.counts = counts; a.cap = cap;
     a.status = ctx->status; a.tickets = ctx->tickets; a.flags = ctx->flags;
     a.spin_limit = ctx->spin_limit;
     a.bitmap = const_cast<uint32_t *>(bitmap); a.bitmap_words = (plan->total + 31) / 32; a.tensor_base = plan->d_tensor_base;
-    return launch_extract<true>(ctx, plan->tile_elems, a, st, src);
+    return launch_extract<true>(ctx, plan->tile_elems, a, st, src, eb);
 }
 }  // namespace
 
@@ -420,12 +447,12 @@ int srs_extract_cast(srs_ctx *ctx, void *weights, const float *master, uint64_t 
     return extract_single(ctx, weights, master, n, bucket_elems, I, V, counts, cap, stream, true);
 }
 
-int srs_apply(srs_ctx *ctx, void *weights, uint64_t n, uint64_t bucket_elems,
-              const int32_t *I, const uint16_t *V, const uint32_t *counts, uint64_t cap, void *stream) {
+static int apply_single(srs_ctx *ctx, void *weights, uint64_t n, uint64_t bucket_elems,
+                        const int32_t *I, const void *V, const uint32_t *counts, uint64_t cap, void *stream, int eb) {
     if (!ctx || bucket_elems == 0 || cap == 0 || n > kMaxIndexable || bucket_elems > kMaxIndexable) return SRS_ERR_INVALID;
     if (n == 0) return SRS_OK;
     if (!weights || !I || !V || !counts) return SRS_ERR_INVALID;
-    if (((uintptr_t)weights | (uintptr_t)V) & 1u) return SRS_ERR_INVALID;
+    if (((uintptr_t)weights | (uintptr_t)V) & ((uintptr_t)eb - 1u)) return SRS_ERR_INVALID;
     if (((uintptr_t)I | (uintptr_t)counts) & 3u) return SRS_ERR_INVALID;
     hipStream_t st = (hipStream_t)stream;
     SRS_HIP(hipSetDevice(ctx->device));
@@ -438,10 +465,27 @@ int srs_apply(srs_ctx *ctx, void *weights, uint64_t n, uint64_t bucket_elems,
     std::memset(&a, 0, sizeof(a));
     a.w = (uint16_t *)weights; a.n = n; a.be = (uint32_t)bucket_elems; a.nb = (uint32_t)nb;
     a.chunks_per_bucket = (uint32_t)cpb;
-    a.I = I; a.V = V; a.counts = counts; a.cap = cap; a.flags = ctx->flags;
-    hipLaunchKernelGGL((apply_kernel<false>), dim3((uint32_t)(nb * cpb)), dim3(kThreads), 0, st, a);
+    a.I = I; a.V = (const uint16_t *)V; a.counts = counts; a.cap = cap; a.flags = ctx->flags;
+    if (eb == 1) hipLaunchKernelGGL((apply_kernel<false, 1>), dim3((uint32_t)(nb * cpb)), dim3(kThreads), 0, st, a);
+    else hipLaunchKernelGGL((apply_kernel<false>), dim3((uint32_t)(nb * cpb)), dim3(kThreads), 0, st, a);
     SRS_HIP(hipGetLastError());
     return SRS_OK;
+}
+
+int srs_apply(srs_ctx *ctx, void *weights, uint64_t n, uint64_t bucket_elems,
+              const int32_t *I, const uint16_t *V, const uint32_t *counts, uint64_t cap, void *stream) {
+    return apply_single(ctx, weights, n, bucket_elems, I, V, counts, cap, stream, 2);
+}
+
+// one-byte elements (FP8 synchronisation precision)
+int srs_extract_u8(srs_ctx *ctx, void *old_snapshot, const void *new_w, uint64_t n, uint64_t bucket_elems,
+                   int32_t *I, uint8_t *V, uint32_t *counts, uint64_t cap, void *stream) {
+    return extract_single(ctx, old_snapshot, new_w, n, bucket_elems, I, V, counts, cap, stream, false, 1);
+}
+
+int srs_apply_u8(srs_ctx *ctx, void *weights, uint64_t n, uint64_t bucket_elems,
+                 const int32_t *I, const uint8_t *V, const uint32_t *counts, uint64_t cap, void *stream) {
+    return apply_single(ctx, weights, n, bucket_elems, I, V, counts, cap, stream, 1);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -563,14 +607,15 @@ int srs_extract_cast_multi(srs_ctx *ctx, srs_plan *plan, const srs_tensor_pair *
     return extract_multi(ctx, plan, t, I, V, counts, cap, stream, kSrcFp32);
 }
 
-int srs_apply_multi(srs_ctx *ctx, srs_plan *plan, const srs_tensor *t,
-                    const int32_t *I, const uint16_t *V, const uint32_t *counts, uint64_t cap, void *stream) {
+static int apply_multi(srs_ctx *ctx, srs_plan *plan, const srs_tensor *t,
+                       const int32_t *I, const void *V, const uint32_t *counts, uint64_t cap, void *stream, int eb) {
     if (!ctx || !plan || cap == 0 || plan->device != ctx->device) return SRS_ERR_INVALID;
     if (plan->total == 0) return SRS_OK;
     if (!t || !I || !V || !counts) return SRS_ERR_INVALID;
-    if (((uintptr_t)V & 1u) || (((uintptr_t)I | (uintptr_t)counts) & 3u)) return SRS_ERR_INVALID;
+    const uintptr_t amask = (uintptr_t)eb - 1u;
+    if (((uintptr_t)V & amask) || (((uintptr_t)I | (uintptr_t)counts) & 3u)) return SRS_ERR_INVALID;
     for (uint32_t k = 0; k < plan->ntensors; ++k)
-        if ((uintptr_t)t[k].weights & 1u) return SRS_ERR_INVALID;
+        if ((uintptr_t)t[k].weights & amask) return SRS_ERR_INVALID;
     hipStream_t st = (hipStream_t)stream;
     SRS_HIP(hipSetDevice(ctx->device));
 
@@ -584,10 +629,27 @@ int srs_apply_multi(srs_ctx *ctx, srs_plan *plan, const srs_tensor *t,
     std::memset(&a, 0, sizeof(a));
     a.segs = plan->d_segs; a.seg_begin = plan->d_seg_begin; a.wptrs = plan->d_wptrs; a.total = plan->total;
     a.be = (uint32_t)plan->be; a.nb = plan->nbuckets; a.chunks_per_bucket = (uint32_t)cpb;
-    a.I = I; a.V = V; a.counts = counts; a.cap = cap; a.flags = ctx->flags;
-    hipLaunchKernelGGL((apply_kernel<true>), dim3((uint32_t)((uint64_t)plan->nbuckets * cpb)), dim3(kThreads), 0, st, a);
+    a.I = I; a.V = (const uint16_t *)V; a.counts = counts; a.cap = cap; a.flags = ctx->flags;
+    const dim3 grid((uint32_t)((uint64_t)plan->nbuckets * cpb));
+    if (eb == 1) hipLaunchKernelGGL((apply_kernel<true, 1>), grid, dim3(kThreads), 0, st, a);
+    else hipLaunchKernelGGL((apply_kernel<true>), grid, dim3(kThreads), 0, st, a);
     SRS_HIP(hipGetLastError());
     return SRS_OK;
+}
+
+int srs_apply_multi(srs_ctx *ctx, srs_plan *plan, const srs_tensor *t,
+                    const int32_t *I, const uint16_t *V, const uint32_t *counts, uint64_t cap, void *stream) {
+    return apply_multi(ctx, plan, t, I, V, counts, cap, stream, 2);
+}
+
+int srs_extract_multi_u8(srs_ctx *ctx, srs_plan *plan, const srs_tensor_pair *t,
+                         int32_t *I, uint8_t *V, uint32_t *counts, uint64_t cap, void *stream) {
+    return extract_multi(ctx, plan, t, I, V, counts, cap, stream, kSrcBf16, nullptr, 1);
+}
+
+int srs_apply_multi_u8(srs_ctx *ctx, srs_plan *plan, const srs_tensor *t,
+                       const int32_t *I, const uint8_t *V, const uint32_t *counts, uint64_t cap, void *stream) {
+    return apply_multi(ctx, plan, t, I, V, counts, cap, stream, 1);
 }
 
 // ---------------------------------------------------------------------------------------------

@@ -118,7 +118,7 @@ __device__ __forceinline__ uint32_t uniform(uint32_t x) {
 }
 
 template <bool NT>
-__device__ __forceinline__ u32x4 load16(const uint16_t *p) {
+__device__ __forceinline__ u32x4 load16(const void *p) {
     const u32x4 *q = reinterpret_cast<const u32x4 *>(p);
     if (NT) return __builtin_nontemporal_load(q);
     return *q;
@@ -180,6 +180,56 @@ __device__ __forceinline__ uint32_t pattern_at(u32x4 v, uint32_t e) {
     const uint32_t w = (e & 4u) ? hi : lo;
     return (e & 1u) ? (w >> 16) : (w & 0xFFFFu);
 }
+
+// 16 one-byte patterns starting at element e of a run of len elements; elements at or beyond len read as 0
+__device__ __forceinline__ u32x4 load16_guarded_u8(const uint8_t *p, uint32_t e, uint32_t len) {
+    uint32_t d[4];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        uint32_t w = 0;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) w |= ((e + 4 * q + k < len) ? (uint32_t)p[e + 4 * q + k] : 0u) << (8 * k);
+        d[q] = w;
+    }
+    u32x4 r;
+    r.x = d[0]; r.y = d[1]; r.z = d[2]; r.w = d[3];
+    return r;
+}
+
+// bit k of the result is set iff byte k of d is non-zero (k = 0..3)
+__device__ __forceinline__ uint32_t nonzero_bytes4(uint32_t d) {
+    const uint32_t t = ((d | ((d & 0x7F7F7F7Fu) + 0x7F7F7F7Fu)) & 0x80808080u) >> 7;   // bits 0, 8, 16, 24
+    return (t * 0x10204080u) >> 28;                                                       // gathered into bits 0..3
+}
+
+// Element width.  EB = 2: BF16 / FP16 patterns, 8 per 16-byte vector; EB = 1: FP8 patterns, 16 per vector
+// (Sec. 2.1 measures the changed-element density at all three synchronisation precisions; nothing in
+// Alg. 1-3 depends on the width).  diff_mask has one bit per element of the vector, in memory order.
+template <int EB> struct Elem;
+template <> struct Elem<2> {
+    typedef uint16_t type;
+    static __device__ __forceinline__ uint32_t diff_mask(u32x4 a, u32x4 b) { return diff_mask8(a, b); }
+    static __device__ __forceinline__ uint32_t pattern(u32x4 v, uint32_t e) { return pattern_at(v, e); }
+    static __device__ __forceinline__ u32x4 load_guarded(const uint16_t *p, uint32_t e, uint32_t len) {
+        return load8_guarded(p, e, len);
+    }
+};
+template <> struct Elem<1> {
+    typedef uint8_t type;
+    static __device__ __forceinline__ uint32_t diff_mask(u32x4 a, u32x4 b) {
+        return nonzero_bytes4(a.x ^ b.x) | (nonzero_bytes4(a.y ^ b.y) << 4) | (nonzero_bytes4(a.z ^ b.z) << 8) |
+               (nonzero_bytes4(a.w ^ b.w) << 12);
+    }
+    static __device__ __forceinline__ uint32_t pattern(u32x4 v, uint32_t e) {
+        const uint32_t lo = (e & 4u) ? v.y : v.x;
+        const uint32_t hi = (e & 4u) ? v.w : v.z;
+        const uint32_t w = (e & 8u) ? hi : lo;
+        return (w >> ((e & 3u) * 8u)) & 0xFFu;
+    }
+    static __device__ __forceinline__ u32x4 load_guarded(const uint8_t *p, uint32_t e, uint32_t len) {
+        return load16_guarded_u8(p, e, len);
+    }
+};
 
 __device__ __forceinline__ unsigned long long status_load(const unsigned long long *p) {
     return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -267,13 +317,19 @@ __device__ __forceinline__ uint32_t bitmap_bits8(const uint32_t *bitmap, uint64_
     return nbits >= 8u ? bits : (bits & ((1u << nbits) - 1u));
 }
 
-template <int V, bool MULTI, int RG, int SRC = kSrcBf16>
+template <int V, bool MULTI, int RG, int SRC = kSrcBf16, int EB = 2>
 __global__ __launch_bounds__(kThreads) void extract_kernel(const ExtractArgs a) {
     constexpr bool NT = false;
     constexpr bool CAST = (SRC == kSrcFp32);
     constexpr bool MARKED = (SRC == kSrcBitmap);
     static_assert(V % 2 == 0, "counts are scanned in packed pairs");
-    constexpr uint32_t TILE = (uint32_t)V * kUnit;
+    static_assert(EB == 2 || SRC == kSrcBf16, "the cast and bitmap flavours exist for 16-bit elements only");
+    typedef Elem<EB> EL;
+    typedef typename EL::type T;
+    constexpr uint32_t VE = 16u / EB;                    // elements per 16-byte vector
+    constexpr uint32_t ROW = 64u * VE;                   // elements covered by one load instruction of a wave
+    constexpr uint32_t TILE = (uint32_t)V * kThreads * VE;
+    static_assert(TILE <= 65536u, "tile-local positions are staged in 16 bits");
     __shared__ uint32_t s_ticket;
     __shared__ uint32_t s_wave_total[kWaves];
     __shared__ uint32_t s_excl;
@@ -316,12 +372,12 @@ __global__ __launch_bounds__(kThreads) void extract_kernel(const ExtractArgs a) 
 
     // ---- where this tile lives
     uint32_t bucket_off, len, idx_base;
-    uint16_t *po; const void *pn_raw; uint64_t pn_off;      // new weights: base pointer and element offset
+    T *po; const void *pn_raw; uint64_t pn_off;      // new weights: base pointer and element offset
     uint64_t g0 = 0;                                        // packed position of the tile's first element (MARKED)
     if (MULTI) {
         const TileDesc d = a.tiles[tile];
         const PtrPair p = a.ptrs[d.tensor];
-        po = p.old_w + d.tensor_off; pn_raw = p.new_w; pn_off = d.tensor_off;
+        po = reinterpret_cast<T *>(p.old_w) + d.tensor_off; pn_raw = p.new_w; pn_off = d.tensor_off;
         bucket_off = d.bucket_off; len = d.len;
         idx_base = bucket_off;                          // index = position inside the bucket
         if (MARKED) g0 = a.tensor_base[d.tensor] + d.tensor_off;
@@ -330,18 +386,18 @@ __global__ __launch_bounds__(kThreads) void extract_kernel(const ExtractArgs a) 
         const uint32_t blen = (uint32_t)((a.n - b0 < a.be) ? (a.n - b0) : a.be);
         bucket_off = k * TILE;
         len = (blen - bucket_off < TILE) ? (blen - bucket_off) : TILE;
-        po = a.old_w + b0 + bucket_off; pn_raw = a.new_w; pn_off = b0 + bucket_off;
+        po = reinterpret_cast<T *>(a.old_w) + b0 + bucket_off; pn_raw = a.new_w; pn_off = b0 + bucket_off;
         idx_base = (uint32_t)(b0 + bucket_off);         // index = tensor-flat position
         if (MARKED) g0 = b0 + bucket_off;
     }
 
-    // ---- stream the tile.  Layout: wave w owns elements [w*V*512, (w+1)*V*512); inside it vector j
-    // of lane l holds elements (j*64 + l)*8 .. +8, so ascending order is (wave, j, lane, element).
+    // ---- stream the tile.  Layout: wave w owns elements [w*V*ROW, (w+1)*V*ROW); inside it vector j
+    // of lane l holds elements (j*64 + l)*VE .. +VE, so ascending order is (wave, j, lane, element).
     u32x4 xo[V], xn[V];
-    const uint32_t e0 = (uint32_t)wave * (V * 512u) + (uint32_t)lane * 8u;
+    const uint32_t e0 = (uint32_t)wave * (V * ROW) + (uint32_t)lane * VE;
     // with CAST pn addresses 32-bit elements: pf is the same position in the master weights
     const uint32_t *const pf = reinterpret_cast<const uint32_t *>(pn_raw) + pn_off;
-    const uint16_t *const pn = reinterpret_cast<const uint16_t *>(pn_raw) + pn_off;
+    const T *const pn = reinterpret_cast<const T *>(pn_raw) + pn_off;
     const bool aligned = CAST ? (((((uintptr_t)po) | ((uintptr_t)pf)) & 15u) == 0)
                      : MARKED ? ((((uintptr_t)pn) & 15u) == 0)
                               : (((((uintptr_t)po) | ((uintptr_t)pn)) & 15u) == 0);
@@ -356,22 +412,22 @@ __global__ __launch_bounds__(kThreads) void extract_kernel(const ExtractArgs a) 
             // with one coalesced load per thread and are handed out through LDS, one byte (8 elements) per lane.
             for (uint32_t i = tid; i < TILE / 32; i += kThreads) s_bits[i] = a.bitmap[(g0 >> 5) + i];
 #pragma unroll
-            for (int j = 0; j < V; ++j) { xo[j] = zero; xn[j] = load16<NT>(pn + e0 + j * 512); }
+            for (int j = 0; j < V; ++j) { xo[j] = zero; xn[j] = load16<NT>(pn + e0 + j * ROW); }
             __syncthreads();
             const uint8_t *const bytes = reinterpret_cast<const uint8_t *>(s_bits);
 #pragma unroll
             for (int j = 0; j < V; ++j) m[j] = bytes[(e0 >> 3) + j * 64];
         } else if (aligned && len == TILE) {
 #pragma unroll
-            for (int j = 0; j < V; ++j) { xo[j] = zero; xn[j] = load16<NT>(pn + e0 + j * 512); }
+            for (int j = 0; j < V; ++j) { xo[j] = zero; xn[j] = load16<NT>(pn + e0 + j * ROW); }
 #pragma unroll
-            for (int j = 0; j < V; ++j) m[j] = bitmap_bits8(a.bitmap, a.bitmap_words, g0 + e0 + j * 512, 8u);
+            for (int j = 0; j < V; ++j) m[j] = bitmap_bits8(a.bitmap, a.bitmap_words, g0 + e0 + j * ROW, 8u);
         } else {
 #pragma unroll
             for (int j = 0; j < V; ++j) {
-                const uint32_t e = e0 + j * 512;
+                const uint32_t e = e0 + j * ROW;
                 xo[j] = zero;
-                xn[j] = (aligned && e + 8 <= len) ? load16<false>(pn + e) : load8_guarded(pn, e, len);
+                xn[j] = (aligned && e + VE <= len) ? load16<false>(pn + e) : EL::load_guarded(pn, e, len);
                 m[j] = (e < len) ? bitmap_bits8(a.bitmap, a.bitmap_words, g0 + e, len - e) : 0u;
             }
         }
@@ -380,30 +436,30 @@ __global__ __launch_bounds__(kThreads) void extract_kernel(const ExtractArgs a) 
             u32x4 f0[V], f1[V];
 #pragma unroll
             for (int j = 0; j < V; ++j) {
-                f0[j] = *reinterpret_cast<const u32x4 *>(pf + e0 + j * 512);
-                f1[j] = *reinterpret_cast<const u32x4 *>(pf + e0 + j * 512 + 4);
+                f0[j] = *reinterpret_cast<const u32x4 *>(pf + e0 + j * ROW);
+                f1[j] = *reinterpret_cast<const u32x4 *>(pf + e0 + j * ROW + 4);
             }
 #pragma unroll
-            for (int j = 0; j < V; ++j) xo[j] = load16<NT>(po + e0 + j * 512);
+            for (int j = 0; j < V; ++j) xo[j] = load16<NT>(po + e0 + j * ROW);
 #pragma unroll
             for (int j = 0; j < V; ++j) xn[j] = round8_bf16(f0[j], f1[j]);
         } else {
 #pragma unroll
-            for (int j = 0; j < V; ++j) xn[j] = load16<NT>(pn + e0 + j * 512);
+            for (int j = 0; j < V; ++j) xn[j] = load16<NT>(pn + e0 + j * ROW);
 #pragma unroll
-            for (int j = 0; j < V; ++j) xo[j] = load16<NT>(po + e0 + j * 512);
+            for (int j = 0; j < V; ++j) xo[j] = load16<NT>(po + e0 + j * ROW);
         }
     } else {
 #pragma unroll
         for (int j = 0; j < V; ++j) {
-            const uint32_t e = e0 + j * 512;
-            if (aligned && e + 8 <= len) {
+            const uint32_t e = e0 + j * ROW;
+            if (aligned && e + VE <= len) {
                 xo[j] = load16<false>(po + e);
                 if (CAST) xn[j] = round8_bf16(*reinterpret_cast<const u32x4 *>(pf + e), *reinterpret_cast<const u32x4 *>(pf + e + 4));
                 else xn[j] = load16<false>(pn + e);
             } else {
-                xo[j] = load8_guarded(po, e, len);
-                xn[j] = CAST ? load8_guarded_cast(pf, e, len) : load8_guarded(pn, e, len);
+                xo[j] = EL::load_guarded(po, e, len);
+                xn[j] = CAST ? load8_guarded_cast(pf, e, len) : EL::load_guarded(pn, e, len);
             }
         }
     }
@@ -412,7 +468,7 @@ __global__ __launch_bounds__(kThreads) void extract_kernel(const ExtractArgs a) 
     uint32_t pk[V / 2];
     if (!MARKED) {
 #pragma unroll
-        for (int j = 0; j < V; ++j) m[j] = diff_mask8(xo[j], xn[j]);
+        for (int j = 0; j < V; ++j) m[j] = EL::diff_mask(xo[j], xn[j]);
     }
 
     // ---- snapshot refresh of full tiles, RG lanes (RG*16 bytes) at a time
@@ -422,7 +478,7 @@ __global__ __launch_bounds__(kThreads) void extract_kernel(const ExtractArgs a) 
         for (int j = 0; j < V; ++j) {
             const unsigned long long changed = __ballot(m[j] != 0);
             const uint32_t grp = (uint32_t)(changed >> (lane & ~(RG > 0 ? RG - 1 : 0))) & ((1u << (RG > 0 ? RG : 1)) - 1u);
-            if (grp) *reinterpret_cast<u32x4 *>(po + e0 + j * 512) = xn[j];
+            if (grp) *reinterpret_cast<u32x4 *>(po + e0 + j * ROW) = xn[j];
         }
     }
 #pragma unroll
@@ -474,18 +530,18 @@ __global__ __launch_bounds__(kThreads) void extract_kernel(const ExtractArgs a) 
 
     // ---- stage (index, value) pairs in LDS in rank order, write out coalesced; kStage per round
     int32_t *const Ib = a.I + (uint64_t)bucket * a.cap;
-    uint16_t *const Vb = a.V + (uint64_t)bucket * a.cap;
+    T *const Vb = reinterpret_cast<T *>(a.V) + (uint64_t)bucket * a.cap;
     for (uint32_t r0 = 0; r0 < tile_total; r0 += kStage) {
 #pragma unroll
         for (int j = 0; j < V; ++j) {
             uint32_t mm = m[j];
             if (mm) {
                 uint32_t rank = wave_base + ex[j] - r0;
-                const uint32_t local = e0 + j * 512;
+                const uint32_t local = e0 + j * ROW;
                 while (mm) {
                     const uint32_t e = (uint32_t)__builtin_ctz(mm);
                     mm &= mm - 1u;
-                    if (rank < kStage) s_stage[rank] = ((local + e) << 16) | pattern_at(xn[j], e);
+                    if (rank < kStage) s_stage[rank] = ((local + e) << 16) | EL::pattern(xn[j], e);
                     ++rank;
                 }
             }
@@ -496,7 +552,7 @@ __global__ __launch_bounds__(kThreads) void extract_kernel(const ExtractArgs a) 
         for (uint32_t k = tid; k < nst; k += kThreads) {
             const uint32_t ent = s_stage[k];
             const uint32_t local = ent >> 16;
-            const uint16_t val = (uint16_t)(ent & 0xFFFFu);
+            const T val = (T)(ent & 0xFFFFu);
             const uint64_t r = (uint64_t)excl + r0 + k;
             if (local < len) {                      // always true for a correct scan; keeps stores in bounds
                 if (r < a.cap) { Ib[r] = (int32_t)(idx_base + local); Vb[r] = val; }
@@ -602,10 +658,11 @@ __device__ __forceinline__ uint32_t apply_chunk(const ApplyArgs &a, uint32_t &b,
 // Scatter of one thread's kApplyPer pairs of bucket b; pair j is live when bit j of `live` is set.
 // idx holds tensor-flat indices (single tensor) or positions inside the bucket (lists).  For lists the
 // bucket's segment table is cached in LDS (start inside the bucket -> byte address of that element).
-template <bool MULTI>
+template <bool MULTI, int EB = 2>
 __device__ __forceinline__ void scatter_pairs(const ApplyArgs &a, ApplyShared &sh, uint32_t b,
                                               const int32_t (&idx)[kApplyPer], const uint16_t (&val)[kApplyPer],
                                               uint32_t live) {
+    typedef typename Elem<EB>::type T;       // width of a stored value; val[] holds it zero-extended
     bool bad = false;
     if (MULTI) {
         const uint64_t b0 = (uint64_t)b * a.be;
@@ -618,7 +675,8 @@ __device__ __forceinline__ void scatter_pairs(const ApplyArgs &a, ApplyShared &s
                 const SegDesc d = a.segs[s_lo + s];
                 sh.off[s] = d.bucket_off;
                 // byte address of the element at bucket position 0 of this segment's tensor run
-                sh.base[s] = (unsigned long long)(uintptr_t)(a.wptrs[d.tensor] + d.tensor_off) - 2ull * d.bucket_off;
+                sh.base[s] = (unsigned long long)(uintptr_t)a.wptrs[d.tensor] + (unsigned long long)EB * d.tensor_off -
+                             (unsigned long long)EB * d.bucket_off;
             }
             if (threadIdx.x == 0) sh.off[nseg] = blen;
             __syncthreads();
@@ -639,7 +697,7 @@ __device__ __forceinline__ void scatter_pairs(const ApplyArgs &a, ApplyShared &s
                     }
                     hint = lo;
                 }
-                *reinterpret_cast<uint16_t *>((uintptr_t)(sh.base[lo] + 2ull * i)) = val[j];
+                *reinterpret_cast<T *>((uintptr_t)(sh.base[lo] + (unsigned long long)EB * i)) = (T)val[j];
             } else {
                 uint32_t lo = s_lo, hi = s_hi;                  // segs[lo].bucket_off <= i < segs[hi].bucket_off
                 while (hi - lo > 1) {
@@ -649,7 +707,7 @@ __device__ __forceinline__ void scatter_pairs(const ApplyArgs &a, ApplyShared &s
                 const SegDesc d = a.segs[lo];
                 const uint32_t off = i - d.bucket_off;
                 if (off >= d.len) { bad = true; continue; }     // cannot happen for a well-formed plan
-                a.wptrs[d.tensor][(uint64_t)d.tensor_off + off] = val[j];
+                reinterpret_cast<T *>(a.wptrs[d.tensor])[(uint64_t)d.tensor_off + off] = (T)val[j];
             }
         }
     } else {
@@ -660,7 +718,7 @@ __device__ __forceinline__ void scatter_pairs(const ApplyArgs &a, ApplyShared &s
             if (!((live >> j) & 1u)) continue;
             const int64_t i = idx[j];
             if (i < (int64_t)lo || i >= (int64_t)hi) { bad = true; continue; }
-            a.w[i] = val[j];
+            reinterpret_cast<T *>(a.w)[i] = (T)val[j];
         }
     }
     if (bad) atomicOr(a.flags, kFlagBadIndex);
@@ -668,15 +726,16 @@ __device__ __forceinline__ void scatter_pairs(const ApplyArgs &a, ApplyShared &s
 
 // 32-bit indices.  When a.max_gap is given, buckets whose indices travel as 16-bit differences are
 // left to apply_encoded_kernel.
-template <bool MULTI>
+template <bool MULTI, int EB = 2>
 __global__ __launch_bounds__(kThreads) void apply_kernel(const ApplyArgs a) {
+    typedef typename Elem<EB>::type T;
     __shared__ ApplyShared sh;
     uint32_t b; uint64_t start;
     const uint32_t nvalid = apply_chunk(a, b, start);
     if (nvalid == 0) return;
     if (a.max_gap && a.max_gap[b] < kWideGap) return;
     const int32_t *const Ib = a.I + (uint64_t)b * a.cap + start;
-    const uint16_t *const Vb = a.V + (uint64_t)b * a.cap + start;
+    const T *const Vb = reinterpret_cast<const T *>(a.V) + (uint64_t)b * a.cap + start;
     int32_t idx[kApplyPer];
     uint16_t val[kApplyPer];
     uint32_t live = 0;
@@ -688,7 +747,7 @@ __global__ __launch_bounds__(kThreads) void apply_kernel(const ApplyArgs a) {
         val[j] = ok ? Vb[k] : (uint16_t)0;
         live |= ok ? (1u << j) : 0u;
     }
-    scatter_pairs<MULTI>(a, sh, b, idx, val, live);
+    scatter_pairs<MULTI, EB>(a, sh, b, idx, val, live);
 }
 
 // 16-bit first differences (Sec. 3.3, index delta coding) decoded on the fly: thread t owns the

@@ -38,6 +38,7 @@ EXPORTS = [
     "srs_extract_cast", "srs_extract_cast_multi", "srs_plan_layout",
     "srs_bitmap_words", "srs_mark_multi", "srs_cast_mark_multi", "srs_extract_marked_multi",
     "srs_value_chunks", "srs_encode_values", "srs_decode_values",
+    "srs_extract_u8", "srs_apply_u8", "srs_extract_multi_u8", "srs_apply_multi_u8",
 ]
 
 
@@ -64,6 +65,10 @@ _lib.srs_plan_info.argtypes = [_vp, C.POINTER(_u64), _u32p, _u32p, _u32p]
 _lib.srs_plan_destroy.argtypes = [_vp]
 _lib.srs_extract_multi.argtypes = [_vp, _vp, C.POINTER(TensorPair), _vp, _vp, _vp, _u64, _vp]
 _lib.srs_apply_multi.argtypes = [_vp, _vp, C.POINTER(Tensor), _vp, _vp, _vp, _u64, _vp]
+_lib.srs_extract_u8.argtypes = _lib.srs_extract.argtypes
+_lib.srs_apply_u8.argtypes = _lib.srs_apply.argtypes
+_lib.srs_extract_multi_u8.argtypes = _lib.srs_extract_multi.argtypes
+_lib.srs_apply_multi_u8.argtypes = _lib.srs_apply_multi.argtypes
 _lib.srs_stream_probe.argtypes = [_vp, _vp, _vp, _u64, _vp, _vp]
 _lib.srs_stream_probe_sink_words.argtypes = [_u64]
 _lib.srs_stream_probe_sink_words.restype = _u64
@@ -114,16 +119,16 @@ def _stream_ptr(stream: Optional[torch.cuda.Stream]) -> int:
     return int(s.cuda_stream)
 
 
-def _dev16(t: torch.Tensor, what: str) -> None:
-    if not (isinstance(t, torch.Tensor) and t.is_cuda and t.element_size() == 2 and t.is_contiguous()):
-        raise TypeError(f"{what}: expected a contiguous 16-bit tensor on the GPU")
+def _dev16(t: torch.Tensor, what: str, width: int = 2) -> None:
+    if not (isinstance(t, torch.Tensor) and t.is_cuda and t.element_size() == width and t.is_contiguous()):
+        raise TypeError(f"{what}: expected a contiguous {8 * width}-bit tensor on the GPU")
 
 
-def _payload_ok(I: torch.Tensor, V: torch.Tensor, counts: torch.Tensor, nb: int, cap: int) -> None:
+def _payload_ok(I: torch.Tensor, V: torch.Tensor, counts: torch.Tensor, nb: int, cap: int, width: int = 2) -> None:
     if not (I.is_cuda and I.dtype == torch.int32 and I.is_contiguous() and I.numel() >= nb * cap):
         raise TypeError("I: expected contiguous int32 GPU tensor of at least nb*cap elements")
-    if not (V.is_cuda and V.element_size() == 2 and V.is_contiguous() and V.numel() >= nb * cap):
-        raise TypeError("V: expected contiguous 16-bit GPU tensor of at least nb*cap elements")
+    if not (V.is_cuda and V.element_size() == width and V.is_contiguous() and V.numel() >= nb * cap):
+        raise TypeError(f"V: expected contiguous {8 * width}-bit GPU tensor of at least nb*cap elements")
     if not (counts.is_cuda and counts.element_size() == 4 and counts.is_contiguous() and counts.numel() >= nb):
         raise TypeError("counts: expected contiguous 32-bit GPU tensor of at least nb elements")
 
@@ -248,25 +253,25 @@ class Context:
     def plan(self, numel: Sequence[int], bucket_elems: int) -> Plan:
         return Plan(self, numel, bucket_elems)
 
-    def bind_pairs(self, plan: Plan, old: Sequence[torch.Tensor], new: Sequence[torch.Tensor]):
+    def bind_pairs(self, plan: Plan, old: Sequence[torch.Tensor], new: Sequence[torch.Tensor], width: int = 2):
         """Marshals (old, new) tensor lists into the srs_tensor_pair[] host array once, for callers
         that repeat the same call (the array can be passed to extract_multi as ``pairs=``)."""
         if len(old) != len(plan.numel) or len(new) != len(plan.numel):
             raise ValueError("tensor list does not match the plan")
         arr = (TensorPair * max(len(old), 1))()
         for k, (o, w) in enumerate(zip(old, new)):
-            _dev16(o, f"old[{k}]"), _dev16(w, f"new[{k}]")
+            _dev16(o, f"old[{k}]", width), _dev16(w, f"new[{k}]", width)
             if o.numel() != plan.numel[k] or w.numel() != plan.numel[k]:
                 raise ValueError(f"tensor {k}: numel differs from the plan")
             arr[k].old_snapshot, arr[k].new_w = o.data_ptr(), w.data_ptr()
         return arr
 
-    def bind_weights(self, plan: Plan, weights: Sequence[torch.Tensor]):
+    def bind_weights(self, plan: Plan, weights: Sequence[torch.Tensor], width: int = 2):
         if len(weights) != len(plan.numel):
             raise ValueError("tensor list does not match the plan")
         arr = (Tensor * max(len(weights), 1))()
         for k, w in enumerate(weights):
-            _dev16(w, f"weights[{k}]")
+            _dev16(w, f"weights[{k}]", width)
             if w.numel() != plan.numel[k]:
                 raise ValueError(f"tensor {k}: numel differs from the plan")
             arr[k].weights = w.data_ptr()
@@ -290,6 +295,46 @@ class Context:
             _payload_ok(I, V, counts, plan.nbuckets, cap)
         _check(_lib.srs_apply_multi(self._h, plan._h, tensors, I.data_ptr(), V.data_ptr(), counts.data_ptr(), cap,
                                     _stream_ptr(stream)), "srs_apply_multi")
+
+    # ---- one-byte elements (FP8 synchronisation precision) ----------------------------------
+    def extract_u8(self, old: torch.Tensor, new: torch.Tensor, bucket_elems: int, I: torch.Tensor, V: torch.Tensor,
+                   counts: torch.Tensor, cap: int, stream: Optional[torch.cuda.Stream] = None) -> None:
+        _dev16(old, "old", 1), _dev16(new, "new", 1)
+        n = old.numel()
+        if new.numel() != n:
+            raise ValueError("old/new size mismatch")
+        if bucket_elems > 0 and cap > 0:
+            _payload_ok(I, V, counts, (n + bucket_elems - 1) // bucket_elems, cap, 1)
+        _check(_lib.srs_extract_u8(self._h, old.data_ptr(), new.data_ptr(), n, bucket_elems, I.data_ptr(),
+                                   V.data_ptr(), counts.data_ptr(), cap, _stream_ptr(stream)), "srs_extract_u8")
+
+    def apply_u8(self, weights: torch.Tensor, bucket_elems: int, I: torch.Tensor, V: torch.Tensor,
+                 counts: torch.Tensor, cap: int, stream: Optional[torch.cuda.Stream] = None) -> None:
+        _dev16(weights, "weights", 1)
+        n = weights.numel()
+        if bucket_elems > 0 and cap > 0:
+            _payload_ok(I, V, counts, (n + bucket_elems - 1) // bucket_elems, cap, 1)
+        _check(_lib.srs_apply_u8(self._h, weights.data_ptr(), n, bucket_elems, I.data_ptr(), V.data_ptr(),
+                                 counts.data_ptr(), cap, _stream_ptr(stream)), "srs_apply_u8")
+
+    def extract_multi_u8(self, plan: Plan, old: Optional[Sequence[torch.Tensor]],
+                         new: Optional[Sequence[torch.Tensor]], I: torch.Tensor, V: torch.Tensor, counts: torch.Tensor,
+                         cap: int, stream: Optional[torch.cuda.Stream] = None, pairs=None) -> None:
+        if pairs is None:
+            pairs = self.bind_pairs(plan, old, new, 1)
+        if cap > 0:
+            _payload_ok(I, V, counts, plan.nbuckets, cap, 1)
+        _check(_lib.srs_extract_multi_u8(self._h, plan._h, pairs, I.data_ptr(), V.data_ptr(), counts.data_ptr(), cap,
+                                         _stream_ptr(stream)), "srs_extract_multi_u8")
+
+    def apply_multi_u8(self, plan: Plan, weights: Optional[Sequence[torch.Tensor]], I: torch.Tensor, V: torch.Tensor,
+                       counts: torch.Tensor, cap: int, stream: Optional[torch.cuda.Stream] = None, tensors=None) -> None:
+        if tensors is None:
+            tensors = self.bind_weights(plan, weights, 1)
+        if cap > 0:
+            _payload_ok(I, V, counts, plan.nbuckets, cap, 1)
+        _check(_lib.srs_apply_multi_u8(self._h, plan._h, tensors, I.data_ptr(), V.data_ptr(), counts.data_ptr(), cap,
+                                       _stream_ptr(stream)), "srs_apply_multi_u8")
 
     # ---- fused cast + diff ----------------------------------------------------------------
     def extract_cast(self, weights: torch.Tensor, master: torch.Tensor, bucket_elems: int, I: torch.Tensor,
@@ -501,6 +546,14 @@ def alloc_encoded(nbuckets: int, cap: int, device) -> tuple:
     max_gap = torch.zeros(nbuckets, dtype=torch.int32, device=device)
     anchors = torch.full((max(anchor_count(nbuckets, cap), 1),), -1, dtype=torch.int32, device=device)
     return D, max_gap, anchors
+
+
+def alloc_payload_u8(nbuckets: int, cap: int, device) -> tuple:
+    """(I, V, counts) for the one-byte calls: V is uint8, filled with 0xFF."""
+    I = torch.full((nbuckets, cap), -1, dtype=torch.int32, device=device)
+    V = torch.full((nbuckets, cap), 0xFF, dtype=torch.uint8, device=device)
+    counts = torch.zeros(nbuckets, dtype=torch.int32, device=device)
+    return I, V, counts
 
 
 def alloc_payload(nbuckets: int, cap: int, device) -> tuple:
