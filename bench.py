@@ -151,6 +151,98 @@ def bench_cast(args, torch, srs, synth, wl, dev) -> int:
     return 0
 
 
+def bench_fp8(args, torch, srs, synth, wl, dev) -> int:
+    """The same tensor list at FP8 synchronisation precision (Sec. 2.1: 0.0655 % of the elements change):
+    srs_extract_multi_u8 + srs_apply_multi_u8 on one-byte patterns, buckets of the same 64 MiB, first with the
+    in-place snapshot refresh, then with the rotating snapshot.  Four sampled buckets of the last step are
+    compared with the oracle."""
+    import dataclasses
+
+    import numpy as np
+    import oracle
+    wl = dataclasses.replace(wl, name=wl.name + "+fp8", bucket_elems=2 * wl.bucket_elems,
+                             density=args.density or synth.FP8_DENSITY)
+    N, be = wl.numel, wl.bucket_elems
+    W0 = synth.ByteSet(wl, dev); W1 = synth.ByteSet(wl, dev); S = synth.ByteSet(wl, dev); R = synth.ByteSet(wl, dev)
+    synth.fill_base_fp8_(W0.flat, args.seed)
+    nchanged, _ = synth.iid_update_fp8_(W1.flat, W0.flat, wl.density, args.seed)
+    S.copy_from(W0); R.copy_from(W0)
+    rho = nchanged / N
+    log(f"fp8: {N} one-byte elements ({N / 1e9:.2f} GB per copy), {wl.num_buckets} buckets of {be}, {nchanged} changed "
+        f"(rho = {rho:.6f})")
+    versions = [W1, W0]
+    cap = (synth.payload_capacity(wl) + 15) // 16 * 16
+    out_modes = {}
+    for mode in ("refresh-in-place", "rotate"):
+        ctx = srs.Context(0)
+        if args.tile:
+            ctx.set_option(srs.OPT_TILE_ELEMS, args.tile)
+        if args.interleave:
+            ctx.set_option(srs.OPT_INTERLEAVE, args.interleave)
+        if mode == "rotate":
+            ctx.set_option(srs.OPT_SNAPSHOT, srs.SNAPSHOT_ROTATE)
+        plans = [ctx.plan(S.numels, be) for _ in (0, 1)]
+        nb = plans[0].nbuckets
+        I = torch.empty((nb, cap), dtype=torch.int32, device=dev)
+        V = torch.empty((nb, cap), dtype=torch.uint8, device=dev)
+        counts = torch.zeros(nb, dtype=torch.int32, device=dev)
+        if mode == "rotate":
+            pairs = [ctx.bind_pairs(plans[d], versions[1 - d].tensors, versions[d].tensors, 1) for d in (0, 1)]
+        else:
+            pairs = [ctx.bind_pairs(plans[d], S.tensors, versions[d].tensors, 1) for d in (0, 1)]
+        rolls = [ctx.bind_weights(plans[d], R.tensors, 1) for d in (0, 1)]
+        steps = max(2, args.steps // 2 * 2)            # even: both modes end where they started
+        ev = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(steps + 2)]
+        for k in range(steps + 2):                     # the first two are warm-up
+            d = k % 2
+            ev[k][0].record()
+            ctx.extract_multi_u8(plans[d], None, None, I, V, counts, cap, pairs=pairs[d])
+            ev[k][1].record()
+            ctx.apply_multi_u8(plans[d], None, I, V, counts, cap, tensors=rolls[d])
+            ev[k][2].record()
+        torch.cuda.synchronize()
+        flags = ctx.status()
+        last, prev = versions[1], versions[0]          # the last step (d = 1) went from versions[0] to versions[1]
+        total = int(counts.to(torch.int64).sum().item())
+        ok = flags == 0 and total == nchanged and torch.equal(R.flat, last.flat)
+        ok = ok and (mode == "rotate" or torch.equal(S.flat, last.flat))
+        if not ok and not args.no_check:
+            raise SystemExit(f"bench self-check failed (fp8, {mode}): flags={flags} counts={total} expected={nchanged}")
+        if not args.no_check:
+            ch = counts.cpu().numpy().view(np.uint32)
+            for b in sorted({0, nb // 3, nb // 2, nb - 1}):
+                lo, hi = b * be, min(N, (b + 1) * be)
+                oI, oV, oc, _ = oracle.extract_u8(prev.flat[lo:hi].cpu().numpy(), last.flat[lo:hi].cpu().numpy(), be, cap=cap)
+                c = int(oc[0])
+                if ch[b] != c or not np.array_equal(I[b, :c].cpu().numpy(), oI[0, :c]) \
+                        or not np.array_equal(V[b, :c].cpu().numpy(), oV[0, :c]):
+                    raise SystemExit(f"bench self-check failed (fp8, {mode}): bucket {b} differs from the oracle")
+        ext = sum(e[0].elapsed_time(e[1]) for e in ev[2:]) / steps
+        app = sum(e[1].elapsed_time(e[2]) for e in ev[2:]) / steps
+        per_changed = 5.0 if mode == "rotate" else 6.0         # I (4) + V (1) [+ snapshot (1)]
+        ach = (2.0 + per_changed * rho) * N / (ext * 1e-3) / 1e9
+        log(f"fp8 {mode}: extract {ext:.3f} ms = {ach:.0f} GB/s on (2 + {per_changed:.0f} rho) N bytes = "
+            f"{100 * ach / HBM_PEAK_GBS:.1f}% of peak, apply {app:.3f} ms")
+        out_modes[mode] = {"extract_ms": round(ext, 4), "apply_ms": round(app, 4), "achieved": round(ach, 1),
+                           "frac": round(ach / HBM_PEAK_GBS, 4)}
+        for pl in plans:
+            pl.close()
+        ctx.close()
+    m = out_modes["refresh-in-place"]
+    step_ms = m["extract_ms"] + m["apply_ms"]
+    out = {"metric": "extract+apply dense GB/s scanned (one-byte elements)", "value": round(2.0 * N / (step_ms * 1e-3) / 1e9, 1),
+           "unit": "GB/s", "n_gpus": 1, "steps": steps, "warmup": 2, "ms_per_step": round(step_ms, 4),
+           "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "u8", "data": "synthetic",
+           "config": {"workload": wl.name, "elements": N, "buckets": wl.num_buckets, "bucket_elems": be,
+                      "changed_fraction": round(rho, 6), "payload_cap": cap},
+           "extract_ms": m["extract_ms"], "apply_ms": m["apply_ms"],
+           "roofline": {"bound": "hbm", "kernel": "extract_kernel<u8>", "achieved": m["achieved"], "peak": HBM_PEAK_GBS,
+                        "unit": "GB/s", "frac": m["frac"], "traffic": None},
+           "rotating_snapshot": out_modes["rotate"], "cpu_baseline": None, "checked": not args.no_check}
+    print(json.dumps(out), flush=True)
+    return 0
+
+
 def chunked_sum(torch, flat) -> int:
     """Sum of the 16-bit patterns of a weight slab, in pieces that keep the temporaries small."""
     v = flat.view(torch.int16)
@@ -163,7 +255,7 @@ def rotating_leg(args, torch, srs, wl, versions, R, payload, cap, i0, nchanged, 
     ctx = srs.Context(0)
     ctx.set_option(srs.OPT_SNAPSHOT, srs.SNAPSHOT_ROTATE)
     ctx.set_option(srs.OPT_TILE_ELEMS, 16384)        # with no stores into the weights this mode measures best with
-    ctx.set_option(srs.OPT_INTERLEAVE, 1024)         # smaller tiles spread over all buckets
+    ctx.set_option(srs.OPT_INTERLEAVE, 256)          # smaller tiles spread over more buckets
     plans = [ctx.plan(R.numels, wl.bucket_elems) for _ in (0, 1)]
     pairs = [ctx.bind_pairs(plans[d], versions[1 - d].tensors, versions[d].tensors) for d in (0, 1)]
     rolls = [ctx.bind_weights(plans[d], R.tensors) for d in (0, 1)]
@@ -289,6 +381,9 @@ def main() -> int:
                     help="time the fused cast + diff instead (srs_extract_cast_multi on FP32 master weights that are "
                          "rebuilt, untimed, before every step; implies 3 resident sets: master, model parameters, "
                          "rollout copy) -- not the headline path")
+    ap.add_argument("--fp8", action="store_true",
+                    help="time the one-byte calls instead (srs_extract_multi_u8 / srs_apply_multi_u8): the same tensor "
+                         "list as E4M3 patterns, 0.0655 %% changed unless --density is given -- not the headline path")
     ap.add_argument("--cumulative", action="store_true",
                     help="time Alg. 1 as printed instead: srs_mark_multi (one optimizer step's diff OR-ed into the bitmap), "
                          "srs_extract_marked_multi, srs_apply_multi -- not the headline path")
@@ -327,6 +422,8 @@ def main() -> int:
         return bench_cast(args, torch, srs, synth, wl, dev)
     if args.cumulative:
         return bench_cumulative(args, torch, srs, synth, wl, dev)
+    if args.fp8:
+        return bench_fp8(args, torch, srs, synth, wl, dev)
 
     if args.rotate_snapshot and args.regen:
         print("bench.py: --rotate-snapshot alternates two resident versions; it cannot be combined with --regen",
@@ -363,9 +460,9 @@ def main() -> int:
     ctx.set_option(srs.OPT_INTERLEAVE, args.interleave) if args.interleave else None
     if args.rotate_snapshot:
         ctx.set_option(srs.OPT_SNAPSHOT, srs.SNAPSHOT_ROTATE)
-        # with no stores into the weights this mode measures best with smaller tiles spread over all buckets
+        # with no stores into the weights this mode measures best with smaller tiles spread over more buckets
         ctx.set_option(srs.OPT_TILE_ELEMS, args.tile or 16384)
-        ctx.set_option(srs.OPT_INTERLEAVE, args.interleave or 1024)
+        ctx.set_option(srs.OPT_INTERLEAVE, args.interleave or 256)
     # one plan per direction: each keeps its own device copy of the pointer table, so alternating the
     # `new` version does not re-upload it every step
     plans = [ctx.plan(S.numels, wl.bucket_elems), ctx.plan(S.numels, wl.bucket_elems)]

@@ -259,7 +259,7 @@ __device__ __forceinline__ uint32_t look_back(const ExtractArgs &a, uint32_t til
         bool found_prefix = false;
         uint32_t polls = 0;
         for (;;) {
-            if (in_bucket) {
+            if (in_bucket && flag == 0) {                                    // only lanes still waiting poll again
                 const unsigned long long w = status_load(a.status + idx);
                 const uint32_t hi = (uint32_t)(w >> 32);
                 flag = hi & 3u;

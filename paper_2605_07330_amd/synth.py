@@ -12,6 +12,7 @@ compare bit patterns.  The update densities bracket what Table 2 reports for BF1
 
 Recipe for one update (one "step"):
   * base weights  ~ N(0, 0.02) in fp32, rounded to BF16 (norm vectors are 1.0);
+    the FP8 stand-ins further down use the same shapes with E4M3 patterns and one-step moves;
   * a change mask, iid Bernoulli(p) per element unless the workload says otherwise;
   * at masked positions  new = bf16(old + N(0, 1e-3*|old| + 1e-6)); if the rounding gives
     back the old pattern the value is moved one BF16 step in the direction of the noise
@@ -363,6 +364,73 @@ def master_from_(master_flat: torch.Tensor, w_flat: torch.Tensor, seed: int, sal
         g = _gen(w_flat.device, seed, salt, c, 6)
         u = torch.rand(hi - lo, generator=g, device=w_flat.device, dtype=torch.float32) * 2.0 - 1.0
         master_flat[lo:hi] = w_flat[lo:hi].float() * (1.0 + u * (2.0 ** -10))
+
+
+# ----------------------------------------------------------------------------------------------
+# FP8 stand-ins (Sec. 2.1 measures 0.0655 % changed elements at FP8 synchronisation precision)
+# ----------------------------------------------------------------------------------------------
+
+FP8_DENSITY = 0.000655
+
+
+class ByteSet:
+    """The tensors of a workload as one-byte patterns (FP8 E4M3), carved end to end from one uint8 slab."""
+
+    def __init__(self, wl: Workload, device):
+        self.wl = wl
+        self.device = torch.device(device)
+        self.flat = torch.empty(wl.numel, dtype=torch.uint8, device=self.device)
+        self.tensors: List[torch.Tensor] = []
+        off = 0
+        for t in wl.tensors:
+            self.tensors.append(self.flat[off:off + t.numel])
+            off += t.numel
+
+    @property
+    def numels(self) -> List[int]:
+        return [t.numel for t in self.wl.tensors]
+
+    def copy_from(self, other: "ByteSet") -> None:
+        self.flat.copy_(other.flat)
+
+    def equal(self, other: "ByteSet") -> bool:
+        return all(torch.equal(a, b) for a, b in zip(self.tensors, other.tensors) if a.numel())
+
+
+def fill_base_fp8_(flat: torch.Tensor, seed: int, salt: int = 0) -> None:
+    """flat (uint8, 1-D) <- the E4M3 patterns of N(0, 1), chunk by chunk (FP8 weights are stored with a scale
+    factor that brings them into the format's range; the stand-in takes them already scaled)."""
+    n = flat.numel()
+    for c, lo in enumerate(range(0, n, _CHUNK)):
+        hi = min(n, lo + _CHUNK)
+        g = _gen(flat.device, seed, salt, c, 7)
+        x = torch.randn(hi - lo, generator=g, device=flat.device, dtype=torch.float32)
+        flat[lo:hi] = x.to(torch.float8_e4m3fn).view(torch.uint8)
+
+
+def iid_update_fp8_(new_flat: torch.Tensor, old_flat: torch.Tensor, p: float, seed: int, salt: int = 0
+                    ) -> Tuple[int, torch.Tensor]:
+    """new <- old with iid Bernoulli(p) positions moved to a neighbouring E4M3 value: one step in pattern space,
+    up or down at random, away from zero at +-0 and downwards from the largest finite magnitude (0x7E), so that
+    no NaN pattern (0x7F / 0xFF) appears and every masked position differs.  Returns (#changed, mask)."""
+    n = old_flat.numel()
+    changed = 0
+    masks = []
+    for c, lo in enumerate(range(0, n, _CHUNK)):
+        hi = min(n, lo + _CHUNK)
+        g = _gen(old_flat.device, seed, salt, c, 8)
+        mask = torch.rand(hi - lo, generator=g, device=old_flat.device) < p
+        up = torch.rand(hi - lo, generator=g, device=old_flat.device) < 0.5
+        ob = old_flat[lo:hi].to(torch.int32)
+        sign, mag = ob & 0x80, ob & 0x7F
+        step = torch.where(up, torch.ones_like(mag), -torch.ones_like(mag))
+        step = torch.where(mag == 0, torch.ones_like(mag), step)
+        step = torch.where(mag >= 0x7E, -torch.ones_like(mag), step)
+        nb = torch.where(mask, sign | (mag + step), ob)
+        new_flat[lo:hi] = nb.to(torch.uint8)
+        changed += int(mask.sum().item())
+        masks.append(mask)
+    return changed, torch.cat(masks) if masks else torch.zeros(0, dtype=torch.bool, device=old_flat.device)
 
 
 def payload_capacity(wl: Workload, max_bucket_count: Optional[int] = None) -> int:

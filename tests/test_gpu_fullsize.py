@@ -215,3 +215,52 @@ def test_largest_single_tensor(srs):
         ctx.close()
         del old, new
         free_all()
+
+
+def test_full_size_fp8_workload(srs):
+    """The 30B-A3B-shaped list as one-byte patterns at the FP8 density of Sec. 2.1 (0.0655 %), 64 MiB buckets,
+    library defaults.  The slab is the packed space, so bucket b of the list is the flat slice [b*be, (b+1)*be)
+    and the single-tensor oracle on that slice gives the bucket's payload."""
+    import dataclasses
+    print("case full-size fp8 cfg=2", flush=True)
+    wl = dataclasses.replace(synth.workload(2), bucket_elems=2 * synth.workload(2).bucket_elems, density=synth.FP8_DENSITY)
+    N, be = wl.numel, wl.bucket_elems
+    S = synth.ByteSet(wl, DEV); W1 = synth.ByteSet(wl, DEV); R = synth.ByteSet(wl, DEV)
+    ctx = srs.Context(0)
+    try:
+        synth.fill_base_fp8_(S.flat, 5)
+        nchanged, _ = synth.iid_update_fp8_(W1.flat, S.flat, wl.density, 5)
+        R.copy_from(S)
+        sigma = (N * wl.density * (1 - wl.density)) ** 0.5
+        assert abs(nchanged - N * wl.density) < 6 * sigma
+        plan = ctx.plan(S.numels, be)
+        nb = plan.nbuckets
+        assert nb == wl.num_buckets == (N + be - 1) // be
+        cap = (synth.payload_capacity(wl) + 15) // 16 * 16
+        I, V, counts = srs.alloc_payload_u8(nb, cap, DEV)
+        picks = sorted({0, 1, nb // 2, nb - 2, nb - 1} | {int(x) for x in np.random.default_rng(5).integers(0, nb, 8)})
+        before = {b: (S.flat[b * be:(b + 1) * be].cpu().numpy(), W1.flat[b * be:(b + 1) * be].cpu().numpy()) for b in picks}
+        ctx.extract_multi_u8(plan, S.tensors, W1.tensors, I, V, counts, cap)
+        ctx.apply_multi_u8(plan, R.tensors, I, V, counts, cap)
+        assert ctx.status() == 0
+        c64 = counts.to(torch.int64)
+        assert int(c64.sum().item()) == nchanged and int(c64.max().item()) <= cap
+        live = torch.arange(cap, device=DEV).unsqueeze(0) < c64.unsqueeze(1)
+        I64 = I.to(torch.int64)
+        blen = torch.full((nb,), be, dtype=torch.int64, device=DEV); blen[-1] = N - (nb - 1) * be
+        assert bool((((I64 >= 0) & (I64 < blen.unsqueeze(1))) | ~live).all().item()), "index outside its bucket"
+        assert bool(((I64[:, 1:] > I64[:, :-1]) | ~live[:, 1:]).all().item()), "indices not strictly ascending"
+        assert bool(((I == -1) | live).all().item()), "slot beyond counts was written"
+        assert S.equal(W1) and R.equal(W1)
+        ch = counts.cpu().numpy().view(np.uint32)
+        for b in picks:
+            old_h, new_h = before[b]
+            oI, oV, oc, ovf = oracle.extract_u8(old_h.copy(), new_h, be, cap=cap)
+            c = int(oc[0])
+            assert ovf == 0 and ch[b] == c, f"bucket {b}: count"
+            assert np.array_equal(I[b, :c].cpu().numpy(), oI[0, :c]) and np.array_equal(V[b, :c].cpu().numpy(), oV[0, :c]), f"bucket {b}"
+        plan.close()
+    finally:
+        ctx.close()
+        del S, W1, R
+        free_all()
