@@ -193,7 +193,8 @@ int srs_extract_cast_multi(srs_ctx *ctx, srs_plan *plan, const srs_tensor_pair *
  *                        (in/out), t[k].new_w the FP32 master weights; parameters <- round_BF16(master) and every
  *                        element whose pattern changed is marked.
  *   srs_extract_marked_multi  the payload of the marked positions, ascending per bucket, with the current values
- *                        of t[k].weights; layout, capacity rule and flags as srs_extract_multi.
+ *                        of t[k].weights; layout, capacity rule and flags as srs_extract_multi.  Only the bitmap
+ *                        and the marked elements are read (a gather), not the whole weight set.
  */
 uint64_t srs_bitmap_words(uint64_t total_elems);
 int srs_mark_multi(srs_ctx *ctx, srs_plan *plan, const srs_tensor_pair *t, uint32_t *bitmap, void *stream);

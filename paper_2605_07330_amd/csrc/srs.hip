@@ -118,10 +118,21 @@ template <bool MULTI>
 int launch_extract(const srs_ctx *ctx, uint32_t tile_elems, const ExtractArgs &a, hipStream_t st, int src, int eb = 2) {
     if (eb == 1) return launch_extract_u8<MULTI>(ctx, tile_elems, a, st);
     const dim3 grid(a.ntiles), block(kThreads);
+    if (src == kSrcBitmap) {                   // the bitmap says where the changes are: gather, do not stream
+        if (!MULTI) return SRS_ERR_INVALID;
+        switch (tile_elems) {
+            case 4096: hipLaunchKernelGGL((extract_marked_kernel<16>), grid, block, 0, st, a); break;
+            case 8192: hipLaunchKernelGGL((extract_marked_kernel<32>), grid, block, 0, st, a); break;
+            case 16384: hipLaunchKernelGGL((extract_marked_kernel<64>), grid, block, 0, st, a); break;
+            case 32768: hipLaunchKernelGGL((extract_marked_kernel<128>), grid, block, 0, st, a); break;
+            default: return SRS_ERR_INVALID;
+        }
+        SRS_HIP(hipGetLastError());
+        return SRS_OK;
+    }
 #define SRS_LAUNCH(VV)                                                                                                \
     do {                                                                                                              \
         if (src == kSrcFp32) hipLaunchKernelGGL((extract_kernel<VV, MULTI, 4, kSrcFp32>), grid, block, 0, st, a);     \
-        else if (src == kSrcBitmap) hipLaunchKernelGGL((extract_kernel<VV, MULTI, 0, kSrcBitmap>), grid, block, 0, st, a); \
         else if (ctx->rotate_snapshot) hipLaunchKernelGGL((extract_kernel<VV, MULTI, -1>), grid, block, 0, st, a);    \
         else if (ctx->refresh_group == 8) hipLaunchKernelGGL((extract_kernel<VV, MULTI, 8>), grid, block, 0, st, a);  \
         else if (ctx->refresh_group == 4) hipLaunchKernelGGL((extract_kernel<VV, MULTI, 4>), grid, block, 0, st, a);  \

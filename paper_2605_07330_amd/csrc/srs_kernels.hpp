@@ -14,8 +14,10 @@
 //   (index, value) pairs of the tile in LDS in rank order and writes them out coalesced
 //   (Alg. 2: V = W[I], I int32 ascending), refreshing the snapshot at the same positions.
 //   Template flavours of the same kernel: SRC = FP32 master weights rounded to BF16 on the fly (the
-//   cast-and-copy of Alg. 1 fused with its diff), SRC = bitmap (masks come from the cumulative index set).
+//   cast-and-copy of Alg. 1 fused with its diff); EB = 1 for one-byte (FP8) patterns; RG = -1 leaves the
+//   snapshot untouched for callers that rotate buffers.
 // mark_kernel: one optimizer step of Alg. 1's index accumulation, OR-ed into a bitmap.
+// extract_marked_kernel: the payload of the accumulated index set, gathered through the bitmap.
 // apply_kernel: the scatter of Alg. 3, W[I] <- V, one workgroup per (bucket, payload chunk).
 // apply_encoded_kernel / encode_indices_kernel: the 16-bit index delta coding of Sec. 3.3.
 // route_kernel / dense_copy_kernel: the per-bucket sparse / dense routing of Sec. 3.4 and its full-copy route.
@@ -302,28 +304,17 @@ __device__ __forceinline__ uint32_t look_back(const ExtractArgs &a, uint32_t til
 // CAST: `new` is not a BF16 buffer but the FP32 master weights; each element is rounded to BF16
 // (nearest even, NaN -> 0x7FC0) on the fly and `old` is the model-parameter buffer itself: the cast-and-
 // copy of Alg. 1 fused with its diff, so that no snapshot exists at all.
-// SRC = kSrcBitmap: there is no `old` at all; the change masks are read from the cumulative bitmap of
-// Alg. 1 (mark_kernel builds it step by step) and `new` is the current weights: Alg. 2's V = W[I] over the
-// accumulated index set.
+// (The cumulative index set of Alg. 1 has a kernel of its own, extract_marked_kernel; kSrcBitmap only names that
+// source for the host code.)
 constexpr int kSrcBf16 = 0, kSrcFp32 = 1, kSrcBitmap = 2;
-
-// the 8 mask bits of packed positions g .. g+7, of which only the first `nbits` exist
-__device__ __forceinline__ uint32_t bitmap_bits8(const uint32_t *bitmap, uint64_t words, uint64_t g, uint32_t nbits) {
-    const uint64_t w = g >> 5;
-    const uint32_t sh = (uint32_t)(g & 31u);
-    const uint32_t lo = bitmap[w];
-    const uint32_t hi = (sh > 24u && w + 1 < words) ? bitmap[w + 1] : 0u;
-    const uint32_t bits = (uint32_t)((((unsigned long long)hi << 32) | lo) >> sh) & 0xFFu;
-    return nbits >= 8u ? bits : (bits & ((1u << nbits) - 1u));
-}
 
 template <int V, bool MULTI, int RG, int SRC = kSrcBf16, int EB = 2>
 __global__ __launch_bounds__(kThreads) void extract_kernel(const ExtractArgs a) {
     constexpr bool NT = false;
     constexpr bool CAST = (SRC == kSrcFp32);
-    constexpr bool MARKED = (SRC == kSrcBitmap);
+    static_assert(SRC == kSrcBf16 || SRC == kSrcFp32, "the bitmap source has its own kernel");
     static_assert(V % 2 == 0, "counts are scanned in packed pairs");
-    static_assert(EB == 2 || SRC == kSrcBf16, "the cast and bitmap flavours exist for 16-bit elements only");
+    static_assert(EB == 2 || SRC == kSrcBf16, "the cast flavour exists for 16-bit elements only");
     typedef Elem<EB> EL;
     typedef typename EL::type T;
     constexpr uint32_t VE = 16u / EB;                    // elements per 16-byte vector
@@ -334,7 +325,6 @@ __global__ __launch_bounds__(kThreads) void extract_kernel(const ExtractArgs a) 
     __shared__ uint32_t s_wave_total[kWaves];
     __shared__ uint32_t s_excl;
     __shared__ uint32_t s_stage[kStage];
-    __shared__ uint32_t s_bits[MARKED ? TILE / 32 : 1];     // the tile's slice of the bitmap (MARKED only)
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
 
@@ -373,14 +363,12 @@ __global__ __launch_bounds__(kThreads) void extract_kernel(const ExtractArgs a) 
     // ---- where this tile lives
     uint32_t bucket_off, len, idx_base;
     T *po; const void *pn_raw; uint64_t pn_off;      // new weights: base pointer and element offset
-    uint64_t g0 = 0;                                        // packed position of the tile's first element (MARKED)
     if (MULTI) {
         const TileDesc d = a.tiles[tile];
         const PtrPair p = a.ptrs[d.tensor];
         po = reinterpret_cast<T *>(p.old_w) + d.tensor_off; pn_raw = p.new_w; pn_off = d.tensor_off;
         bucket_off = d.bucket_off; len = d.len;
         idx_base = bucket_off;                          // index = position inside the bucket
-        if (MARKED) g0 = a.tensor_base[d.tensor] + d.tensor_off;
     } else {
         const uint64_t b0 = (uint64_t)bucket * a.be;
         const uint32_t blen = (uint32_t)((a.n - b0 < a.be) ? (a.n - b0) : a.be);
@@ -388,7 +376,6 @@ __global__ __launch_bounds__(kThreads) void extract_kernel(const ExtractArgs a) 
         len = (blen - bucket_off < TILE) ? (blen - bucket_off) : TILE;
         po = reinterpret_cast<T *>(a.old_w) + b0 + bucket_off; pn_raw = a.new_w; pn_off = b0 + bucket_off;
         idx_base = (uint32_t)(b0 + bucket_off);         // index = tensor-flat position
-        if (MARKED) g0 = b0 + bucket_off;
     }
 
     // ---- stream the tile.  Layout: wave w owns elements [w*V*ROW, (w+1)*V*ROW); inside it vector j
@@ -399,39 +386,9 @@ __global__ __launch_bounds__(kThreads) void extract_kernel(const ExtractArgs a) 
     const uint32_t *const pf = reinterpret_cast<const uint32_t *>(pn_raw) + pn_off;
     const T *const pn = reinterpret_cast<const T *>(pn_raw) + pn_off;
     const bool aligned = CAST ? (((((uintptr_t)po) | ((uintptr_t)pf)) & 15u) == 0)
-                     : MARKED ? ((((uintptr_t)pn) & 15u) == 0)
                               : (((((uintptr_t)po) | ((uintptr_t)pn)) & 15u) == 0);
     uint32_t m[V];
-    if (MARKED) {
-        // masks from the bitmap.  The weights of the tile are streamed in full, independently of the bitmap
-        // loads: making them wait for the masks (to skip rows without a set bit) halves the loads in flight
-        // and measured slower at every density down to 0.1 %.
-        const u32x4 zero = {0, 0, 0, 0};
-        if (aligned && len == TILE && (g0 & 31u) == 0) {
-            // straight-line: every load is issued before the first use.  The tile's TILE/32 bitmap words come in
-            // with one coalesced load per thread and are handed out through LDS, one byte (8 elements) per lane.
-            for (uint32_t i = tid; i < TILE / 32; i += kThreads) s_bits[i] = a.bitmap[(g0 >> 5) + i];
-#pragma unroll
-            for (int j = 0; j < V; ++j) { xo[j] = zero; xn[j] = load16<NT>(pn + e0 + j * ROW); }
-            __syncthreads();
-            const uint8_t *const bytes = reinterpret_cast<const uint8_t *>(s_bits);
-#pragma unroll
-            for (int j = 0; j < V; ++j) m[j] = bytes[(e0 >> 3) + j * 64];
-        } else if (aligned && len == TILE) {
-#pragma unroll
-            for (int j = 0; j < V; ++j) { xo[j] = zero; xn[j] = load16<NT>(pn + e0 + j * ROW); }
-#pragma unroll
-            for (int j = 0; j < V; ++j) m[j] = bitmap_bits8(a.bitmap, a.bitmap_words, g0 + e0 + j * ROW, 8u);
-        } else {
-#pragma unroll
-            for (int j = 0; j < V; ++j) {
-                const uint32_t e = e0 + j * ROW;
-                xo[j] = zero;
-                xn[j] = (aligned && e + VE <= len) ? load16<false>(pn + e) : EL::load_guarded(pn, e, len);
-                m[j] = (e < len) ? bitmap_bits8(a.bitmap, a.bitmap_words, g0 + e, len - e) : 0u;
-            }
-        }
-    } else if (aligned && len == TILE) {
+    if (aligned && len == TILE) {
         if (CAST) {
             u32x4 f0[V], f1[V];
 #pragma unroll
@@ -466,13 +423,11 @@ __global__ __launch_bounds__(kThreads) void extract_kernel(const ExtractArgs a) 
 
     // ---- change masks and their counts
     uint32_t pk[V / 2];
-    if (!MARKED) {
 #pragma unroll
-        for (int j = 0; j < V; ++j) m[j] = EL::diff_mask(xo[j], xn[j]);
-    }
+    for (int j = 0; j < V; ++j) m[j] = EL::diff_mask(xo[j], xn[j]);
 
     // ---- snapshot refresh of full tiles, RG lanes (RG*16 bytes) at a time
-    const bool group_refresh = !MARKED && (RG > 0) && aligned && len == TILE;      // uniform
+    const bool group_refresh = (RG > 0) && aligned && len == TILE;      // uniform
     if (group_refresh) {
 #pragma unroll
         for (int j = 0; j < V; ++j) {
@@ -556,12 +511,146 @@ __global__ __launch_bounds__(kThreads) void extract_kernel(const ExtractArgs a) 
             const uint64_t r = (uint64_t)excl + r0 + k;
             if (local < len) {                      // always true for a correct scan; keeps stores in bounds
                 if (r < a.cap) { Ib[r] = (int32_t)(idx_base + local); Vb[r] = val; }
-                if (!MARKED && RG >= 0 && !group_refresh) po[local] = val;   // snapshot refresh: W_prev <- W at changed positions
+                if (RG >= 0 && !group_refresh) po[local] = val;   // snapshot refresh: W_prev <- W at changed positions
             }
         }
         __syncthreads();
     }
 
+}
+
+// ---------------------------------------------------------------------------------------------
+// extract_marked_kernel: Alg. 2's V = W[I] over the cumulative index set of Alg. 1, held as a bitmap over packed
+// positions (mark_kernel builds it).  The bitmap already says where the changes are, so the weights are not
+// streamed: the workgroup reads its tile's slice of the bitmap (one bit per element), ranks the set bits like
+// extract_kernel ranks changed elements (wave scan, LDS combine, the same per-bucket ticket and look-back chain),
+// stages their tile-local positions in LDS in rank order, and only then fetches the values, one 2-byte gather
+// per pair, balanced over the 256 threads and written out coalesced next to the indices.  Memory traffic is the
+// bitmap plus the lines that hold a marked element instead of the whole weight set.
+// E = elements per thread (tile of the plan / 256); thread t owns the tile-local positions [t*E, (t+1)*E).
+// ---------------------------------------------------------------------------------------------
+
+// the nbits (1..32) bitmap bits of packed positions g .. g+nbits-1, bit k of the result for position g + k
+__device__ __forceinline__ uint32_t bitmap_bits32(const uint32_t *bitmap, uint64_t words, uint64_t g, uint32_t nbits) {
+    const uint64_t w = g >> 5;
+    const uint32_t sh = (uint32_t)(g & 31u);
+    const uint32_t lo = bitmap[w];
+    const uint32_t hi = (sh != 0u && sh + nbits > 32u && w + 1 < words) ? bitmap[w + 1] : 0u;
+    const uint32_t bits = (uint32_t)((((unsigned long long)hi << 32) | lo) >> sh);
+    return nbits >= 32u ? bits : (bits & ((1u << nbits) - 1u));
+}
+
+template <int E>
+__global__ __launch_bounds__(kThreads) void extract_marked_kernel(const ExtractArgs a) {
+    static_assert(E == 16 || E == 32 || E == 64 || E == 128, "tile of 4096 .. 32768 elements");
+    constexpr int NW = (E + 31) / 32;                    // mask words per thread
+    constexpr uint32_t CH = (E < 32) ? (uint32_t)E : 32u; // elements per mask word
+    constexpr int kGather = 4;                           // gathers in flight per thread in the write-out loop
+    __shared__ uint32_t s_ticket;
+    __shared__ uint32_t s_wave_total[kWaves];
+    __shared__ uint32_t s_excl;
+    __shared__ uint32_t s_stage[kStage];                 // tile-local positions in rank order
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+
+    // ---- bucket, ticket, tile: as in extract_kernel (tensor lists only)
+    const uint32_t bucket = a.wg_bucket[blockIdx.x];
+    const uint32_t first_tile = a.bucket_first[bucket];
+    const uint32_t bucket_tiles = a.bucket_first[bucket + 1] - first_tile;
+    if (tid == 0)
+        s_ticket = __hip_atomic_fetch_add(a.tickets + (uint64_t)bucket * a.ticket_stride, 1u, __ATOMIC_RELAXED,
+                                          __HIP_MEMORY_SCOPE_AGENT);
+    __syncthreads();
+    const uint32_t k = uniform(s_ticket);
+    if (k >= bucket_tiles) return;
+    const uint32_t tile = first_tile + k;
+    const bool last = (k == bucket_tiles - 1);
+    const TileDesc d = a.tiles[tile];
+    const uint16_t *const pn = reinterpret_cast<const uint16_t *>(a.ptrs[d.tensor].new_w) + d.tensor_off;
+    const uint32_t len = d.len, idx_base = d.bucket_off;
+    const uint64_t g0 = a.tensor_base[d.tensor] + d.tensor_off;      // packed position of the tile's first element
+
+    // ---- this thread's slice of the bitmap and its count
+    const uint32_t e0 = (uint32_t)tid * E;
+    uint32_t m[NW];
+    uint32_t mine = 0;
+#pragma unroll
+    for (int c = 0; c < NW; ++c) {
+        const uint32_t e = e0 + c * 32u;
+        const uint32_t left = (e < len) ? (len - e) : 0u;
+        const uint32_t nbits = left < CH ? left : CH;
+        m[c] = nbits ? bitmap_bits32(a.bitmap, a.bitmap_words, g0 + e, nbits) : 0u;
+        mine += __popc(m[c]);
+    }
+    const uint32_t inc = wave_inclusive_scan(mine);                  // at most 64 * 128 per wave
+    const uint32_t wave_total = lane63(inc);
+    if (lane == 0) s_wave_total[wave] = wave_total;
+    __syncthreads();
+    uint32_t wave_base = 0, tile_total = 0;
+#pragma unroll
+    for (int w = 0; w < kWaves; ++w) {
+        const uint32_t t = s_wave_total[w];
+        wave_base += (w < wave) ? t : 0u;
+        tile_total += t;
+    }
+    tile_total = uniform(tile_total);
+
+    // ---- chain with the earlier tiles of the bucket
+    if (wave == 0) {
+        uint32_t excl = 0;
+        if (tile == first_tile) {
+            if (lane == 0) status_store(a.status + tile, status_word(kStPrefix, tile_total));
+        } else {
+            if (lane == 0) status_store(a.status + tile, status_word(kStAgg, tile_total));
+            excl = look_back(a, tile, first_tile, lane);
+            if (lane == 0) status_store(a.status + tile, status_word(kStPrefix, excl + tile_total));
+        }
+        if (lane == 0) {
+            s_excl = excl;
+            if (last) {
+                const uint32_t c = excl + tile_total;
+                a.counts[bucket] = c;
+                if ((uint64_t)c > a.cap) atomicOr(a.flags, kFlagOverflow);
+            }
+        }
+    }
+
+    // ---- positions into LDS in rank order, then gather + coalesced write-out, kStage pairs per round
+    int32_t *const Ib = a.I + (uint64_t)bucket * a.cap;
+    uint16_t *const Vb = a.V + (uint64_t)bucket * a.cap;
+    for (uint32_t r0 = 0; r0 < tile_total; r0 += kStage) {
+        uint32_t rank = wave_base + (inc - mine) - r0;               // wraps for pairs of earlier rounds: skipped below
+#pragma unroll
+        for (int c = 0; c < NW; ++c) {
+            uint32_t mm = m[c];
+            while (mm) {
+                const uint32_t e = (uint32_t)__builtin_ctz(mm);
+                mm &= mm - 1u;
+                if (rank < kStage) s_stage[rank] = e0 + c * 32u + e;
+                ++rank;
+            }
+        }
+        __syncthreads();
+        const uint32_t excl = s_excl;
+        const uint32_t nst = (tile_total - r0 < kStage) ? (tile_total - r0) : kStage;
+        for (uint32_t k0 = tid; k0 < nst; k0 += kGather * kThreads) {
+            uint32_t local[kGather];
+            uint16_t val[kGather];
+#pragma unroll
+            for (int u = 0; u < kGather; ++u) {
+                const uint32_t kk = k0 + u * kThreads;
+                local[u] = (kk < nst) ? s_stage[kk] : 0xFFFFFFFFu;
+            }
+#pragma unroll
+            for (int u = 0; u < kGather; ++u) val[u] = (local[u] < len) ? pn[local[u]] : (uint16_t)0;
+#pragma unroll
+            for (int u = 0; u < kGather; ++u) {
+                const uint64_t r = (uint64_t)excl + r0 + k0 + u * kThreads;
+                if (local[u] < len && r < a.cap) { Ib[r] = (int32_t)(idx_base + local[u]); Vb[r] = val[u]; }
+            }
+        }
+        __syncthreads();
+    }
 }
 
 // ---------------------------------------------------------------------------------------------
