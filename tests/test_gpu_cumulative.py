@@ -128,3 +128,35 @@ def test_odd_shapes_and_capacity(srs):
     finally:
         c.close()
     assert_payload_equal(payload_to_host(I, V, counts), (wI, wV, wc), "marked, overflow")
+
+
+@pytest.mark.parametrize("tile", [4096, 8192, 16384, 32768])
+@pytest.mark.parametrize("density", [0.0, 0.003, 0.2, 1.0])
+def test_bitmap_gather_every_tile_size(srs, tile, density):
+    """The bitmap is given directly (any set of positions is a valid index set): empty, sparse, dense enough for
+    several staging rounds per tile, and all ones; odd tensor sizes put tile starts at every bit offset of a word."""
+    print(f"case bitmap gather tile={tile} density={density}", flush=True)
+    numel = [33, 70001, 1, 0, 131072, 4097, 95, 262144 + 17]
+    total, be = sum(numel), 150000
+    rng = np.random.default_rng(int(density * 1000) + tile)
+    cur = [rng.integers(0, 1 << 16, size=m, dtype=np.uint16) for m in numel]
+    bits = (rng.random(total) < density) if density < 1.0 else np.ones(total, bool)
+    words = oracle.bitmap_words(total)
+    padded = np.zeros(words * 32, bool); padded[:total] = bits
+    bm = np.packbits(padded.reshape(-1, 32), axis=1, bitorder="little").view(np.uint32).reshape(-1).copy()
+    cap = be
+    wI, wV, wc, ovf = oracle.extract_marked_multi(cur, numel, be, bm, cap=cap)
+    assert ovf == 0 and int(wc.sum()) == int(bits.sum())
+    c = srs.Context(0)
+    try:
+        c.set_option(srs.OPT_TILE_ELEMS, tile)
+        plan = c.plan(numel, be)
+        d_cur = [from_u16(w, DEV) for w in cur]
+        bitmap = torch.from_numpy(bm.view(np.int32)).to(DEV)
+        I, V, counts = srs.alloc_payload(plan.nbuckets, cap, DEV)
+        c.extract_marked_multi(plan, d_cur, bitmap, I, V, counts, cap)
+        assert c.status() == 0
+        plan.close()
+    finally:
+        c.close()
+    assert_payload_equal(payload_to_host(I, V, counts), (wI, wV, wc), "bitmap gather")
