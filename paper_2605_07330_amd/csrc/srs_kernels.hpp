@@ -1050,57 +1050,84 @@ __global__ __launch_bounds__(kThreads) void vc_hist_kernel(const ValueCodecArgs 
     if (h[threadIdx.x]) atomicAdd(a.hist + (uint64_t)b * 256 + threadIdx.x, h[threadIdx.x]);
 }
 
-// one workgroup per bucket; lane 0 builds the Huffman lengths exactly as the header specifies (two smallest
-// live nodes, ties to the smaller id; weights halved until no length exceeds 12), then all threads derive
-// the canonical codes.  At most 256 leaves: the sequential part is a few ten thousand steps at worst.
+// One workgroup per bucket builds the Huffman lengths exactly as the header specifies (merge the two smallest
+// live nodes, ties to the smaller id; weights halved until no length exceeds 12), then all threads derive the
+// canonical codes.  The merge runs in wave 0: node ids 0..255 are the symbols, 256.. the merged nodes in order
+// of creation; lane l keeps the keys (weight << 9 | id) of the nodes l, l + 64, ... l + 448 in registers (all
+// ones = not live), so "the smallest live node by (weight, id)" is a wave-wide minimum of one 64-bit key per
+// lane and a merge step is two of those.  The leaf depths are then read off the parent array by all threads.
+__device__ __forceinline__ unsigned long long wave_min_u64(unsigned long long x) {
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        const unsigned long long y = __shfl_xor(x, d, 64);
+        x = y < x ? y : x;
+    }
+    return x;
+}
+
 __global__ __launch_bounds__(kThreads) void vc_build_kernel(const ValueCodecArgs a) {
-    __shared__ unsigned long long weight[511];
-    __shared__ int parent[511];
-    __shared__ uint16_t live[256];
+    constexpr unsigned long long kDead = ~0ull;
+    __shared__ int16_t parent[512];
     __shared__ uint32_t w0[256];
     __shared__ uint8_t len[256];
     __shared__ uint32_t count_l[kVcMaxLen + 2];
+    __shared__ uint32_t s_used, s_maxlen;
     const uint32_t b = blockIdx.x, s = threadIdx.x;
+    const int lane = s & 63;
     w0[s] = a.hist[(uint64_t)b * 256 + s];
     len[s] = 0;
     if (s < kVcMaxLen + 2) count_l[s] = 0;
+    if (s == 0) s_used = 0;
     __syncthreads();
-    if (s == 0) {
-        int used = 0;
-        for (int i = 0; i < 256; ++i) used += w0[i] != 0;
-        while (used > 0) {
-            // live[]: ids of the nodes not merged yet (unordered); the two smallest by (weight, id) are merged
-            int nlive = 0, nnodes = 256;
-            for (int i = 0; i < 256; ++i) {
-                parent[i] = -1;
-                if (w0[i]) { weight[i] = w0[i]; live[nlive++] = (uint16_t)i; }
+    if (w0[s]) atomicAdd(&s_used, 1u);
+    __syncthreads();
+    const uint32_t used = s_used;
+    while (used > 0) {                                       // uniform: every thread takes every barrier
+        parent[s] = -1; parent[s + 256] = -1;
+        if (s == 0) s_maxlen = 0;
+        __syncthreads();
+        if (s < 64) {
+            unsigned long long key[8];
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const uint32_t id = (uint32_t)lane + 64u * r, w = w0[id];
+                key[r] = w ? (((unsigned long long)w << 9) | id) : kDead;
+                key[r + 4] = kDead;                           // merged nodes 256 + lane + 64 r: none yet
             }
-            while (nlive > 1) {
-                int px = -1, py = -1;                                // positions in live[] of the smallest, second smallest
-                for (int p = 0; p < nlive; ++p) {
-                    const int i = live[p];
-                    if (px < 0 || weight[i] < weight[live[px]] || (weight[i] == weight[live[px]] && i < live[px])) { py = px; px = p; }
-                    else if (py < 0 || weight[i] < weight[live[py]] || (weight[i] == weight[live[py]] && i < live[py])) { py = p; }
+            uint32_t nnodes = 256;
+            for (uint32_t nlive = used; nlive > 1; --nlive, ++nnodes) {
+                unsigned long long pick[2];
+#pragma unroll
+                for (int t = 0; t < 2; ++t) {                 // the smallest, then the smallest of what is left
+                    unsigned long long m = key[0];
+#pragma unroll
+                    for (int r = 1; r < 8; ++r) m = key[r] < m ? key[r] : m;
+                    m = wave_min_u64(m);
+                    pick[t] = m;
+#pragma unroll
+                    for (int r = 0; r < 8; ++r) if (key[r] == m) key[r] = kDead;      // ids are unique: one lane, one slot
                 }
-                const int x = live[px], y = live[py];
-                weight[nnodes] = weight[x] + weight[y];
-                parent[nnodes] = -1; parent[x] = parent[y] = nnodes;
-                live[px] = (uint16_t)nnodes;                         // the merged node takes one slot, the last entry the other
-                live[py] = live[nlive - 1];
-                --nlive; ++nnodes;
+                const uint32_t x = (uint32_t)(pick[0] & 511u), y = (uint32_t)(pick[1] & 511u);
+                const unsigned long long wsum = (pick[0] >> 9) + (pick[1] >> 9);
+                if (lane == 0) { parent[x] = (int16_t)nnodes; parent[y] = (int16_t)nnodes; }
+                const uint32_t slot = nnodes - 256u;          // owner: lane slot & 63, register 4 + slot / 64
+#pragma unroll
+                for (int r = 0; r < 4; ++r)
+                    if ((slot >> 6) == (uint32_t)r && (slot & 63u) == (uint32_t)lane) key[r + 4] = (wsum << 9) | nnodes;
             }
-            uint32_t maxlen = 0;
-            for (int i = 0; i < 256; ++i) {
-                if (!w0[i]) { len[i] = 0; continue; }
-                uint32_t d = 0;
-                for (int j = i; parent[j] >= 0; j = parent[j]) ++d;
-                if (used == 1) d = 1;
-                len[i] = (uint8_t)d;
-                maxlen = d > maxlen ? d : maxlen;
-            }
-            if (maxlen <= kVcMaxLen) break;
-            for (int i = 0; i < 256; ++i) if (w0[i]) w0[i] = (w0[i] + 1) / 2;
         }
+        __syncthreads();
+        uint32_t d = 0;
+        if (w0[s]) {
+            for (int jn = (int)s; parent[jn] >= 0; jn = parent[jn]) ++d;
+            if (used == 1) d = 1;
+            atomicMax(&s_maxlen, d);
+        }
+        len[s] = (uint8_t)d;
+        __syncthreads();
+        if (s_maxlen <= kVcMaxLen) break;
+        if (w0[s]) w0[s] = (w0[s] + 1) / 2;
+        __syncthreads();
     }
     __syncthreads();
     const uint32_t l = len[s];
@@ -1176,24 +1203,30 @@ __global__ __launch_bounds__(kThreads) void vc_encode_kernel(const ValueCodecArg
 }
 
 // per (bucket, group of kVcDecodeChunks chunks): rebuild the code from its lengths, fill a 4096-entry table
-// indexed by the next 12 stream bits, then for each chunk let 32 lanes decode 64 values each and write the values
-// (decoded high byte | stored low byte) coalesced
+// indexed by the next 12 stream bits, bring the group's bit streams into LDS, then all 256 threads decode at
+// once -- 32 threads per chunk, 64 values each, every thread starting at its own recorded bit offset -- and the
+// values (decoded high byte | stored low byte) are written coalesced
 constexpr uint32_t kVcDecodeChunks = 8;
+static_assert(kVcDecodeChunks * 32 == kThreads, "one thread per sub-block of the group");
 
 __global__ __launch_bounds__(kThreads) void vc_decode_kernel(const ValueCodecArgs a) {
     __shared__ uint16_t s_lut[1u << kVcMaxLen];      // symbol << 4 | length
     __shared__ uint32_t s_cnt[kVcMaxLen + 1][kWaves];
-    __shared__ uint32_t s_words[kVcSlotWords + 1];
-    __shared__ uint8_t s_sym[kVcChunk];
+    __shared__ uint8_t s_sorted[256];                // symbols in (length, symbol) order
+    __shared__ uint32_t s_words[kVcDecodeChunks][kVcSlotWords + 1];
+    // decoded high bytes: value q*4 + c of thread t is byte c of word q * kSymPitch + t (the odd pitch keeps both
+    // the decoders' stores and the write-out's loads off each other's LDS banks)
+    constexpr uint32_t kSymPitch = kThreads + 1;
+    __shared__ uint32_t s_sym[(kVcSub / 4) * kSymPitch];
     const uint32_t groups = (a.nchunk + kVcDecodeChunks - 1) / kVcDecodeChunks;
     const uint32_t b = blockIdx.x / groups, g = blockIdx.x - b * groups;
     const uint64_t cnt = ((uint64_t)a.counts[b] < a.cap) ? a.counts[b] : a.cap;
-    if ((uint64_t)g * kVcDecodeChunks * kVcChunk >= cnt) return;
+    const uint64_t g0 = (uint64_t)g * kVcDecodeChunks * kVcChunk;        // first value of the group
+    if (g0 >= cnt) return;
     const uint32_t s = threadIdx.x;
     const int lane = s & 63, wave = s >> 6;
     uint32_t l = a.lens[(uint64_t)b * 256 + s];
     if (l > kVcMaxLen) l = 0;                        // not a length this format can hold: treated as absent
-    for (uint32_t i = s; i < (1u << kVcMaxLen); i += kThreads) s_lut[i] = 0;
     // canonical code of symbol s = first code of its length + number of smaller symbols of that length
     uint32_t rank = 0;
     for (uint32_t j = 1; j <= kVcMaxLen; ++j) {
@@ -1201,50 +1234,139 @@ __global__ __launch_bounds__(kThreads) void vc_decode_kernel(const ValueCodecArg
         if (l == j) rank = __builtin_popcountll(m & ((1ull << lane) - 1ull));
         if (lane == 0) s_cnt[j][wave] = (uint32_t)__builtin_popcountll(m);
     }
+    // the group's streams: chunk kk of the group is chunk g*8 + kk of the bucket; chunks past the end read as empty
+    const uint32_t gn = (uint32_t)((cnt - g0 < (uint64_t)kVcDecodeChunks * kVcChunk) ? (cnt - g0) : kVcDecodeChunks * kVcChunk);
+    const uint32_t nch = (gn + kVcChunk - 1) / kVcChunk;                  // chunks of this group that hold values
+    const uint64_t slot0 = (uint64_t)b * a.nchunk + (uint64_t)g * kVcDecodeChunks;
+    {   // every load of the group's streams is issued before the first is stored (3 words per thread and chunk)
+        static_assert(kVcSlotWords == 3 * kThreads, "three stream words per thread");
+        uint32_t used[kVcDecodeChunks], tmp[kVcDecodeChunks][3];
+#pragma unroll
+        for (uint32_t kk = 0; kk < kVcDecodeChunks; ++kk) {
+            used[kk] = (kk < nch) ? a.chunk_words[slot0 + kk] : 0u;
+            used[kk] = used[kk] > kVcSlotWords ? kVcSlotWords : used[kk];
+        }
+#pragma unroll
+        for (uint32_t kk = 0; kk < kVcDecodeChunks; ++kk) {
+            const uint32_t *in = a.bits + (slot0 + kk) * kVcSlotWords;
+#pragma unroll
+            for (uint32_t r = 0; r < 3; ++r) tmp[kk][r] = (s + r * kThreads < used[kk]) ? in[s + r * kThreads] : 0u;
+        }
+#pragma unroll
+        for (uint32_t kk = 0; kk < kVcDecodeChunks; ++kk) {
+#pragma unroll
+            for (uint32_t r = 0; r < 3; ++r) s_words[kk][s + r * kThreads] = tmp[kk][r];
+        }
+        if (s < kVcDecodeChunks) s_words[s][kVcSlotWords] = 0u;
+    }
     __syncthreads();
-    if (l) {
-        uint32_t first = 0, code = 0;
+    // Per length j: how many symbols have it, the first code of that length and where its symbols start in the
+    // list of symbols sorted by (length, symbol) -- every thread keeps the three small tables in registers.
+    uint32_t cnt_j[kVcMaxLen + 1], first_j[kVcMaxLen + 1], off_j[kVcMaxLen + 1];
+    {
+        uint32_t code = 0, off = 0;
+#pragma unroll
         for (uint32_t j = 1; j <= kVcMaxLen; ++j) {
             uint32_t cj = 0;
 #pragma unroll
             for (int w = 0; w < kWaves; ++w) { cj += s_cnt[j][w]; if (j == l && w < wave) rank += s_cnt[j][w]; }
-            if (j == l) first = code;
-            code = (code + cj) << 1;
+            cnt_j[j] = cj; first_j[j] = code; off_j[j] = off;
+            code = (code + cj) << 1; off += cj;
         }
-        const uint32_t rc = __brev(first + rank) >> (32 - l);
-        if (rc < (1u << l))                          // a malformed length table cannot write outside the table
-            for (uint32_t hi = 0; hi < (1u << (kVcMaxLen - l)); ++hi) s_lut[rc | (hi << l)] = (uint16_t)((s << 4) | l);
     }
+#pragma unroll
+    for (uint32_t j = 1; j <= kVcMaxLen; ++j)
+        if (l == j) s_sorted[off_j[j] + rank] = (uint8_t)s;            // off + rank < 256: each symbol has one length
+    __syncthreads();
+    // Table entry i: the 12 stream bits i, first bit in bit 0, are a code word's bits most significant first;
+    // the entry's length is the one length j whose first j bits fall inside that length's run of canonical codes.
+    for (uint32_t i = s; i < (1u << kVcMaxLen); i += kThreads) {
+        const uint32_t c12 = __brev(i) >> (32 - kVcMaxLen);
+        uint32_t e = 0;
+#pragma unroll
+        for (uint32_t j = kVcMaxLen; j >= 1; --j) {                    // descending, so that the shortest match is kept
+            const uint32_t d = (c12 >> (kVcMaxLen - j)) - first_j[j];  // wraps to a huge value below the run
+            if (d < cnt_j[j]) e = ((uint32_t)s_sorted[off_j[j] + d] << 4) | j;
+        }
+        s_lut[i] = (uint16_t)e;
+    }
+    __syncthreads();
     bool bad = false;
-    for (uint32_t kk = 0; kk < kVcDecodeChunks; ++kk) {
-        const uint32_t k = g * kVcDecodeChunks + kk;
-        const uint64_t r0 = (uint64_t)k * kVcChunk;
-        if (k >= a.nchunk || r0 >= cnt) break;       // uniform
-        const uint32_t n = (uint32_t)((cnt - r0 < kVcChunk) ? (cnt - r0) : kVcChunk);
-        const uint64_t slot = (uint64_t)b * a.nchunk + k;
-        uint32_t used = a.chunk_words[slot];
-        used = used > kVcSlotWords ? kVcSlotWords : used;
-        const uint32_t *in = a.bits + slot * kVcSlotWords;
-        __syncthreads();                             // table ready / previous chunk's buffers free
-        for (uint32_t i = s; i < kVcSlotWords + 1; i += kThreads) s_words[i] = (i < used) ? in[i] : 0u;
-        __syncthreads();
-        if (s < 32 && s * kVcSub < n) {
-            uint32_t pos = a.sub[slot * 32 + s];
-            const uint32_t i1 = ((s + 1) * kVcSub < n) ? (s + 1) * kVcSub : n;
-            for (uint32_t i = s * kVcSub; i < i1; ++i) {
+    {
+        const uint32_t kk = s >> 5, sb = s & 31u;                         // chunk of the group, sub-block of the chunk
+        const uint32_t v0 = kk * kVcChunk + sb * kVcSub;                  // first value of this thread, inside the group
+        if (v0 < gn) {
+            const uint32_t v1 = (v0 + kVcSub < gn) ? (v0 + kVcSub) : gn;  // a chunk holds a multiple of kVcSub unless it is the last
+            uint32_t pos = a.sub[(slot0 + kk) * 32 + sb];
+            uint32_t pack = 0;
+            for (uint32_t i = v0; i < v1; ++i) {
                 const uint32_t w = pos >> 5, sh = pos & 31;
                 uint32_t x = 0;
-                if (w < kVcSlotWords) x = (uint32_t)((((unsigned long long)s_words[w + 1] << 32) | s_words[w]) >> sh);
+                if (w < kVcSlotWords) x = (uint32_t)((((unsigned long long)s_words[kk][w + 1] << 32) | s_words[kk][w]) >> sh);
                 const uint32_t e = s_lut[x & ((1u << kVcMaxLen) - 1u)];
-                if ((e & 15u) == 0) { bad = true; break; }        // not a code of this table
+                if ((e & 15u) == 0) { bad = true; break; }                // not a code of this table
                 pos += e & 15u;
-                s_sym[i] = (uint8_t)(e >> 4);
+                const uint32_t it = i - v0;
+                pack |= (e >> 4) << (8u * (it & 3u));
+                if ((it & 3u) == 3u || i + 1 == v1) { s_sym[(it >> 2) * kSymPitch + s] = pack; pack = 0; }
             }
         }
-        __syncthreads();
-        const uint8_t *lo = a.low + (uint64_t)b * a.cap + r0;
-        uint16_t *out = a.V_out + (uint64_t)b * a.cap + r0;
-        for (uint32_t i = s; i < n; i += kThreads) out[i] = (uint16_t)(((uint32_t)s_sym[i] << 8) | lo[i]);
+    }
+    __syncthreads();
+    const uint8_t *lo = a.low + (uint64_t)b * a.cap + g0;
+    uint16_t *out = a.V_out + (uint64_t)b * a.cap + g0;
+    if (((((uintptr_t)lo) & 7u) | (((uintptr_t)out) & 15u)) == 0) {
+        // 8 consecutive values per thread and step: one 8-byte load of low bytes, two words of symbols, one
+        // 16-byte store; all of a thread's loads are issued first
+        constexpr uint32_t kSteps = kVcDecodeChunks * kVcChunk / (8 * kThreads);
+        uint2 lw[kSteps];
+#pragma unroll
+        for (uint32_t q = 0; q < kSteps; ++q) {
+            const uint32_t i0 = (q * kThreads + s) * 8u;
+            lw[q] = (i0 + 8u <= gn) ? *reinterpret_cast<const uint2 *>(lo + i0) : make_uint2(0u, 0u);
+        }
+#pragma unroll
+        for (uint32_t q = 0; q < kSteps; ++q) {
+            const uint32_t i0 = (q * kThreads + s) * 8u;
+            if (i0 + 8u <= gn) {
+                const uint32_t t = i0 / kVcSub, w0 = (i0 % kVcSub) >> 2;
+                const uint32_t lwq[2] = {lw[q].x, lw[q].y};
+                uint32_t o[4];
+#pragma unroll
+                for (uint32_t c = 0; c < 2; ++c) {                        // 4 values per word of symbols / of low bytes
+                    const uint32_t sy = s_sym[(w0 + c) * kSymPitch + t], lb = lwq[c];
+                    o[2 * c] = ((sy & 0xFFu) << 8) | (lb & 0xFFu) | ((sy & 0xFF00u) << 16) | ((lb & 0xFF00u) << 8);
+                    o[2 * c + 1] = ((sy >> 8) & 0xFF00u) | ((lb >> 16) & 0xFFu) | (sy & 0xFF000000u) | ((lb >> 8) & 0xFF0000u);
+                }
+                u32x4 a0;
+                a0.x = o[0]; a0.y = o[1]; a0.z = o[2]; a0.w = o[3];
+                *reinterpret_cast<u32x4 *>(out + i0) = a0;
+            } else {
+                for (uint32_t i = i0; i < gn; ++i) {                      // the ragged end of the bucket's payload
+                    const uint32_t t = i / kVcSub, it = i % kVcSub;
+                    out[i] = (uint16_t)((((s_sym[(it >> 2) * kSymPitch + t] >> (8u * (it & 3u))) & 0xFFu) << 8) | lo[i]);
+                }
+            }
+        }
+    } else {
+        // any alignment: 8 loads in flight per thread
+        for (uint32_t base = 0; base < gn; base += 8 * kThreads) {
+            uint32_t lb[8];
+#pragma unroll
+            for (uint32_t u = 0; u < 8; ++u) {
+                const uint32_t i = base + u * kThreads + s;
+                lb[u] = (i < gn) ? (uint32_t)lo[i] : 0u;
+            }
+#pragma unroll
+            for (uint32_t u = 0; u < 8; ++u) {
+                const uint32_t i = base + u * kThreads + s;
+                if (i < gn) {
+                    const uint32_t t = i / kVcSub, it = i % kVcSub;       // decoding thread, its it-th value
+                    const uint32_t sym = (s_sym[(it >> 2) * kSymPitch + t] >> (8u * (it & 3u))) & 0xFFu;
+                    out[i] = (uint16_t)((sym << 8) | lb[u]);
+                }
+            }
+        }
     }
     if (bad) atomicOr(a.flags, kFlagBadIndex);
 }
