@@ -895,7 +895,8 @@ int srs_encode_values(srs_ctx *ctx, const uint16_t *V, const uint32_t *counts, u
     hipLaunchKernelGGL(zero_strided_kernel, dim3((uint32_t)((nh + 255) / 256)), dim3(256), 0, st, a.hist, nh, 1u);
     SRS_HIP(hipGetLastError());
     const dim3 grid((uint32_t)((uint64_t)nbuckets * nchunk));
-    hipLaunchKernelGGL(vc_hist_kernel, grid, dim3(kThreads), 0, st, a);
+    const dim3 hist_grid((uint32_t)((uint64_t)nbuckets * ((nchunk + kVcHistChunks - 1) / kVcHistChunks)));
+    hipLaunchKernelGGL(vc_hist_kernel, hist_grid, dim3(kThreads), 0, st, a);
     SRS_HIP(hipGetLastError());
     hipLaunchKernelGGL(vc_build_kernel, dim3(nbuckets), dim3(kThreads), 0, st, a);
     SRS_HIP(hipGetLastError());

@@ -1035,19 +1035,56 @@ struct ValueCodecArgs {
 };
 
 // per (bucket, chunk): histogram of the high bytes, accumulated per bucket
+constexpr uint32_t kVcHistChunks = 8;        // chunks of one bucket counted by one workgroup
+
 __global__ __launch_bounds__(kThreads) void vc_hist_kernel(const ValueCodecArgs a) {
-    __shared__ uint32_t h[256];
-    const uint32_t b = blockIdx.x / a.nchunk, k = blockIdx.x - b * a.nchunk;
+    // The high bytes of a payload crowd into a handful of bins, and LDS atomics of one wave on one address take
+    // turns: 32 partial histograms, one per 8 lanes, 257 words apart so that the same bin of different partials
+    // lies in different banks.
+    constexpr uint32_t kParts = kThreads / 8, kPitch = 257;
+    __shared__ uint32_t h[kParts * kPitch];
+    const uint32_t groups = (a.nchunk + kVcHistChunks - 1) / kVcHistChunks;
+    const uint32_t b = blockIdx.x / groups, g = blockIdx.x - b * groups;
     const uint64_t cnt = ((uint64_t)a.counts[b] < a.cap) ? a.counts[b] : a.cap;
-    const uint64_t r0 = (uint64_t)k * kVcChunk;
-    if (r0 >= cnt) return;
-    h[threadIdx.x] = 0;
+    const uint64_t g0 = (uint64_t)g * kVcHistChunks * kVcChunk;
+    if (g0 >= cnt) return;
+    const uint32_t s = threadIdx.x;
+    uint32_t *const mine = h + (s >> 3) * kPitch;
+    const uint32_t gn = (uint32_t)((cnt - g0 < (uint64_t)kVcHistChunks * kVcChunk) ? (cnt - g0) : kVcHistChunks * kVcChunk);
+    for (uint32_t i = s; i < kParts * kPitch; i += kThreads) h[i] = 0;
     __syncthreads();
-    const uint32_t n = (uint32_t)((cnt - r0 < kVcChunk) ? (cnt - r0) : kVcChunk);
-    const uint16_t *v = a.V + (uint64_t)b * a.cap + r0;
-    for (uint32_t i = threadIdx.x; i < n; i += kThreads) atomicAdd(&h[v[i] >> 8], 1u);
+    const uint16_t *v = a.V + (uint64_t)b * a.cap + g0;
+    if ((((uintptr_t)v) & 15u) == 0) {
+        constexpr uint32_t kSteps = kVcHistChunks * kVcChunk / (8 * kThreads);   // 8 values per 16-byte load
+        u32x4 x[kSteps];
+        const u32x4 none = {0, 0, 0, 0};
+#pragma unroll
+        for (uint32_t q = 0; q < kSteps; ++q) {
+            const uint32_t i0 = (q * kThreads + s) * 8u;
+            x[q] = (i0 + 8u <= gn) ? *reinterpret_cast<const u32x4 *>(v + i0) : none;
+        }
+#pragma unroll
+        for (uint32_t q = 0; q < kSteps; ++q) {
+            const uint32_t i0 = (q * kThreads + s) * 8u;
+            if (i0 + 8u <= gn) {
+                const uint32_t d[4] = {x[q].x, x[q].y, x[q].z, x[q].w};
+#pragma unroll
+                for (int c = 0; c < 4; ++c) {
+                    atomicAdd(&mine[(d[c] >> 8) & 0xFFu], 1u);
+                    atomicAdd(&mine[d[c] >> 24], 1u);
+                }
+            } else {
+                for (uint32_t i = i0; i < gn; ++i) atomicAdd(&mine[v[i] >> 8], 1u);
+            }
+        }
+    } else {
+        for (uint32_t i = s; i < gn; i += kThreads) atomicAdd(&mine[v[i] >> 8], 1u);
+    }
     __syncthreads();
-    if (h[threadIdx.x]) atomicAdd(a.hist + (uint64_t)b * 256 + threadIdx.x, h[threadIdx.x]);
+    uint32_t t = 0;
+#pragma unroll 8
+    for (uint32_t p = 0; p < kParts; ++p) t += h[p * kPitch + s];
+    if (t) atomicAdd(a.hist + (uint64_t)b * 256 + s, t);
 }
 
 // One workgroup per bucket builds the Huffman lengths exactly as the header specifies (merge the two smallest
@@ -1165,11 +1202,28 @@ __global__ __launch_bounds__(kThreads) void vc_encode_kernel(const ValueCodecArg
     const uint32_t k0 = threadIdx.x * 8;
     unsigned long long buf0 = 0, buf1 = 0;          // 128-bit bit buffer, stream order = ascending bit index
     uint32_t nbits = 0;
+    // the thread's 8 values: one 16-byte load and one 8-byte store of the low bytes where the rows allow it
+    uint32_t xs[8];
+    const bool vec = (k0 + 8 <= n) && (((((uintptr_t)(v + k0)) & 15u) | (((uintptr_t)(lo + k0)) & 7u)) == 0);
+    if (vec) {
+        const u32x4 q = *reinterpret_cast<const u32x4 *>(v + k0);
+        xs[0] = q.x & 0xFFFFu; xs[1] = q.x >> 16; xs[2] = q.y & 0xFFFFu; xs[3] = q.y >> 16;
+        xs[4] = q.z & 0xFFFFu; xs[5] = q.z >> 16; xs[6] = q.w & 0xFFFFu; xs[7] = q.w >> 16;
+        uint2 lb;
+        lb.x = (xs[0] & 0xFFu) | ((xs[1] & 0xFFu) << 8) | ((xs[2] & 0xFFu) << 16) | ((xs[3] & 0xFFu) << 24);
+        lb.y = (xs[4] & 0xFFu) | ((xs[5] & 0xFFu) << 8) | ((xs[6] & 0xFFu) << 16) | ((xs[7] & 0xFFu) << 24);
+        *reinterpret_cast<uint2 *>(lo + k0) = lb;
+    } else {
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            xs[j] = (k0 + j < n) ? (uint32_t)v[k0 + j] : 0u;
+            if (k0 + j < n) lo[k0 + j] = (uint8_t)(xs[j] & 0xFFu);
+        }
+    }
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
         if (k0 + j < n) {
-            const uint32_t x = v[k0 + j];
-            lo[k0 + j] = (uint8_t)(x & 0xFFu);
+            const uint32_t x = xs[j];
             const uint32_t sym = x >> 8, l = s_len[sym];
             const unsigned long long rc = s_rcode[sym];
             if (nbits < 64) { buf0 |= rc << nbits; if (nbits + l > 64) buf1 |= rc >> (64 - nbits); }
