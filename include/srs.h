@@ -59,8 +59,9 @@ typedef enum {
 #define SRS_OPT_SPIN_LIMIT 1   /* max polls of a predecessor tile before SRS_FLAG_TIMEOUT (default 1<<24) */
 #define SRS_OPT_TILE_ELEMS 2   /* elements per extract tile: 4096, 8192, 16384 or 32768 (default; tuning; affects
                                   plans created afterwards) */
-#define SRS_OPT_REFRESH_GROUP 3 /* snapshot refresh granularity in 16-byte lanes: 0 = element-wise 2-byte stores
-                                  (default), 4 = whole aligned 64 bytes around a change, 8 = 128 bytes (tuning) */
+#define SRS_OPT_REFRESH_GROUP 3 /* snapshot refresh: 0 = a 2-byte store per changed element; 4 (default) / 8 = the same,
+                                  except that a quarter of a tile in which at least 1 element in 32 changed is
+                                  refreshed by whole aligned 64- / 128-byte blocks around the changes (tuning) */
 #define SRS_OPT_INTERLEAVE 4   /* buckets whose tiles are interleaved over consecutive workgroups, 1..4096
                                   (default 64; tuning; affects plans created afterwards) */
 #define SRS_OPT_SNAPSHOT 5     /* what srs_extract / srs_extract_multi do with the snapshot:

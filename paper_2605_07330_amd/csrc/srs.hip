@@ -36,7 +36,7 @@ struct srs_ctx {
     uint32_t spin_limit = 1u << 24;
     uint32_t tile_elems = 32768;
     uint32_t group = 64;                    // buckets whose tiles are interleaved over consecutive workgroups
-    uint32_t refresh_group = 0;             // 0: element-wise refresh; 4 / 8: lanes (x16 bytes) rewritten around a change
+    uint32_t refresh_group = 4;             // 0: element-wise refresh; 4 / 8: dense quarters of a tile by blocks of that many 16-byte lanes
     bool rotate_snapshot = false;           // true: extract leaves the snapshot alone, the caller swaps buffers
 };
 

@@ -297,10 +297,12 @@ __device__ __forceinline__ uint32_t look_back(const ExtractArgs &a, uint32_t til
 // ---------------------------------------------------------------------------------------------
 // extract
 // ---------------------------------------------------------------------------------------------
-// RG = lanes per snapshot-refresh group: 0 refreshes element by element (2-byte stores); 4 / 8 rewrite
-// the whole aligned 64 / 128 bytes around a change from the new weights (unchanged elements get the
-// value they already hold), so that the memory system sees full-sector writes instead of masked ones;
-// -1 does not touch the snapshot at all (the caller rotates buffers: `new` is the next call's `old`).
+// RG = lanes per snapshot-refresh group: 0 refreshes element by element (2-byte stores from the write-out
+// loop); 4 / 8 do the same for sparse data, but a wave whose quarter of a full tile has at least one changed
+// element in 32 rewrites the whole aligned 64 / 128 bytes around each change from the new weights (unchanged
+// elements get the value they already hold): at such densities nearly every block holds a change and full
+// blocks are the cheaper writes; -1 does not touch the snapshot at all (the caller rotates buffers: `new` is the
+// next call's `old`).
 // CAST: `new` is not a BF16 buffer but the FP32 master weights; each element is rounded to BF16
 // (nearest even, NaN -> 0x7FC0) on the fly and `old` is the model-parameter buffer itself: the cast-and-
 // copy of Alg. 1 fused with its diff, so that no snapshot exists at all.
@@ -426,16 +428,6 @@ __global__ __launch_bounds__(kThreads) void extract_kernel(const ExtractArgs a) 
 #pragma unroll
     for (int j = 0; j < V; ++j) m[j] = EL::diff_mask(xo[j], xn[j]);
 
-    // ---- snapshot refresh of full tiles, RG lanes (RG*16 bytes) at a time
-    const bool group_refresh = (RG > 0) && aligned && len == TILE;      // uniform
-    if (group_refresh) {
-#pragma unroll
-        for (int j = 0; j < V; ++j) {
-            const unsigned long long changed = __ballot(m[j] != 0);
-            const uint32_t grp = (uint32_t)(changed >> (lane & ~(RG > 0 ? RG - 1 : 0))) & ((1u << (RG > 0 ? RG : 1)) - 1u);
-            if (grp) *reinterpret_cast<u32x4 *>(po + e0 + j * ROW) = xn[j];
-        }
-    }
 #pragma unroll
     for (int q = 0; q < V / 2; ++q) pk[q] = __popc(m[2 * q]) | (__popc(m[2 * q + 1]) << 16);
 
@@ -452,12 +444,26 @@ __global__ __launch_bounds__(kThreads) void extract_kernel(const ExtractArgs a) 
         ex[2 * q + 1] = wave_total + (exc >> 16);
         wave_total += tot >> 16;
     }
-    if (lane == 0) s_wave_total[wave] = wave_total;
+    // ---- snapshot refresh by groups of RG lanes (RG*16 bytes), for the waves of a full tile whose quarter of it is
+    // dense enough (at least one element in kGroupFrom changed): there nearly every group holds a change and whole
+    // blocks are the cheaper way to write; sparser quarters are refreshed element by element in the write-out loop
+    constexpr uint32_t kGroupFrom = 32;
+    const bool group_refresh = (RG > 0) && aligned && len == TILE && wave_total * kGroupFrom >= V * ROW;   // per wave
+    if (group_refresh) {
+#pragma unroll
+        for (int j = 0; j < V; ++j) {
+            const unsigned long long changed = __ballot(m[j] != 0);
+            const uint32_t grp = (uint32_t)(changed >> (lane & ~(RG > 0 ? RG - 1 : 0))) & ((1u << (RG > 0 ? RG : 1)) - 1u);
+            if (grp) *reinterpret_cast<u32x4 *>(po + e0 + j * ROW) = xn[j];
+        }
+    }
+    if (lane == 0) s_wave_total[wave] = wave_total | (group_refresh ? 0x80000000u : 0u);
     __syncthreads();
-    uint32_t wave_base = 0, tile_total = 0;
+    uint32_t wave_base = 0, tile_total = 0, grouped = 0;                 // grouped: bit w = wave w refreshed by groups
 #pragma unroll
     for (int w = 0; w < kWaves; ++w) {
-        const uint32_t t = s_wave_total[w];
+        const uint32_t t = s_wave_total[w] & 0x7FFFFFFFu;
+        grouped |= (s_wave_total[w] >> 31) << w;
         wave_base += (w < wave) ? t : 0u;
         tile_total += t;
     }
@@ -511,7 +517,8 @@ __global__ __launch_bounds__(kThreads) void extract_kernel(const ExtractArgs a) 
             const uint64_t r = (uint64_t)excl + r0 + k;
             if (local < len) {                      // always true for a correct scan; keeps stores in bounds
                 if (r < a.cap) { Ib[r] = (int32_t)(idx_base + local); Vb[r] = val; }
-                if (RG >= 0 && !group_refresh) po[local] = val;   // snapshot refresh: W_prev <- W at changed positions
+                // snapshot refresh: W_prev <- W at changed positions, unless that wave's quarter went by groups
+                if (RG == 0 || (RG > 0 && !((grouped >> (local / (V * ROW))) & 1u))) po[local] = val;
             }
         }
         __syncthreads();
