@@ -47,7 +47,7 @@ struct srs_plan {
     uint32_t max_bucket_tiles = 0;          // most tiles in any one bucket
     TileDesc *d_tiles = nullptr;
     uint64_t *d_tensor_base = nullptr;      // [ntensors] packed position of each tensor's element 0
-    uint32_t *d_wg_bucket = nullptr;        // [ntiles] bucket served by each workgroup of extract
+    WgInfo *d_wg_info = nullptr;            // [ntiles] bucket served by each workgroup of extract, and that bucket's tiles
     uint32_t *d_bucket_first = nullptr;     // [nbuckets+1] first tile of each bucket
     SegDesc *d_segs = nullptr;
     uint32_t *d_seg_begin = nullptr;
@@ -354,7 +354,7 @@ int extract_multi(srs_ctx *ctx, srs_plan *plan, const srs_tensor_pair *t,
     int rc = prepare_extract(ctx, plan->ntiles, plan->nbuckets, st, &a.ticket_stride);
     if (rc != SRS_OK) return rc;
     a.tiles = plan->d_tiles; a.ptrs = plan->d_pairs; a.ntiles = plan->ntiles;
-    a.wg_bucket = plan->d_wg_bucket; a.bucket_first = plan->d_bucket_first; a.nb = plan->nbuckets;
+    a.wg_info = plan->d_wg_info; a.bucket_first = plan->d_bucket_first; a.nb = plan->nbuckets;
     a.I = I; a.V = (uint16_t *)V; a.counts = counts; a.cap = cap;
     a.status = ctx->status; a.tickets = ctx->tickets; a.flags = ctx->flags;
     a.spin_limit = ctx->spin_limit;
@@ -550,7 +550,19 @@ int srs_plan_create(srs_ctx *ctx, const uint64_t *numel, uint32_t ntensors, uint
     ok = ok && upload((void **)&p->d_segs, segs.empty() ? nullptr : segs.data(), segs.size() * sizeof(SegDesc));
     ok = ok && upload((void **)&p->d_seg_begin, seg_begin.data(), seg_begin.size() * sizeof(uint32_t));
     ok = ok && upload((void **)&p->d_bucket_first, bucket_first.data(), bucket_first.size() * sizeof(uint32_t));
-    ok = ok && upload((void **)&p->d_wg_bucket, wg_bucket.empty() ? nullptr : wg_bucket.data(), wg_bucket.size() * sizeof(uint32_t));
+    // what extract's workgroup i needs before it can take its ticket, in one 16-byte load: the bucket it serves,
+    // that bucket's first tile and its number of tiles
+    std::vector<WgInfo> wg_info;
+    try {
+        wg_info.resize(wg_bucket.size());
+    } catch (const std::bad_alloc &) {
+        srs_plan_destroy(p); return SRS_ERR_NOMEM;
+    }
+    for (size_t i = 0; i < wg_bucket.size(); ++i) {
+        const uint32_t b = wg_bucket[i];
+        wg_info[i] = WgInfo{b, bucket_first[b], bucket_first[b + 1] - bucket_first[b], 0u};
+    }
+    ok = ok && upload((void **)&p->d_wg_info, wg_info.empty() ? nullptr : wg_info.data(), wg_info.size() * sizeof(WgInfo));
     std::vector<uint64_t> tensor_base((size_t)ntensors + 1, 0);
     for (uint32_t k = 0; k < ntensors; ++k) tensor_base[k + 1] = tensor_base[k] + numel[k];
     ok = ok && upload((void **)&p->d_tensor_base, tensor_base.data(), tensor_base.size() * sizeof(uint64_t));
@@ -599,7 +611,7 @@ int srs_plan_destroy(srs_plan *p) {
     if (p->d_segs) (void)hipFree(p->d_segs);
     if (p->d_seg_begin) (void)hipFree(p->d_seg_begin);
     if (p->d_bucket_first) (void)hipFree(p->d_bucket_first);
-    if (p->d_wg_bucket) (void)hipFree(p->d_wg_bucket);
+    if (p->d_wg_info) (void)hipFree(p->d_wg_info);
     if (p->d_tensor_base) (void)hipFree(p->d_tensor_base);
     if (p->d_pairs) (void)hipFree(p->d_pairs);
     if (p->d_wptrs) (void)hipFree(p->d_wptrs);

@@ -49,6 +49,13 @@ struct TileDesc {          // one extract tile of a tensor list (16 bytes)
     uint32_t len;          // 1 .. TILE
 };
 
+struct WgInfo {            // what one extract workgroup serves (16 bytes)
+    uint32_t bucket;       // the bucket whose next tile it claims
+    uint32_t first_tile;   // id of that bucket's first tile
+    uint32_t ntiles;       // number of tiles of that bucket
+    uint32_t pad;
+};
+
 struct SegDesc {           // a run of one tensor inside one bucket (16 bytes)
     uint32_t bucket_off;
     uint32_t len;
@@ -64,7 +71,7 @@ struct ExtractArgs {
     uint32_t nb; uint32_t last_tiles; uint32_t group;      // group = buckets interleaved per group
     // tensor list
     const TileDesc *tiles; const PtrPair *ptrs;
-    const uint32_t *wg_bucket;      // [ntiles] bucket served by each workgroup
+    const WgInfo *wg_info;          // [ntiles] bucket served by each workgroup
     const uint32_t *bucket_first;   // [nb+1] id of each bucket's first tile
     uint32_t ntiles;
     int32_t *I; uint16_t *V; uint32_t *counts; uint64_t cap;
@@ -333,9 +340,8 @@ __global__ __launch_bounds__(kThreads) void extract_kernel(const ExtractArgs a) 
     // ---- which bucket this workgroup serves, then claim that bucket's next tile
     uint32_t bucket, first_tile, bucket_tiles;
     if (MULTI) {
-        bucket = a.wg_bucket[blockIdx.x];
-        first_tile = a.bucket_first[bucket];
-        bucket_tiles = a.bucket_first[bucket + 1] - first_tile;
+        const WgInfo wi = a.wg_info[blockIdx.x];
+        bucket = wi.bucket; first_tile = wi.first_tile; bucket_tiles = wi.ntiles;
     } else {
         // groups of `group` buckets; inside a group consecutive workgroups rotate over its buckets.
         // Only the very last bucket may have fewer tiles: in its group the first last_tiles rounds
@@ -561,9 +567,8 @@ __global__ __launch_bounds__(kThreads) void extract_marked_kernel(const ExtractA
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
 
     // ---- bucket, ticket, tile: as in extract_kernel (tensor lists only)
-    const uint32_t bucket = a.wg_bucket[blockIdx.x];
-    const uint32_t first_tile = a.bucket_first[bucket];
-    const uint32_t bucket_tiles = a.bucket_first[bucket + 1] - first_tile;
+    const WgInfo wi = a.wg_info[blockIdx.x];
+    const uint32_t bucket = wi.bucket, first_tile = wi.first_tile, bucket_tiles = wi.ntiles;
     if (tid == 0)
         s_ticket = __hip_atomic_fetch_add(a.tickets + (uint64_t)bucket * a.ticket_stride, 1u, __ATOMIC_RELAXED,
                                           __HIP_MEMORY_SCOPE_AGENT);
