@@ -319,7 +319,10 @@ constexpr int kSrcBf16 = 0, kSrcFp32 = 1, kSrcBitmap = 2;
 
 template <int V, bool MULTI, int RG, int SRC = kSrcBf16, int EB = 2>
 __global__ __launch_bounds__(kThreads) void extract_kernel(const ExtractArgs a) {
-    constexpr bool NT = false;
+    // A snapshot that is not written is read exactly once, like the new weights: both streams then carry the
+    // non-temporal hint (measured 4 % faster; with the in-place refresh the hint on either stream measures slower,
+    // on the snapshot by 5 ms: the refresh stores must find their line still cached).
+    constexpr bool NT = (RG < 0);
     constexpr bool CAST = (SRC == kSrcFp32);
     static_assert(SRC == kSrcBf16 || SRC == kSrcFp32, "the bitmap source has its own kernel");
     static_assert(V % 2 == 0, "counts are scanned in packed pairs");
@@ -692,9 +695,11 @@ __global__ __launch_bounds__(kThreads) void mark_kernel(const ExtractArgs a) {
     for (int j = 0; j < V; ++j) {
         const uint32_t e = e0 + j * 512;
         if (full || (aligned && e + 8 <= len)) {
-            xo[j] = load16<false>(po + e);
+            // two versions that are only compared are read once each: non-temporal (2 % faster); with CAST the
+            // parameters are rewritten below and stay on ordinary loads, like extract's snapshot
+            xo[j] = CAST ? load16<false>(po + e) : load16<true>(po + e);
             if (CAST) xn[j] = round8_bf16(*reinterpret_cast<const u32x4 *>(pf + e), *reinterpret_cast<const u32x4 *>(pf + e + 4));
-            else xn[j] = load16<false>(pn + e);
+            else xn[j] = load16<true>(pn + e);
         } else {
             xo[j] = load8_guarded(po, e, len);
             xn[j] = CAST ? load8_guarded_cast(pf, e, len) : load8_guarded(pn, e, len);
