@@ -749,10 +749,20 @@ struct ApplyShared {
 };
 
 // Common front of the apply kernels: which (bucket, chunk) this workgroup owns and how many of the
-// chunk's pairs are valid; 0 when there is nothing to do.
+// chunk's pairs are valid; 0 when there is nothing to do.  Consecutive workgroups take the same chunk number of
+// consecutive buckets (groups of kApplyInterleave buckets), so that the scatter of the moment is spread over the
+// whole weight set instead of a dozen buckets: 12 % faster on the 910-bucket benchmark set at 1 %, 9 % at 5 %,
+// nothing lost on the 244-bucket sets, 0.16 ms lost on the skewed set.
+constexpr uint32_t kApplyInterleave = 1024;
+
 __device__ __forceinline__ uint32_t apply_chunk(const ApplyArgs &a, uint32_t &b, uint64_t &start) {
-    b = blockIdx.x / a.chunks_per_bucket;
-    const uint32_t c = blockIdx.x - b * a.chunks_per_bucket;
+    const uint32_t per_group = kApplyInterleave * a.chunks_per_bucket;
+    const uint32_t g = blockIdx.x / per_group, j = blockIdx.x - g * per_group;
+    const uint32_t g0 = g * kApplyInterleave;
+    if (g0 >= a.nb) return 0;
+    const uint32_t gb = (a.nb - g0 < kApplyInterleave) ? (a.nb - g0) : kApplyInterleave;   // buckets in this group
+    const uint32_t c = j / gb;
+    b = g0 + (j - c * gb);
     if (b >= a.nb) return 0;
     const uint32_t cnt_true = a.counts[b];
     const uint64_t cnt = ((uint64_t)cnt_true < a.cap) ? cnt_true : a.cap;
@@ -761,7 +771,8 @@ __device__ __forceinline__ uint32_t apply_chunk(const ApplyArgs &a, uint32_t &b,
     return (uint32_t)((cnt - start < kApplyChunk) ? (cnt - start) : kApplyChunk);
 }
 
-// Scatter of one thread's kApplyPer pairs of bucket b; pair j is live when bit j of `live` is set.
+// Scatter of one thread's kApplyPer pairs of bucket b; pair j is live when bit j of `live` is set.  The stores carry
+// the non-temporal hint: each lands in a line nothing else will touch soon, and measures 10 % faster that way.
 // idx holds tensor-flat indices (single tensor) or positions inside the bucket (lists).  For lists the
 // bucket's segment table is cached in LDS (start inside the bucket -> byte address of that element).
 template <bool MULTI, int EB = 2>
@@ -803,7 +814,7 @@ __device__ __forceinline__ void scatter_pairs(const ApplyArgs &a, ApplyShared &s
                     }
                     hint = lo;
                 }
-                *reinterpret_cast<T *>((uintptr_t)(sh.base[lo] + (unsigned long long)EB * i)) = (T)val[j];
+                __builtin_nontemporal_store((T)val[j], reinterpret_cast<T *>((uintptr_t)(sh.base[lo] + (unsigned long long)EB * i)));
             } else {
                 uint32_t lo = s_lo, hi = s_hi;                  // segs[lo].bucket_off <= i < segs[hi].bucket_off
                 while (hi - lo > 1) {
@@ -813,7 +824,7 @@ __device__ __forceinline__ void scatter_pairs(const ApplyArgs &a, ApplyShared &s
                 const SegDesc d = a.segs[lo];
                 const uint32_t off = i - d.bucket_off;
                 if (off >= d.len) { bad = true; continue; }     // cannot happen for a well-formed plan
-                reinterpret_cast<T *>(a.wptrs[d.tensor])[(uint64_t)d.tensor_off + off] = (T)val[j];
+                __builtin_nontemporal_store((T)val[j], reinterpret_cast<T *>(a.wptrs[d.tensor]) + ((uint64_t)d.tensor_off + off));
             }
         }
     } else {
@@ -824,7 +835,7 @@ __device__ __forceinline__ void scatter_pairs(const ApplyArgs &a, ApplyShared &s
             if (!((live >> j) & 1u)) continue;
             const int64_t i = idx[j];
             if (i < (int64_t)lo || i >= (int64_t)hi) { bad = true; continue; }
-            reinterpret_cast<T *>(a.w)[i] = (T)val[j];
+            __builtin_nontemporal_store((T)val[j], reinterpret_cast<T *>(a.w) + i);
         }
     }
     if (bad) atomicOr(a.flags, kFlagBadIndex);
