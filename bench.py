@@ -31,7 +31,7 @@ HBM_PEAK_GBS = 8000.0
 # HBM traffic per extract launch measured with rocprofv3 --pmc (FETCH_SIZE x 2.00 + WRITE_SIZE x 1.00, the
 # factors from a 61.06 GB copy in the same runs): profiles/extract_apply_qwen3-30b-a3b.md.  Only the workload
 # that was profiled has a figure.
-MEASURED_TRAFFIC_BYTES = {"qwen3-30b-a3b": 133.3e9}
+MEASURED_TRAFFIC_BYTES = {"qwen3-30b-a3b": 133.4e9}
 
 
 def log(msg: str) -> None:
