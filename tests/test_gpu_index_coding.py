@@ -49,6 +49,7 @@ def check_encoded(got, want, counts, nchunk):
     (300000, 100000, 100000, "iid1"), (300000, 100000, 100000, "iid30"), (300000, 100000, 100000, "dense"),
     (300000, 100000, 100000, "empty"), (300000, 100000, 100000, "wide"), (300000, 100000, 100000, "edge"),
     (70001, 7000, 7000, "iid1"), (1 << 20, 1 << 18, 5000, "iid1"), (5000, 5000, 4999, "iid30"),
+    (1500 * 3000 + 11, 3000, 3000, "iid30"),            # 1501 buckets: two groups of the bucket interleave
 ])
 def test_single_tensor_encode_and_encoded_apply(srs, ctx, n, be, cap, kind):
     print(f"case n={n} be={be} cap={cap} kind={kind}", flush=True)

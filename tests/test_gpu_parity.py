@@ -76,6 +76,8 @@ SINGLE_CASES = [
     (100003, 20000, 1.0, "iid"), (300000, 65536, 0.01, "edges"), (300000, 100000, 0.01, "runs"),
     (1 << 20, 1 << 18, 0.01, "iid"), ((1 << 20) + 5, (1 << 18) + 3, 0.01, "iid"),
     (1 << 20, 1 << 20, 0.3, "iid"), (70001, 1000, 0.02, "iid"),
+    # more than 1024 buckets: apply's bucket-interleaved order has a full group and a ragged one; 3 chunks per bucket
+    (3000017, 1000, 0.02, "iid"), (2500 * 5000 + 7, 5000, 1.0, "iid"),
 ]
 
 
@@ -223,6 +225,7 @@ def test_tensor_lists_tiny_model_shapes(srs, cfg, tile, slab, misalign):
 @pytest.mark.parametrize("numel,be", [
     ([5, 1, 1, 20, 3], 7), ([5, 1, 1, 20, 3], 1), ([5, 1, 1, 20, 3], 31), ([100, 0, 50, 0, 0, 25], 64),
     ([4096] * 5 + [1] + [70000], 8192), ([1], 1), ([3, 3, 3], 3), ([40000, 7, 40000, 9, 16385], 16384),
+    ([700001, 3, 1200000, 50, 999999], 1300),          # 2231 buckets: three groups of apply's bucket interleave
 ])
 def test_tensor_lists_odd_shapes(srs, ctx, numel, be):
     print(f"case numel={numel} be={be}", flush=True)
