@@ -97,6 +97,8 @@ def _load():
                                                     C.c_int]
         lib.srs_oracle_apply_multi_u8.restype = C.c_int
         lib.srs_oracle_apply_multi_u8.argtypes = [pp8, u64p, C.c_uint32, C.c_uint64, i32p, u8p, u32p, C.c_uint64]
+        lib.srs_oracle_tensor_indices.restype = C.c_int
+        lib.srs_oracle_tensor_indices.argtypes = [i32p, u32p, u64p, C.c_uint32, C.c_uint64, C.c_uint64, u32p, i32p]
         lib.srs_oracle_num_buckets.restype = C.c_uint64
         lib.srs_oracle_num_buckets.argtypes = [u64p, C.c_uint32, C.c_uint64]
         _lib = lib
@@ -530,3 +532,20 @@ def apply_multi_u8(w: Sequence[np.ndarray], numel: Sequence[int], be: int, I: np
     if rc == BAD_ARG:
         raise ValueError("srs_oracle_apply_multi_u8: bad argument")
     return rc
+
+
+def tensor_indices(I: np.ndarray, counts: np.ndarray, numel: Sequence[int], be: int) -> Tuple[np.ndarray, np.ndarray, int]:
+    """Per-tensor view of a list payload (Alg. 2's int32 index into each tensor): returns (tensor_id[nb, cap] uint32,
+    tensor_idx[nb, cap] int32, rc); unused slots hold 0xFFFFFFFF / -1 (this wrapper's fill values)."""
+    lib = _load()
+    I = np.ascontiguousarray(I, np.int32)
+    counts = np.ascontiguousarray(counts, np.uint32)
+    ne = np.asarray(list(numel), np.uint64)
+    nb, cap = I.shape
+    tid = np.full((nb, cap), 0xFFFFFFFF, np.uint32)
+    tix = np.full((nb, cap), -1, np.int32)
+    rc = lib.srs_oracle_tensor_indices(_p(I, C.c_int32), _p(counts, C.c_uint32), _p(ne, C.c_uint64), len(numel), be, cap,
+                                       _p(tid, C.c_uint32), _p(tix, C.c_int32))
+    if rc == BAD_ARG:
+        raise ValueError("srs_oracle_tensor_indices: bad argument")
+    return tid, tix, rc

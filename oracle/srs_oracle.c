@@ -48,6 +48,8 @@
  * the cumulative index set of Alg. 1 (brute-force unions), value entropy coding
  * (prefix-free, optimal cost, entropy bound, the construction rule restated
  * independently, alpha against the paper's printed range).
+ * Per-tensor view of a list payload: pinned to numpy's flatnonzero taken tensor by
+ * tensor (the paper's own index), tests/test_oracle_pins.py.
  * One-byte elements (FP8 synchronisation): the same pins as the 16-bit
  * functions (tests/test_oracle_u8.py), plus agreement with the 16-bit functions
  * on byte patterns widened to 16 bits.
@@ -302,6 +304,41 @@ int srs_oracle_apply_multi_u8(uint8_t *const *w, const uint64_t *numel, uint32_t
             uint32_t k = 0;
             while (g >= numel[k]) { g -= numel[k]; k += 1; }
             w[k][g] = V[b * cap + r];
+        }
+    }
+    return rc;
+}
+
+/* The per-tensor view of a tensor-list payload.  Alg. 2 sends, for every parameter tensor, (name, I, V) with I
+ * the int32 indices into that tensor's flattened elements; the list calls above store positions inside the bucket
+ * instead (a packed position of a 30 B-element model does not fit int32).  The two are the same information: pair r
+ * of bucket b sits at packed position g = b*be + I[b*cap + r], which lies in exactly one tensor k at flat index
+ * g - (numel[0] + ... + numel[k-1]).  Outputs, laid out like I: tensor_id[b*cap + r] = k, tensor_idx[b*cap + r] =
+ * that flat index, for r < min(counts[b], cap); other slots are left alone.  A position outside the bucket's span
+ * is an error (SRS_ORACLE_BAD_INDEX, slot left alone). */
+int srs_oracle_tensor_indices(const int32_t *I, const uint32_t *counts, const uint64_t *numel, uint32_t ntensors,
+                              uint64_t be, uint64_t cap, uint32_t *tensor_id, int32_t *tensor_idx)
+{
+    if (be == 0 || cap == 0 || be > 0x7fffffffULL) return SRS_ORACLE_BAD_ARG;
+    uint64_t total = 0;
+    for (uint32_t k = 0; k < ntensors; ++k) {
+        if (numel[k] > 0x7fffffffULL) return SRS_ORACLE_BAD_ARG;
+        total += numel[k];
+    }
+    uint64_t nb = (total + be - 1) / be;
+    int rc = SRS_ORACLE_OK;
+    for (uint64_t b = 0; b < nb; ++b) {
+        uint64_t lo = b * be;
+        uint64_t span = lo + be < total ? be : total - lo;
+        uint64_t c = counts[b] < cap ? counts[b] : cap;
+        for (uint64_t r = 0; r < c; ++r) {
+            int64_t local = I[b * cap + r];
+            if (local < 0 || (uint64_t)local >= span) { rc = SRS_ORACLE_BAD_INDEX; continue; }
+            uint64_t g = lo + (uint64_t)local;
+            uint32_t k = 0;
+            while (g >= numel[k]) { g -= numel[k]; k += 1; }
+            tensor_id[b * cap + r] = k;
+            tensor_idx[b * cap + r] = (int32_t)g;
         }
     }
     return rc;

@@ -356,3 +356,33 @@ def test_bad_arguments():
         oracle.extract(a.copy(), a, 1 << 31)
     I, V, c, _ = oracle.extract(np.zeros(0, np.uint16), np.zeros(0, np.uint16), 8)
     assert c.size == 0
+
+
+# ---------------------------------------------------------------------------------------------
+# the per-tensor view of a list payload is the paper's own index: flatnonzero taken tensor by tensor (Alg. 2)
+# ---------------------------------------------------------------------------------------------
+
+@pytest.mark.parametrize("numel,be", [([5, 1, 1, 20, 3], 7), ([100, 0, 50, 0, 0, 25], 64), ([4096] * 3 + [1, 70000], 8192),
+                                      ([40000, 7, 40000, 9, 16385], 16384), ([3, 3, 3], 1)])
+def test_per_tensor_view_is_flatnonzero_per_tensor(numel, be):
+    rng = np.random.default_rng(sum(numel) * 31 + be)
+    olds = [rnd_u16(rng, m) for m in numel]
+    news = [flip(o, np.flatnonzero(rng.random(o.size) < 0.2), rng) if o.size else o.copy() for o in olds]
+    I, V, counts, _ = oracle.extract_multi([o.copy() for o in olds], news, numel, be)
+    tid, tix, rc = oracle.tensor_indices(I, counts, numel, be)
+    assert rc == oracle.OK
+    # gather the view in payload order (bucket by bucket), then split by tensor: order inside a tensor is preserved
+    ids = np.concatenate([tid[b, :counts[b]] for b in range(counts.size)]) if counts.size else np.zeros(0, np.uint32)
+    idx = np.concatenate([tix[b, :counts[b]] for b in range(counts.size)]) if counts.size else np.zeros(0, np.int32)
+    val = np.concatenate([V[b, :counts[b]] for b in range(counts.size)]) if counts.size else np.zeros(0, np.uint16)
+    assert np.all(ids[1:] >= ids[:-1])                                    # tensors appear in list order
+    for k, (o, w) in enumerate(zip(olds, news)):
+        want = np.flatnonzero(o != w)
+        assert np.array_equal(idx[ids == k], want), f"tensor {k}"
+        assert np.array_equal(val[ids == k], w[want]), f"tensor {k}"
+    # untouched slots keep the wrapper's fill; a position outside its bucket is reported
+    for b in range(counts.size):
+        assert (tid[b, counts[b]:] == 0xFFFFFFFF).all() and (tix[b, counts[b]:] == -1).all()
+    if counts.size and counts[-1]:
+        bad = I.copy(); bad[-1, 0] = be
+        assert oracle.tensor_indices(bad, counts, numel, be)[2] == oracle.BAD_INDEX
