@@ -142,6 +142,17 @@ int srs_apply_multi(srs_ctx *ctx, srs_plan *plan, const srs_tensor *t,
                     const int32_t *I, const uint16_t *V, const uint32_t *counts, uint64_t cap, void *stream);
 
 /*
+ * Per-tensor view of a list payload.  Alg. 2's message is, per parameter tensor, (name, I, V) with I the int32
+ * indices into that tensor's flattened elements; the list calls store positions inside the bucket.  This call
+ * gives the former from the latter: for r < min(counts[b], cap), tensor_id[b*cap + r] = the list position k of
+ * the tensor that holds the pair and tensor_idx[b*cap + r] = its flat index inside tensor k (device arrays laid
+ * out like I; other slots are left alone).  Within a bucket the pairs of one tensor are contiguous and ascending,
+ * tensors in list order.  A position outside its bucket raises SRS_FLAG_BAD_INDEX and its slot is left alone.
+ */
+int srs_tensor_indices(srs_ctx *ctx, srs_plan *plan, const int32_t *I, const uint32_t *counts, uint64_t cap,
+                       uint32_t *tensor_id, int32_t *tensor_idx, void *stream);
+
+/*
  * One-byte elements.  The changed-element density is measured at BF16, FP16 and FP8 synchronisation precision
  * (Sec. 2.1); Alg. 1-3 compare and move opaque patterns and do not depend on their width.  FP16 weights go
  * through the 16-bit calls above unchanged.  These four calls are the same operations on 8-bit patterns (FP8 in

@@ -665,6 +665,28 @@ int srs_apply_multi(srs_ctx *ctx, srs_plan *plan, const srs_tensor *t,
     return apply_multi(ctx, plan, t, I, V, counts, cap, stream, 2);
 }
 
+int srs_tensor_indices(srs_ctx *ctx, srs_plan *plan, const int32_t *I, const uint32_t *counts, uint64_t cap,
+                       uint32_t *tensor_id, int32_t *tensor_idx, void *stream) {
+    if (!ctx || !plan || cap == 0 || plan->device != ctx->device) return SRS_ERR_INVALID;
+    if (plan->total == 0) return SRS_OK;
+    if (!I || !counts || !tensor_id || !tensor_idx) return SRS_ERR_INVALID;
+    if (((uintptr_t)I | (uintptr_t)counts | (uintptr_t)tensor_id | (uintptr_t)tensor_idx) & 3u) return SRS_ERR_INVALID;
+    hipStream_t st = (hipStream_t)stream;
+    SRS_HIP(hipSetDevice(ctx->device));
+    const uint64_t slots = cap < plan->be ? cap : plan->be;
+    const uint64_t cpb = (slots + kApplyChunk - 1) / kApplyChunk;
+    if ((uint64_t)plan->nbuckets * cpb > 0x7fffffffull) return SRS_ERR_INVALID;
+    ApplyArgs a;
+    std::memset(&a, 0, sizeof(a));
+    a.segs = plan->d_segs; a.seg_begin = plan->d_seg_begin; a.total = plan->total;
+    a.be = (uint32_t)plan->be; a.nb = plan->nbuckets; a.chunks_per_bucket = (uint32_t)cpb;
+    a.I = I; a.counts = counts; a.cap = cap; a.flags = ctx->flags;
+    hipLaunchKernelGGL(tensor_view_kernel, dim3((uint32_t)((uint64_t)plan->nbuckets * cpb)), dim3(kThreads), 0, st, a,
+                       tensor_id, tensor_idx);
+    SRS_HIP(hipGetLastError());
+    return SRS_OK;
+}
+
 int srs_extract_multi_u8(srs_ctx *ctx, srs_plan *plan, const srs_tensor_pair *t,
                          int32_t *I, uint8_t *V, uint32_t *counts, uint64_t cap, void *stream) {
     return extract_multi(ctx, plan, t, I, V, counts, cap, stream, kSrcBf16, nullptr, 1);

@@ -867,6 +867,36 @@ __global__ __launch_bounds__(kThreads) void apply_kernel(const ApplyArgs a) {
     scatter_pairs<MULTI, EB>(a, sh, b, idx, val, live);
 }
 
+// The per-tensor view of a list payload: Alg. 2's message carries, per parameter tensor, int32 indices into that
+// tensor's flattened elements; pair r of bucket b is at packed position b*be + I, inside exactly one segment of the
+// bucket.  tensor_id / tensor_idx are laid out like I.  Same workgroup-to-chunk mapping and segment search as apply.
+__global__ __launch_bounds__(kThreads) void tensor_view_kernel(const ApplyArgs a, uint32_t *tensor_id, int32_t *tensor_idx) {
+    uint32_t b; uint64_t start;
+    const uint32_t nvalid = apply_chunk(a, b, start);
+    if (nvalid == 0) return;
+    const uint64_t b0 = (uint64_t)b * a.be;
+    const uint32_t blen = (uint32_t)((a.total - b0 < a.be) ? (a.total - b0) : a.be);
+    const uint32_t s_lo = a.seg_begin[b], s_hi = a.seg_begin[b + 1];
+    const uint64_t row = (uint64_t)b * a.cap + start;
+    bool bad = false;
+    for (uint32_t k = threadIdx.x; k < nvalid; k += kThreads) {
+        const int32_t iv = a.I[row + k];
+        if (iv < 0 || (uint32_t)iv >= blen) { bad = true; continue; }
+        const uint32_t i = (uint32_t)iv;
+        uint32_t lo = s_lo, hi = s_hi;                  // segs[lo].bucket_off <= i < segs[hi].bucket_off
+        while (hi - lo > 1) {
+            const uint32_t mid = (lo + hi) >> 1;
+            if (a.segs[mid].bucket_off <= i) lo = mid; else hi = mid;
+        }
+        const SegDesc d = a.segs[lo];
+        const uint32_t off = i - d.bucket_off;
+        if (off >= d.len) { bad = true; continue; }     // cannot happen for a well-formed plan
+        tensor_id[row + k] = d.tensor;
+        tensor_idx[row + k] = (int32_t)(d.tensor_off + off);
+    }
+    if (bad) atomicOr(a.flags, kFlagBadIndex);
+}
+
 // 16-bit first differences (Sec. 3.3, index delta coding) decoded on the fly: thread t owns the
 // kApplyPer consecutive pairs t*8 .. t*8+7 of the chunk, sums its differences, the workgroup scans the
 // 256 thread sums (DPP wave scan + LDS), and the chunk's anchor (the position of its first pair) turns

@@ -38,7 +38,7 @@ EXPORTS = [
     "srs_extract_cast", "srs_extract_cast_multi", "srs_plan_layout",
     "srs_bitmap_words", "srs_mark_multi", "srs_cast_mark_multi", "srs_extract_marked_multi",
     "srs_value_chunks", "srs_encode_values", "srs_decode_values",
-    "srs_extract_u8", "srs_apply_u8", "srs_extract_multi_u8", "srs_apply_multi_u8",
+    "srs_extract_u8", "srs_apply_u8", "srs_extract_multi_u8", "srs_apply_multi_u8", "srs_tensor_indices",
 ]
 
 
@@ -69,6 +69,7 @@ _lib.srs_extract_u8.argtypes = _lib.srs_extract.argtypes
 _lib.srs_apply_u8.argtypes = _lib.srs_apply.argtypes
 _lib.srs_extract_multi_u8.argtypes = _lib.srs_extract_multi.argtypes
 _lib.srs_apply_multi_u8.argtypes = _lib.srs_apply_multi.argtypes
+_lib.srs_tensor_indices.argtypes = [_vp, _vp, _vp, _vp, _u64, _vp, _vp, _vp]
 _lib.srs_stream_probe.argtypes = [_vp, _vp, _vp, _u64, _vp, _vp]
 _lib.srs_stream_probe_sink_words.argtypes = [_u64]
 _lib.srs_stream_probe_sink_words.restype = _u64
@@ -295,6 +296,17 @@ class Context:
             _payload_ok(I, V, counts, plan.nbuckets, cap)
         _check(_lib.srs_apply_multi(self._h, plan._h, tensors, I.data_ptr(), V.data_ptr(), counts.data_ptr(), cap,
                                     _stream_ptr(stream)), "srs_apply_multi")
+
+    def tensor_indices(self, plan: Plan, I: torch.Tensor, counts: torch.Tensor, cap: int, tensor_id: torch.Tensor,
+                       tensor_idx: torch.Tensor, stream: Optional[torch.cuda.Stream] = None) -> None:
+        """Per-tensor view of a list payload: (tensor_id, tensor_idx) laid out like I (32-bit GPU tensors)."""
+        for t, what in ((I, "I"), (tensor_id, "tensor_id"), (tensor_idx, "tensor_idx")):
+            if not (t.is_cuda and t.element_size() == 4 and t.is_contiguous() and t.numel() >= plan.nbuckets * cap):
+                raise TypeError(f"{what}: expected contiguous 32-bit GPU tensor of at least nb*cap elements")
+        if not (counts.is_cuda and counts.element_size() == 4 and counts.numel() >= plan.nbuckets):
+            raise TypeError("counts: expected 32-bit GPU tensor of at least nb elements")
+        _check(_lib.srs_tensor_indices(self._h, plan._h, I.data_ptr(), counts.data_ptr(), cap, tensor_id.data_ptr(),
+                                       tensor_idx.data_ptr(), _stream_ptr(stream)), "srs_tensor_indices")
 
     # ---- one-byte elements (FP8 synchronisation precision) ----------------------------------
     def extract_u8(self, old: torch.Tensor, new: torch.Tensor, bucket_elems: int, I: torch.Tensor, V: torch.Tensor,
