@@ -31,7 +31,13 @@
  *     returned.  Device-side conditions (overflow, bad index, look-back time-out) are reported
  *     through srs_status().
  *   - A context serialises its own scratch memory: use one context per stream, and do not run
- *     two calls on the same context concurrently.
+ *     two calls on the same context concurrently.  A plan caches the device copy of the last pointer
+ *     arrays it was called with (one for extract-side pairs, one for apply-side weights) and is
+ *     updated by the calls that take it: one host thread at a time per plan, and calls that pass
+ *     DIFFERENT pointer arrays to one plan must be ordered on one stream (the array of a later call
+ *     replaces the earlier one in stream order).  Callers that alternate between pointer sets keep
+ *     one plan per set.
+ *   - Weights of a call may not overlap each other or the payload buffers.
  */
 #ifndef SRS_H
 #define SRS_H
