@@ -82,7 +82,10 @@ def cpu_baseline_and_check(torch, np, oracle, wl, old_ws, new_ws, payload, bucke
             c = int(oc[j])
             if not (np.array_equal(gI[j, :c], oI[j, :c]) and np.array_equal(gV[j, :c], oV[j, :c])):
                 raise SystemExit(f"bench self-check failed: payload differs in bucket {b_lo + j}")
-        log(f"oracle sample buckets [{b_lo},{b_hi}): extract {t1 - t0:.2f}s apply {t2 - t1:.2f}s, GPU payload matches")
+        done = starts.index(b_lo) + 1
+        if done % 6 == 0 or done == len(starts):         # a progress line every couple of seconds
+            log(f"oracle: {done} of {len(starts)} groups of {buckets_per_group} buckets done (last [{b_lo},{b_hi})): "
+                f"extract {t_extract:.2f}s apply {t_apply:.2f}s so far, GPU payload matches")
     return t_extract, t_apply, elems, len(starts) * buckets_per_group
 
 
