@@ -184,6 +184,8 @@ def bench_fp8(args, torch, srs, synth, wl, dev) -> int:
             ctx.set_option(srs.OPT_INTERLEAVE, args.interleave)
         if mode == "rotate":
             ctx.set_option(srs.OPT_SNAPSHOT, srs.SNAPSHOT_ROTATE)
+            if not args.interleave:
+                ctx.set_option(srs.OPT_INTERLEAVE, 256)
         plans = [ctx.plan(S.numels, be) for _ in (0, 1)]
         nb = plans[0].nbuckets
         I = torch.empty((nb, cap), dtype=torch.int32, device=dev)
@@ -257,8 +259,8 @@ def rotating_leg(args, torch, srs, wl, versions, R, payload, cap, i0, nchanged, 
     I, V, counts = payload
     ctx = srs.Context(0)
     ctx.set_option(srs.OPT_SNAPSHOT, srs.SNAPSHOT_ROTATE)
-    ctx.set_option(srs.OPT_TILE_ELEMS, 16384)        # with no stores into the weights this mode measures best with
-    ctx.set_option(srs.OPT_INTERLEAVE, 256)          # smaller tiles spread over more buckets
+    ctx.set_option(srs.OPT_INTERLEAVE, 256)          # with no stores into the weights this mode measures best with
+                                                     # more buckets in flight than the in-place one (18.7 against 19.0 ms)
     plans = [ctx.plan(R.numels, wl.bucket_elems) for _ in (0, 1)]
     pairs = [ctx.bind_pairs(plans[d], versions[1 - d].tensors, versions[d].tensors) for d in (0, 1)]
     rolls = [ctx.bind_weights(plans[d], R.tensors) for d in (0, 1)]
@@ -464,8 +466,9 @@ def main() -> int:
     ctx.set_option(srs.OPT_INTERLEAVE, args.interleave) if args.interleave else None
     if args.rotate_snapshot:
         ctx.set_option(srs.OPT_SNAPSHOT, srs.SNAPSHOT_ROTATE)
-        # with no stores into the weights this mode measures best with smaller tiles spread over more buckets
-        ctx.set_option(srs.OPT_TILE_ELEMS, args.tile or 16384)
+        # with no stores into the weights this mode measures best with more buckets in flight than the in-place one
+        if args.tile:
+            ctx.set_option(srs.OPT_TILE_ELEMS, args.tile)
         ctx.set_option(srs.OPT_INTERLEAVE, args.interleave or 256)
     # one plan per direction: each keeps its own device copy of the pointer table, so alternating the
     # `new` version does not re-upload it every step
@@ -636,7 +639,7 @@ def main() -> int:
         "dtype": "u16",
         "data": "synthetic",
         "config": {"workload": wl.name, "elements": N, "buckets": plan.nbuckets, "bucket_elems": wl.bucket_elems,
-                   "changed_fraction": round(rho, 6), "payload_cap": cap, "tile_elems": args.tile or (16384 if args.rotate_snapshot else 32768),
+                   "changed_fraction": round(rho, 6), "payload_cap": cap, "tile_elems": args.tile or 32768,
                    "index_coding": bool(args.index_coding),
                    "snapshot": "rotate" if args.rotate_snapshot else "refresh-in-place"},
         "sync_ms": round(ms_per_step, 4),
