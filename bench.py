@@ -586,7 +586,7 @@ def main() -> int:
             f"value stream {wire / 1e9:.3f} GB against {2 * nchanged / 1e9:.3f} GB raw: alpha = {wire / (2 * nchanged):.4f}")
 
     probe_gbs = None
-    if args.probe:
+    if args.probe or not (args.regen or args.tiny):     # context for the roofline: what two plain read streams reach here
         nbytes = min(2 * N, 16 << 30) // 32768 * 32768
         sink = torch.empty(srs.stream_probe_sink_words(nbytes), dtype=torch.int32, device=dev)
         a = W0.flat.view(torch.int16)[: nbytes // 2]; b = W1.flat.view(torch.int16)[: nbytes // 2]
@@ -648,6 +648,8 @@ def main() -> int:
         "pct_hbm_peak_combined": round(100 * combined / HBM_PEAK_GBS, 2),
         "pct_hbm_peak_extract": round(100 * ach / HBM_PEAK_GBS, 2),
         "apply_strict_gbs": round(bytes_apply / (app_avg * 1e-3) / 1e9, 1),
+        # line model for iid changes: payload read + read-modify-write of every 128-byte line that holds a change
+        "apply_line_model_gbs": round((6.0 * rho * N + 2 * 128.0 * (N / 64.0) * (1.0 - (1.0 - rho) ** 64)) / (app_avg * 1e-3) / 1e9, 1),
         "read_probe_gbs": None if probe_gbs is None else round(probe_gbs, 1),
         "roofline": {"bound": "hbm", "kernel": "extract_kernel", "achieved": round(ach, 1), "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": round(ach / HBM_PEAK_GBS, 4),
