@@ -38,6 +38,8 @@
  *     replaces the earlier one in stream order).  Callers that alternate between pointer sets keep
  *     one plan per set.
  *   - Weights of a call may not overlap each other or the payload buffers.
+ *   - A context belongs to the device it was created on; every call works on that device whatever device is
+ *     current in the calling thread, and leaves the caller's current device as it found it.
  */
 #ifndef SRS_H
 #define SRS_H
@@ -118,6 +120,9 @@ int srs_apply(srs_ctx *ctx, void *weights, uint64_t n, uint64_t bucket_elems,
  * a bucket may hold many tensors.  Indices are positions INSIDE the bucket (packed position minus
  * b*bucket_elems), because packed positions of a 30 B-element model do not fit int32; with the
  * plan's segment table they map one-to-one to Alg. 2's per-tensor flat indices.
+ * The pointer arrays are host arrays of plan-many entries, read during the call; a tensor that has elements needs
+ * every pointer the call uses, aligned to its element size (else SRS_ERR_INVALID); the entries of a tensor without
+ * elements are ignored.
  */
 typedef struct { void *old_snapshot; const void *new_w; } srs_tensor_pair;   /* extract side */
 typedef struct { void *weights; } srs_tensor;                                 /* apply side   */

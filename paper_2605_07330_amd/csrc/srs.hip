@@ -22,6 +22,25 @@ constexpr uint64_t kMaxIndexable = 0x7fffffffull;   // int32 indices (Sec. 3.2: 
         if (e_ != hipSuccess) { (void)hipGetLastError(); return SRS_ERR_HIP; } \
     } while (0)
 
+// Makes `device` current for the rest of the enclosing scope and puts the caller's device back afterwards.
+struct DeviceGuard {
+    int prev = -1, target;
+    bool ok;
+    explicit DeviceGuard(int device) : target(device) {
+        ok = hipGetDevice(&prev) == hipSuccess && (prev == device || hipSetDevice(device) == hipSuccess);
+        if (!ok) (void)hipGetLastError();
+    }
+    ~DeviceGuard() {
+        if (ok && prev != target) DeviceGuard device_guard_(prev);
+    }
+    DeviceGuard(const DeviceGuard &) = delete;
+    DeviceGuard &operator=(const DeviceGuard &) = delete;
+};
+
+#define SRS_ON_DEVICE(device)            \
+    DeviceGuard device_guard_(device);   \
+    if (!device_guard_.ok) return SRS_ERR_HIP
+
 }  // namespace
 
 struct srs_ctx {
@@ -56,6 +75,7 @@ struct srs_plan {
     std::vector<PtrPair> h_pairs;           // what d_pairs currently holds
     std::vector<uint16_t *> h_wptrs;
     bool pairs_valid = false, wptrs_valid = false;
+    std::vector<uint8_t> has_elems;         // [ntensors] 1 where the tensor has elements, i.e. its pointers are used
 };
 
 namespace {
@@ -231,6 +251,23 @@ int build_layout(const uint64_t *numel, uint32_t ntensors, uint64_t bucket_elems
     return SRS_OK;
 }
 
+// Pointer arrays of a call: every tensor that has elements needs its pointers, aligned to their element size
+// (old_mask / new_mask / mask = alignment - 1).  Tensors without elements may carry anything.
+bool pair_pointers_ok(const srs_plan *plan, const srs_tensor_pair *t, uintptr_t old_mask, uintptr_t new_mask, bool need_old) {
+    for (uint32_t k = 0; k < plan->ntensors; ++k) {
+        if (!plan->has_elems[k]) continue;
+        if (!t[k].new_w || (need_old && !t[k].old_snapshot)) return false;
+        if (((uintptr_t)t[k].old_snapshot & old_mask) || ((uintptr_t)t[k].new_w & new_mask)) return false;
+    }
+    return true;
+}
+
+bool weight_pointers_ok(const srs_plan *plan, const srs_tensor *t, uintptr_t mask) {
+    for (uint32_t k = 0; k < plan->ntensors; ++k)
+        if (plan->has_elems[k] && (!t[k].weights || ((uintptr_t)t[k].weights & mask))) return false;
+    return true;
+}
+
 // keeps the device copy of the extract-side pointer table in step with the caller's array
 int upload_pair_pointers(srs_plan *plan, const srs_tensor_pair *t, hipStream_t st) {
     bool same = plan->pairs_valid;
@@ -301,7 +338,7 @@ int extract_single(srs_ctx *ctx, void *old_snapshot, const void *new_w, uint64_t
     if (((uintptr_t)I | (uintptr_t)counts) & 3u) return SRS_ERR_INVALID;
     if (eb == 1 && ctx->tile_elems < 8192) return SRS_ERR_INVALID;
     hipStream_t st = (hipStream_t)stream;
-    SRS_HIP(hipSetDevice(ctx->device));
+    SRS_ON_DEVICE(ctx->device);
 
     const uint64_t T = ctx->tile_elems;
     const uint64_t nb = (n + bucket_elems - 1) / bucket_elems;
@@ -340,11 +377,9 @@ int extract_multi(srs_ctx *ctx, srs_plan *plan, const srs_tensor_pair *t,
     const uintptr_t amask = (uintptr_t)eb - 1u;
     if (((uintptr_t)V & amask) || (((uintptr_t)I | (uintptr_t)counts) & 3u)) return SRS_ERR_INVALID;
     if (eb == 1 && plan->tile_elems < 8192) return SRS_ERR_INVALID;
-    // numel is not known here any more, but a tensor with elements has at least one segment
-    for (uint32_t k = 0; k < plan->ntensors; ++k)
-        if (((uintptr_t)t[k].old_snapshot & amask) || ((uintptr_t)t[k].new_w & (cast ? 3u : amask))) return SRS_ERR_INVALID;
+    if (!pair_pointers_ok(plan, t, amask, cast ? 3u : amask, src != kSrcBitmap)) return SRS_ERR_INVALID;
     hipStream_t st = (hipStream_t)stream;
-    SRS_HIP(hipSetDevice(ctx->device));
+    SRS_ON_DEVICE(ctx->device);
 
     int rc_up = upload_pair_pointers(plan, t, st);
     if (rc_up != SRS_OK) return rc_up;
@@ -384,7 +419,7 @@ int srs_create(srs_ctx **out, int device) {
     int ndev = 0;
     if (hipGetDeviceCount(&ndev) != hipSuccess || ndev <= 0) { (void)hipGetLastError(); return SRS_ERR_NO_DEVICE; }
     if (device < 0 || device >= ndev) return SRS_ERR_INVALID;
-    SRS_HIP(hipSetDevice(device));
+    SRS_ON_DEVICE(device);
     srs_ctx *ctx = new (std::nothrow) srs_ctx();
     if (!ctx) return SRS_ERR_NOMEM;
     ctx->device = device;
@@ -400,7 +435,7 @@ int srs_create(srs_ctx **out, int device) {
 
 int srs_destroy(srs_ctx *ctx) {
     if (!ctx) return SRS_ERR_INVALID;
-    (void)hipSetDevice(ctx->device);
+    DeviceGuard device_guard_(ctx->device);
     (void)hipDeviceSynchronize();
     if (ctx->status) (void)hipFree(ctx->status);
     if (ctx->tickets) (void)hipFree(ctx->tickets);
@@ -435,7 +470,7 @@ int srs_set_option(srs_ctx *ctx, int option, uint64_t value) {
 int srs_status(srs_ctx *ctx, uint32_t *flags, void *stream) {
     if (!ctx || !flags) return SRS_ERR_INVALID;
     hipStream_t st = (hipStream_t)stream;
-    SRS_HIP(hipSetDevice(ctx->device));
+    SRS_ON_DEVICE(ctx->device);
     SRS_HIP(hipMemcpyAsync(flags, ctx->flags, sizeof(uint32_t), hipMemcpyDeviceToHost, st));
     SRS_HIP(hipStreamSynchronize(st));
     hipLaunchKernelGGL(fill_u64_kernel, dim3(1), dim3(64), 0, st, (unsigned long long *)ctx->flags, (uint64_t)1, 0ull);
@@ -466,7 +501,7 @@ static int apply_single(srs_ctx *ctx, void *weights, uint64_t n, uint64_t bucket
     if (((uintptr_t)weights | (uintptr_t)V) & ((uintptr_t)eb - 1u)) return SRS_ERR_INVALID;
     if (((uintptr_t)I | (uintptr_t)counts) & 3u) return SRS_ERR_INVALID;
     hipStream_t st = (hipStream_t)stream;
-    SRS_HIP(hipSetDevice(ctx->device));
+    SRS_ON_DEVICE(ctx->device);
 
     const uint64_t nb = (n + bucket_elems - 1) / bucket_elems;
     const uint64_t slots = cap < bucket_elems ? cap : bucket_elems;       // a bucket never holds more pairs than elements
@@ -513,7 +548,7 @@ int srs_plan_create(srs_ctx *ctx, const uint64_t *numel, uint32_t ntensors, uint
     }
     const uint64_t nb64 = (total + bucket_elems - 1) / bucket_elems;
     if (nb64 > 0x7fffffffull) return SRS_ERR_INVALID;
-    SRS_HIP(hipSetDevice(ctx->device));
+    SRS_ON_DEVICE(ctx->device);
 
     srs_plan *p = new (std::nothrow) srs_plan();
     if (!p) return SRS_ERR_NOMEM;
@@ -528,6 +563,8 @@ int srs_plan_create(srs_ctx *ctx, const uint64_t *numel, uint32_t ntensors, uint
     try {
         p->h_pairs.assign(ntensors, PtrPair{nullptr, nullptr});
         p->h_wptrs.assign(ntensors, nullptr);
+        p->has_elems.resize(ntensors);
+        for (uint32_t k = 0; k < ntensors; ++k) p->has_elems[k] = numel[k] != 0;
     } catch (const std::bad_alloc &) {
         delete p; return SRS_ERR_NOMEM;
     }
@@ -605,7 +642,7 @@ int srs_plan_layout(const uint64_t *numel, uint32_t ntensors, uint64_t bucket_el
 
 int srs_plan_destroy(srs_plan *p) {
     if (!p) return SRS_ERR_INVALID;
-    (void)hipSetDevice(p->device);
+    DeviceGuard device_guard_(p->device);
     (void)hipDeviceSynchronize();
     if (p->d_tiles) (void)hipFree(p->d_tiles);
     if (p->d_segs) (void)hipFree(p->d_segs);
@@ -637,10 +674,9 @@ static int apply_multi(srs_ctx *ctx, srs_plan *plan, const srs_tensor *t,
     if (!t || !I || !V || !counts) return SRS_ERR_INVALID;
     const uintptr_t amask = (uintptr_t)eb - 1u;
     if (((uintptr_t)V & amask) || (((uintptr_t)I | (uintptr_t)counts) & 3u)) return SRS_ERR_INVALID;
-    for (uint32_t k = 0; k < plan->ntensors; ++k)
-        if ((uintptr_t)t[k].weights & amask) return SRS_ERR_INVALID;
+    if (!weight_pointers_ok(plan, t, amask)) return SRS_ERR_INVALID;
     hipStream_t st = (hipStream_t)stream;
-    SRS_HIP(hipSetDevice(ctx->device));
+    SRS_ON_DEVICE(ctx->device);
 
     int rc_up = upload_weight_pointers(plan, t, st);
     if (rc_up != SRS_OK) return rc_up;
@@ -672,7 +708,7 @@ int srs_tensor_indices(srs_ctx *ctx, srs_plan *plan, const int32_t *I, const uin
     if (!I || !counts || !tensor_id || !tensor_idx) return SRS_ERR_INVALID;
     if (((uintptr_t)I | (uintptr_t)counts | (uintptr_t)tensor_id | (uintptr_t)tensor_idx) & 3u) return SRS_ERR_INVALID;
     hipStream_t st = (hipStream_t)stream;
-    SRS_HIP(hipSetDevice(ctx->device));
+    SRS_ON_DEVICE(ctx->device);
     const uint64_t slots = cap < plan->be ? cap : plan->be;
     const uint64_t cpb = (slots + kApplyChunk - 1) / kApplyChunk;
     if ((uint64_t)plan->nbuckets * cpb > 0x7fffffffull) return SRS_ERR_INVALID;
@@ -707,10 +743,9 @@ static int mark_common(srs_ctx *ctx, srs_plan *plan, const srs_tensor_pair *t, u
     if (!ctx || !plan || plan->device != ctx->device) return SRS_ERR_INVALID;
     if (plan->total == 0) return SRS_OK;
     if (!t || !bitmap || ((uintptr_t)bitmap & 3u)) return SRS_ERR_INVALID;
-    for (uint32_t k = 0; k < plan->ntensors; ++k)
-        if (((uintptr_t)t[k].old_snapshot & 1u) || ((uintptr_t)t[k].new_w & (cast ? 3u : 1u))) return SRS_ERR_INVALID;
+    if (!pair_pointers_ok(plan, t, 1u, cast ? 3u : 1u, true)) return SRS_ERR_INVALID;
     hipStream_t st = (hipStream_t)stream;
-    SRS_HIP(hipSetDevice(ctx->device));
+    SRS_ON_DEVICE(ctx->device);
     int rc = upload_pair_pointers(plan, t, st);
     if (rc != SRS_OK) return rc;
     ExtractArgs a;
@@ -775,7 +810,7 @@ int srs_encode_indices(srs_ctx *ctx, const int32_t *I, const uint32_t *counts, u
     if (((uintptr_t)D & 1u) || (((uintptr_t)I | (uintptr_t)counts | (uintptr_t)max_gap | (uintptr_t)anchors) & 3u))
         return SRS_ERR_INVALID;
     hipStream_t st = (hipStream_t)stream;
-    SRS_HIP(hipSetDevice(ctx->device));
+    SRS_ON_DEVICE(ctx->device);
     const uint64_t cpb = (cap + kApplyChunk - 1) / kApplyChunk;
     if ((uint64_t)nbuckets * cpb > 0x7fffffffull) return SRS_ERR_INVALID;
     hipLaunchKernelGGL(zero_strided_kernel, dim3((nbuckets + 255) / 256), dim3(256), 0, st, max_gap, (uint64_t)nbuckets, 1u);
@@ -797,7 +832,7 @@ int srs_apply_encoded(srs_ctx *ctx, void *weights, uint64_t n, uint64_t bucket_e
     if (n == 0) return SRS_OK;
     if (!weights || ((uintptr_t)weights & 1u) || !encoded_args_ok(D, I_wide, V, counts, max_gap, anchors)) return SRS_ERR_INVALID;
     hipStream_t st = (hipStream_t)stream;
-    SRS_HIP(hipSetDevice(ctx->device));
+    SRS_ON_DEVICE(ctx->device);
     const uint64_t nb = (n + bucket_elems - 1) / bucket_elems;
     const uint64_t cpb = (cap + kApplyChunk - 1) / kApplyChunk;       // the anchors' layout
     if (nb * cpb > 0x7fffffffull) return SRS_ERR_INVALID;
@@ -821,10 +856,9 @@ int srs_apply_multi_encoded(srs_ctx *ctx, srs_plan *plan, const srs_tensor *t, c
     if (!ctx || !plan || cap == 0 || plan->device != ctx->device) return SRS_ERR_INVALID;
     if (plan->total == 0) return SRS_OK;
     if (!t || !encoded_args_ok(D, I_wide, V, counts, max_gap, anchors)) return SRS_ERR_INVALID;
-    for (uint32_t k = 0; k < plan->ntensors; ++k)
-        if ((uintptr_t)t[k].weights & 1u) return SRS_ERR_INVALID;
+    if (!weight_pointers_ok(plan, t, 1u)) return SRS_ERR_INVALID;
     hipStream_t st = (hipStream_t)stream;
-    SRS_HIP(hipSetDevice(ctx->device));
+    SRS_ON_DEVICE(ctx->device);
     int rc = upload_weight_pointers(plan, t, st);
     if (rc != SRS_OK) return rc;
     const uint64_t cpb = (cap + kApplyChunk - 1) / kApplyChunk;
@@ -855,7 +889,7 @@ int srs_route(srs_ctx *ctx, const uint32_t *counts, uint32_t nbuckets, uint64_t 
     if (nbuckets && (!counts || !route_slot || !sparse_counts || (!dense_bucket && max_dense))) return SRS_ERR_INVALID;
     if (((uintptr_t)counts | (uintptr_t)route_slot | (uintptr_t)sparse_counts | (uintptr_t)dense_bucket) & 3u) return SRS_ERR_INVALID;
     hipStream_t st = (hipStream_t)stream;
-    SRS_HIP(hipSetDevice(ctx->device));
+    SRS_ON_DEVICE(ctx->device);
     RouteArgs a;
     std::memset(&a, 0, sizeof(a));
     a.counts = counts; a.nb = nbuckets; a.be = bucket_elems; a.total = total_elems; a.cap = cap;
@@ -872,10 +906,9 @@ int srs_pack_dense_multi(srs_ctx *ctx, srs_plan *plan, const srs_tensor_pair *t,
     if (!ctx || !plan || plan->device != ctx->device) return SRS_ERR_INVALID;
     if (plan->total == 0 || max_dense == 0) return SRS_OK;
     if (!t || !dense_bucket || !n_dense || !dense || ((uintptr_t)dense & 1u)) return SRS_ERR_INVALID;
-    for (uint32_t k = 0; k < plan->ntensors; ++k)
-        if (((uintptr_t)t[k].old_snapshot | (uintptr_t)t[k].new_w) & 1u) return SRS_ERR_INVALID;
+    if (!pair_pointers_ok(plan, t, 1u, 1u, false)) return SRS_ERR_INVALID;       // only the new weights are read
     hipStream_t st = (hipStream_t)stream;
-    SRS_HIP(hipSetDevice(ctx->device));
+    SRS_ON_DEVICE(ctx->device);
     int rc = upload_pair_pointers(plan, t, st);
     if (rc != SRS_OK) return rc;
     return launch_dense_copy<true>(ctx, plan, dense_bucket, n_dense, max_dense, dense, st);
@@ -886,10 +919,9 @@ int srs_unpack_dense_multi(srs_ctx *ctx, srs_plan *plan, const srs_tensor *t, co
     if (!ctx || !plan || plan->device != ctx->device) return SRS_ERR_INVALID;
     if (plan->total == 0 || max_dense == 0) return SRS_OK;
     if (!t || !dense_bucket || !n_dense || !dense || ((uintptr_t)dense & 1u)) return SRS_ERR_INVALID;
-    for (uint32_t k = 0; k < plan->ntensors; ++k)
-        if ((uintptr_t)t[k].weights & 1u) return SRS_ERR_INVALID;
+    if (!weight_pointers_ok(plan, t, 1u)) return SRS_ERR_INVALID;
     hipStream_t st = (hipStream_t)stream;
-    SRS_HIP(hipSetDevice(ctx->device));
+    SRS_ON_DEVICE(ctx->device);
     int rc = upload_weight_pointers(plan, t, st);
     if (rc != SRS_OK) return rc;
     return launch_dense_copy<false>(ctx, plan, dense_bucket, n_dense, max_dense, const_cast<uint16_t *>(dense), st);
@@ -909,7 +941,7 @@ int srs_encode_values(srs_ctx *ctx, const uint16_t *V, const uint32_t *counts, u
     if ((((uintptr_t)V | (uintptr_t)sub) & 1u) || (((uintptr_t)counts | (uintptr_t)bits | (uintptr_t)chunk_words) & 3u))
         return SRS_ERR_INVALID;
     hipStream_t st = (hipStream_t)stream;
-    SRS_HIP(hipSetDevice(ctx->device));
+    SRS_ON_DEVICE(ctx->device);
     const uint64_t nchunk = (cap + kVcChunk - 1) / kVcChunk;
     if ((uint64_t)nbuckets * nchunk > 0x7fffffffull) return SRS_ERR_INVALID;
     const uint64_t words = (uint64_t)nbuckets * 512;
@@ -948,7 +980,7 @@ int srs_decode_values(srs_ctx *ctx, const uint8_t *lens, const uint8_t *low, con
     if ((((uintptr_t)V_out | (uintptr_t)sub) & 1u) || (((uintptr_t)counts | (uintptr_t)bits | (uintptr_t)chunk_words) & 3u))
         return SRS_ERR_INVALID;
     hipStream_t st = (hipStream_t)stream;
-    SRS_HIP(hipSetDevice(ctx->device));
+    SRS_ON_DEVICE(ctx->device);
     const uint64_t nchunk = (cap + kVcChunk - 1) / kVcChunk;
     if ((uint64_t)nbuckets * nchunk > 0x7fffffffull) return SRS_ERR_INVALID;
     ValueCodecArgs a;
@@ -975,7 +1007,7 @@ int srs_stream_probe(srs_ctx *ctx, const void *a, const void *b, uint64_t bytes,
     if (!ctx || !a || !b || !sink || (bytes & 15u) || (((uintptr_t)a | (uintptr_t)b) & 15u)) return SRS_ERR_INVALID;
     if (bytes == 0) return SRS_OK;
     hipStream_t st = (hipStream_t)stream;
-    SRS_HIP(hipSetDevice(ctx->device));
+    SRS_ON_DEVICE(ctx->device);
     const uint64_t nvec = bytes / 16;
     const uint64_t tile_bytes = 16384ull * 2ull;
     const uint64_t blocks = (bytes + tile_bytes - 1) / tile_bytes;

@@ -337,6 +337,37 @@ def test_invalid_arguments_are_rejected_before_launch(srs, ctx):
     plan.close()
 
 
+def test_null_tensor_pointers_are_rejected_before_launch(srs, ctx):
+    """A tensor with elements needs its pointers; one without elements may carry anything."""
+    numel = [100, 0, 60]
+    olds = [from_u16(np.zeros(m, np.uint16), DEV) for m in numel]
+    news = [from_u16(np.ones(m, np.uint16), DEV) for m in numel]
+    plan = ctx.plan(numel, 64)
+    I, V, counts = srs.alloc_payload(plan.nbuckets, 64, DEV)
+    pairs = ctx.bind_pairs(plan, olds, news)
+    weights = ctx.bind_weights(plan, olds)
+    pairs[1].old_snapshot = None; pairs[1].new_w = None; weights[1].weights = None     # the empty tensor
+    ctx.extract_multi(plan, None, None, I, V, counts, 64, pairs=pairs)
+    ctx.apply_multi(plan, None, I, V, counts, 64, tensors=weights)
+    assert ctx.status() == 0 and counts.tolist() == [64, 64, 32]
+    keep = pairs[2].new_w
+    pairs[2].new_w = None
+    with pytest.raises(srs.SrsError) as e:
+        ctx.extract_multi(plan, None, None, I, V, counts, 64, pairs=pairs)
+    assert e.value.code == srs.ERR_INVALID
+    pairs[2].new_w = keep
+    pairs[0].old_snapshot = None
+    with pytest.raises(srs.SrsError) as e:
+        ctx.extract_multi(plan, None, None, I, V, counts, 64, pairs=pairs)
+    assert e.value.code == srs.ERR_INVALID
+    weights[2].weights = None
+    with pytest.raises(srs.SrsError) as e:
+        ctx.apply_multi(plan, None, I, V, counts, 64, tensors=weights)
+    assert e.value.code == srs.ERR_INVALID
+    assert ctx.status() == 0
+    plan.close()
+
+
 def test_repeated_runs_are_bit_identical(srs, ctx):
     """The look-back chain is the only cross-workgroup interaction: 20 runs must agree exactly."""
     n, be = 3_000_017, 1_000_003
