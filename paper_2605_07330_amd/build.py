@@ -44,6 +44,23 @@ def build_membench(verbose: bool = False) -> str:
     return MEMBENCH
 
 
+C_CONSUMER_SRC = os.path.join(ROOT, "tests", "c_abi", "roundtrip.c")
+C_CONSUMER = os.path.join(ROOT, "tests", "c_abi", "roundtrip")
+
+
+def build_c_consumer(verbose: bool = False) -> str:
+    """The plain C program the GPU tests run against libsrs.so (gcc, C99: the header must be valid C)."""
+    gcc = os.environ.get("CC", "gcc")
+    cmd = [gcc, "-std=c99", "-O1", "-Wall", "-Wextra", "-Werror", "-I", os.path.join(ROOT, "include"),
+           "-isystem", "/opt/rocm/include", C_CONSUMER_SRC, "-o", C_CONSUMER,
+           "-L", HERE, "-lsrs", "-L", "/opt/rocm/lib", "-lamdhip64",
+           "-Wl,-rpath,$ORIGIN/../../paper_2605_07330_amd", "-Wl,-rpath,/opt/rocm/lib"]
+    if verbose:
+        print(" ".join(cmd), flush=True)
+    subprocess.check_call(cmd)
+    return C_CONSUMER
+
+
 def is_stale() -> bool:
     if not os.path.exists(LIB):
         return True
@@ -54,4 +71,5 @@ def is_stale() -> bool:
 if __name__ == "__main__":
     build_lib(verbose=True)
     build_membench(verbose=True)
+    build_c_consumer(verbose=True)
     print(LIB)
