@@ -30,8 +30,11 @@ HBM_PEAK_GBS = 8000.0
 
 # HBM traffic per extract launch measured with rocprofv3 --pmc (FETCH_SIZE x 2.00 + WRITE_SIZE x 1.00, the
 # factors from a 61.06 GB copy in the same runs): profiles/extract_apply_qwen3-30b-a3b.md.  Only the workload
-# that was profiled has a figure.
-MEASURED_TRAFFIC_BYTES = {"qwen3-30b-a3b": 133.4e9}
+# that was profiled has a figure.  122.4 GB read (old + new once, tile tables, status words) + 30.9 GB written:
+# 1.83 GB of payload and the 224 M lines of the snapshot that hold a change, rewritten whole (28.7 GB for 0.61 GB
+# of changed values: the memory side charges a sparse store by the line it touches, and a whole line costs it
+# less than a part of one).
+MEASURED_TRAFFIC_BYTES = {"qwen3-30b-a3b": 153.3e9}
 
 
 def log(msg: str) -> None:
@@ -105,6 +108,8 @@ def bench_cast(args, torch, srs, synth, wl, dev) -> int:
         ctx.set_option(srs.OPT_TILE_ELEMS, args.tile)
     if args.interleave:
         ctx.set_option(srs.OPT_INTERLEAVE, args.interleave)
+    if args.refresh_group >= 0:
+        ctx.set_option(srs.OPT_REFRESH_GROUP, args.refresh_group)
     plan = ctx.plan(W.numels, wl.bucket_elems)
     cap = (synth.payload_capacity(wl) + 7) // 8 * 8
     I = torch.empty((plan.nbuckets, cap), dtype=torch.int32, device=dev)
@@ -182,6 +187,8 @@ def bench_fp8(args, torch, srs, synth, wl, dev) -> int:
             ctx.set_option(srs.OPT_TILE_ELEMS, args.tile)
         if args.interleave:
             ctx.set_option(srs.OPT_INTERLEAVE, args.interleave)
+        if args.refresh_group >= 0:
+            ctx.set_option(srs.OPT_REFRESH_GROUP, args.refresh_group)
         if mode == "rotate":
             ctx.set_option(srs.OPT_SNAPSHOT, srs.SNAPSHOT_ROTATE)
             if not args.interleave:
@@ -368,7 +375,7 @@ def main() -> int:
     ap.add_argument("--density", type=float, default=None)
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--tile", type=int, default=0, help="extract tile elements (0 = library default)")
-    ap.add_argument("--refresh-group", type=int, default=-1, help="snapshot refresh granularity (0, 4 or 8 lanes of 16 B)")
+    ap.add_argument("--refresh-group", type=int, default=-1, help="snapshot refresh: 8 = whole 128-byte lines (default), 0 = element by element")
     ap.add_argument("--interleave", type=int, default=0, help="buckets interleaved over consecutive workgroups (0 = default)")
     ap.add_argument("--tiny", action="store_true", help="structure-preserving tiny workload (debugging only)")
     ap.add_argument("--no-cpu-baseline", action="store_true")

@@ -67,9 +67,12 @@ typedef enum {
 #define SRS_OPT_SPIN_LIMIT 1   /* max polls of a predecessor tile before SRS_FLAG_TIMEOUT (default 1<<24) */
 #define SRS_OPT_TILE_ELEMS 2   /* elements per extract tile: 4096, 8192, 16384 or 32768 (default; tuning; affects
                                   plans created afterwards) */
-#define SRS_OPT_REFRESH_GROUP 3 /* snapshot refresh: 0 = a 2-byte store per changed element; 4 (default) / 8 = the same,
-                                  except that a quarter of a tile in which at least 1 element in 32 changed is
-                                  refreshed by whole aligned 64- / 128-byte blocks around the changes (tuning) */
+#define SRS_OPT_REFRESH_GROUP 3 /* snapshot refresh: 8 (default) = a full tile of 16-byte-aligned weights rewrites
+                                  every 128-byte run of the snapshot that holds a change (a whole line when the tensor
+                                  starts on a 128-byte boundary, which is where the gain comes from), from the
+                                  new weights (unchanged elements get the value they have), other tiles store element
+                                  by element; 0 = a store per changed element everywhere.  Same result; tuning.
+                                  Applies to the extract calls of every element width and to the fused cast. */
 #define SRS_OPT_INTERLEAVE 4   /* buckets whose tiles are interleaved over consecutive workgroups, 1..4096
                                   (default 64; tuning; affects plans created afterwards) */
 #define SRS_OPT_SNAPSHOT 5     /* what srs_extract / srs_extract_multi do with the snapshot:
@@ -171,8 +174,7 @@ int srs_tensor_indices(srs_ctx *ctx, srs_plan *plan, const int32_t *I, const uin
  * V is uint8_t[nb*cap]; indices, counts, capacity rule, flags, snapshot semantics (SRS_OPT_SNAPSHOT included) and
  * error behaviour are those of the 16-bit calls.  No alignment is required (16-byte aligned tensors take the
  * vector path).  A plan serves both widths.  Restrictions: SRS_OPT_TILE_ELEMS 4096 is rejected with
- * SRS_ERR_INVALID (a one-byte tile is at least 8192 elements), and SRS_OPT_REFRESH_GROUP is ignored (the
- * snapshot is refreshed element by element).  The fused cast, the cumulative set, the index coding of an
+ * SRS_ERR_INVALID (a one-byte tile is at least 8192 elements).  The fused cast, the cumulative set, the index coding of an
  * existing payload (srs_encode_indices reads I only) and the routing work as they stand or do not apply; an
  * encoded apply and a value coder for one-byte values are not provided.
  */

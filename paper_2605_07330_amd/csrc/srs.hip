@@ -55,7 +55,7 @@ struct srs_ctx {
     uint32_t spin_limit = 1u << 24;
     uint32_t tile_elems = 32768;
     uint32_t group = 64;                    // buckets whose tiles are interleaved over consecutive workgroups
-    uint32_t refresh_group = 4;             // 0: element-wise refresh; 4 / 8: dense quarters of a tile by blocks of that many 16-byte lanes
+    uint32_t refresh_group = 8;             // 8: snapshot refreshed by whole 128-byte lines (full, aligned tiles); 0: element by element
     bool rotate_snapshot = false;           // true: extract leaves the snapshot alone, the caller swaps buffers
 };
 
@@ -114,13 +114,14 @@ int prepare_extract(srs_ctx *ctx, uint64_t ntiles, uint64_t nb, hipStream_t st, 
 
 // One-byte elements: a tile of tile_elems elements is V = tile_elems / 4096 vectors per lane (16 elements each), so
 // the smallest tile (4096) has no kernel (V is even by construction of the packed scan).  The snapshot is refreshed
-// element by element, or not at all under the rotating-snapshot option.
+// as for 16-bit elements: by whole lines, element by element, or not at all under the rotating-snapshot option.
 template <bool MULTI>
 int launch_extract_u8(const srs_ctx *ctx, uint32_t tile_elems, const ExtractArgs &a, hipStream_t st) {
     const dim3 grid(a.ntiles), block(kThreads);
 #define SRS_LAUNCH8(VV)                                                                                               \
     do {                                                                                                              \
         if (ctx->rotate_snapshot) hipLaunchKernelGGL((extract_kernel<VV, MULTI, -1, kSrcBf16, 1>), grid, block, 0, st, a); \
+        else if (ctx->refresh_group == 8) hipLaunchKernelGGL((extract_kernel<VV, MULTI, 8, kSrcBf16, 1>), grid, block, 0, st, a); \
         else hipLaunchKernelGGL((extract_kernel<VV, MULTI, 0, kSrcBf16, 1>), grid, block, 0, st, a);                   \
     } while (0)
     switch (tile_elems) {
@@ -152,10 +153,11 @@ int launch_extract(const srs_ctx *ctx, uint32_t tile_elems, const ExtractArgs &a
     }
 #define SRS_LAUNCH(VV)                                                                                                \
     do {                                                                                                              \
-        if (src == kSrcFp32) hipLaunchKernelGGL((extract_kernel<VV, MULTI, 4, kSrcFp32>), grid, block, 0, st, a);     \
-        else if (ctx->rotate_snapshot) hipLaunchKernelGGL((extract_kernel<VV, MULTI, -1>), grid, block, 0, st, a);    \
+        if (src == kSrcFp32) {                                                                                        \
+            if (ctx->refresh_group == 8) hipLaunchKernelGGL((extract_kernel<VV, MULTI, 8, kSrcFp32>), grid, block, 0, st, a); \
+            else hipLaunchKernelGGL((extract_kernel<VV, MULTI, 0, kSrcFp32>), grid, block, 0, st, a);                 \
+        } else if (ctx->rotate_snapshot) hipLaunchKernelGGL((extract_kernel<VV, MULTI, -1>), grid, block, 0, st, a);  \
         else if (ctx->refresh_group == 8) hipLaunchKernelGGL((extract_kernel<VV, MULTI, 8>), grid, block, 0, st, a);  \
-        else if (ctx->refresh_group == 4) hipLaunchKernelGGL((extract_kernel<VV, MULTI, 4>), grid, block, 0, st, a);  \
         else hipLaunchKernelGGL((extract_kernel<VV, MULTI, 0>), grid, block, 0, st, a);                               \
     } while (0)
     switch (tile_elems) {
@@ -455,7 +457,7 @@ int srs_set_option(srs_ctx *ctx, int option, uint64_t value) {
             if (!valid_tile_elems(value)) return SRS_ERR_INVALID;
             ctx->tile_elems = (uint32_t)value; return SRS_OK;
         case SRS_OPT_REFRESH_GROUP:
-            if (value != 0 && value != 4 && value != 8) return SRS_ERR_INVALID;
+            if (value != 0 && value != 8) return SRS_ERR_INVALID;
             ctx->refresh_group = (uint32_t)value; return SRS_OK;
         case SRS_OPT_INTERLEAVE:
             if (value == 0 || value > 4096) return SRS_ERR_INVALID;

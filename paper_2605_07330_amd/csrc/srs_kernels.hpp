@@ -26,6 +26,8 @@
 // is HBM-bandwidth bound and there is no contraction, hence no MFMA.
 #pragma once
 #include <hip/hip_runtime.h>
+
+#include <type_traits>
 #include <stdint.h>
 
 namespace srs {
@@ -311,12 +313,18 @@ __device__ __forceinline__ uint32_t look_back(const ExtractArgs &a, uint32_t til
 // ---------------------------------------------------------------------------------------------
 // extract
 // ---------------------------------------------------------------------------------------------
-// RG = lanes per snapshot-refresh group: 0 refreshes element by element (2-byte stores from the write-out
-// loop); 4 / 8 do the same for sparse data, but a wave whose quarter of a full tile has at least one changed
-// element in 32 rewrites the whole aligned 64 / 128 bytes around each change from the new weights (unchanged
-// elements get the value they already hold): at such densities nearly every block holds a change and full
-// blocks are the cheaper writes; -1 does not touch the snapshot at all (the caller rotates buffers: `new` is the
-// next call's `old`).
+// RG = how the snapshot is refreshed.  8: by whole lines -- a full tile of 16-byte-aligned weights rewrites every
+// aligned 128-byte line of the snapshot that holds a change (8 lanes x 16 bytes of one store instruction) from the
+// new weights it has in registers; unchanged elements get the value they already hold.  The snapshot's loads and
+// these stores carry the non-temporal hint: a line written in full needs no read-modify-write behind the L2, and
+// nothing of the snapshot is needed again.  Measured on the 910-bucket benchmark set against element-wise refresh,
+// in one process, ms: 21.8 / 22.4 at 0.1 % changed, 25.8 / 28.7 at 1 %, 30.1 / 36.2 at 3 %, 33.6 / 40.4 at 10 %.
+// The two hints only pay together (at 1 %: stores alone 27.6, loads alone 28.3; 64-byte blocks 28.8, 256-byte
+// blocks 30.5).  The new weights are hinted as well (read once; worth 1 % on one-byte and on sparse data, nothing
+// at 1 %), except the FP32 master weights of CAST, where the hint costs 1 ms of 38.  Tiles that are ragged or not
+// 16-byte aligned refresh element by element with ordinary loads.
+// 0: element by element everywhere (2-byte stores from the write-out loop).  -1: the snapshot is not touched at all
+// (the caller rotates buffers: `new` is the next call's `old`).
 // CAST: `new` is not a BF16 buffer but the FP32 master weights; each element is rounded to BF16
 // (nearest even, NaN -> 0x7FC0) on the fly and `old` is the model-parameter buffer itself: the cast-and-
 // copy of Alg. 1 fused with its diff, so that no snapshot exists at all.
@@ -327,10 +335,11 @@ constexpr int kSrcBf16 = 0, kSrcFp32 = 1, kSrcBitmap = 2;
 template <int V, bool MULTI, int RG, int SRC = kSrcBf16, int EB = 2>
 __global__ __launch_bounds__(kThreads) void extract_kernel(const ExtractArgs a) {
     // A snapshot that is not written is read exactly once, like the new weights: both streams then carry the
-    // non-temporal hint (measured 4 % faster; with the in-place refresh the hint on either stream measures slower,
-    // on the snapshot by 5 ms: the refresh stores must find their line still cached; hinting the loads and the
-    // refresh stores together measures 0.2 ms slower than no hint at all).
+    // non-temporal hint (measured 4 % faster).  With element-wise refresh the hint on either stream measures slower,
+    // on the snapshot by 5 ms: 2-byte refresh stores must find their line still cached, hinted or not.
+    static_assert(RG == -1 || RG == 0 || RG == 8, "refresh: none, element-wise or whole lines");
     constexpr bool NT = (RG < 0);
+    constexpr bool LINES = (RG == 8);
     constexpr bool CAST = (SRC == kSrcFp32);
     static_assert(SRC == kSrcBf16 || SRC == kSrcFp32, "the bitmap source has its own kernel");
     static_assert(V % 2 == 0, "counts are scanned in packed pairs");
@@ -407,24 +416,32 @@ __global__ __launch_bounds__(kThreads) void extract_kernel(const ExtractArgs a) 
     const bool aligned = CAST ? (((((uintptr_t)po) | ((uintptr_t)pf)) & 15u) == 0)
                               : (((((uintptr_t)po) | ((uintptr_t)pn)) & 15u) == 0);
     uint32_t m[V];
+    // Whole-line refresh: any full tile of 16-byte vectors.  (A tile that does not start on a 128-byte boundary
+    // writes the same bytes in runs of 128 that straddle two lines: correct, only without the benefit.)
+    const bool by_lines = LINES && aligned && len == TILE;              // uniform over the workgroup
     if (aligned && len == TILE) {
-        if (CAST) {
-            u32x4 f0[V], f1[V];
+        auto stream_tile = [&](auto hint) {                // all loads of the tile issued back to back
+            constexpr bool H = decltype(hint)::value;
+            if (CAST) {
+                u32x4 f0[V], f1[V];
 #pragma unroll
-            for (int j = 0; j < V; ++j) {
-                f0[j] = *reinterpret_cast<const u32x4 *>(pf + e0 + j * ROW);
-                f1[j] = *reinterpret_cast<const u32x4 *>(pf + e0 + j * ROW + 4);
+                for (int j = 0; j < V; ++j) {
+                    f0[j] = load16<false>(pf + e0 + j * ROW);
+                    f1[j] = load16<false>(pf + e0 + j * ROW + 4);
+                }
+#pragma unroll
+                for (int j = 0; j < V; ++j) xo[j] = load16<H>(po + e0 + j * ROW);
+#pragma unroll
+                for (int j = 0; j < V; ++j) xn[j] = round8_bf16(f0[j], f1[j]);
+            } else {
+#pragma unroll
+                for (int j = 0; j < V; ++j) xn[j] = load16<H>(pn + e0 + j * ROW);
+#pragma unroll
+                for (int j = 0; j < V; ++j) xo[j] = load16<H>(po + e0 + j * ROW);
             }
-#pragma unroll
-            for (int j = 0; j < V; ++j) xo[j] = load16<NT>(po + e0 + j * ROW);
-#pragma unroll
-            for (int j = 0; j < V; ++j) xn[j] = round8_bf16(f0[j], f1[j]);
-        } else {
-#pragma unroll
-            for (int j = 0; j < V; ++j) xn[j] = load16<NT>(pn + e0 + j * ROW);
-#pragma unroll
-            for (int j = 0; j < V; ++j) xo[j] = load16<NT>(po + e0 + j * ROW);
-        }
+        };
+        // one flavour of loads per instantiation: choosing between two at run time cost 2 ms of the 3 ms the hints gain
+        stream_tile(std::integral_constant<bool, NT || LINES>{});
     } else {
 #pragma unroll
         for (int j = 0; j < V; ++j) {
@@ -461,26 +478,21 @@ __global__ __launch_bounds__(kThreads) void extract_kernel(const ExtractArgs a) 
         ex[2 * q + 1] = wave_total + (exc >> 16);
         wave_total += tot >> 16;
     }
-    // ---- snapshot refresh by groups of RG lanes (RG*16 bytes), for the waves of a full tile whose quarter of it is
-    // dense enough (at least one element in kGroupFrom changed): there nearly every group holds a change and whole
-    // blocks are the cheaper way to write; sparser quarters are refreshed element by element in the write-out loop
-    constexpr uint32_t kGroupFrom = 32;
-    const bool group_refresh = (RG > 0) && aligned && len == TILE && wave_total * kGroupFrom >= V * ROW;   // per wave
-    if (group_refresh) {
+    // ---- snapshot refresh by whole lines: lane groups of 8 hold one aligned 128-byte line per vector
+    if (by_lines) {
 #pragma unroll
         for (int j = 0; j < V; ++j) {
             const unsigned long long changed = __ballot(m[j] != 0);
-            const uint32_t grp = (uint32_t)(changed >> (lane & ~(RG > 0 ? RG - 1 : 0))) & ((1u << (RG > 0 ? RG : 1)) - 1u);
-            if (grp) *reinterpret_cast<u32x4 *>(po + e0 + j * ROW) = xn[j];
+            if ((uint32_t)(changed >> (lane & ~7)) & 0xFFu)
+                __builtin_nontemporal_store(xn[j], reinterpret_cast<u32x4 *>(po + e0 + j * ROW));
         }
     }
-    if (lane == 0) s_wave_total[wave] = wave_total | (group_refresh ? 0x80000000u : 0u);
+    if (lane == 0) s_wave_total[wave] = wave_total;
     __syncthreads();
-    uint32_t wave_base = 0, tile_total = 0, grouped = 0;                 // grouped: bit w = wave w refreshed by groups
+    uint32_t wave_base = 0, tile_total = 0;
 #pragma unroll
     for (int w = 0; w < kWaves; ++w) {
-        const uint32_t t = s_wave_total[w] & 0x7FFFFFFFu;
-        grouped |= (s_wave_total[w] >> 31) << w;
+        const uint32_t t = s_wave_total[w];
         wave_base += (w < wave) ? t : 0u;
         tile_total += t;
     }
@@ -521,7 +533,7 @@ __global__ __launch_bounds__(kThreads) void extract_kernel(const ExtractArgs a) 
         // 22.3 / 39.9 ms staged; smaller tiles do better staged).
         __syncthreads();                            // s_excl
         const uint32_t excl = s_excl;
-        const bool elementwise = RG == 0 || (RG > 0 && !group_refresh);
+        const bool elementwise = RG == 0 || (LINES && !by_lines);
 #pragma unroll
         for (int j = 0; j < V; ++j) {
             uint32_t mm = m[j];
@@ -567,8 +579,8 @@ __global__ __launch_bounds__(kThreads) void extract_kernel(const ExtractArgs a) 
             const uint64_t r = (uint64_t)excl + r0 + k;
             if (local < len) {                      // always true for a correct scan; keeps stores in bounds
                 if (r < a.cap) { Ib[r] = (int32_t)(idx_base + local); Vb[r] = val; }
-                // snapshot refresh: W_prev <- W at changed positions, unless that wave's quarter went by groups
-                if (RG == 0 || (RG > 0 && !((grouped >> (local / (V * ROW))) & 1u))) po[local] = val;
+                // snapshot refresh: W_prev <- W at changed positions, unless the tile went by whole lines
+                if (RG == 0 || (LINES && !by_lines)) po[local] = val;
             }
         }
         lds_barrier();
