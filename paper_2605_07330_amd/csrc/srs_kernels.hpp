@@ -726,7 +726,8 @@ __global__ __launch_bounds__(kThreads) void extract_marked_kernel(const ExtractA
 // mark_kernel: one optimizer step of Alg. 1's index accumulation, I_cum <- I_cum U { i : W[i] != W_prev[i] },
 // kept as a bitmap over packed positions.  CAST = false compares two BF16 versions; CAST = true is the
 // Trainer's own sequence without the clone: W <- round_BF16(master) and the elements whose pattern changed
-// are marked.  One workgroup per tile of the plan; no chain, no ticket: tiles are independent here.
+// are marked.  One workgroup per tile of the plan, in tile order; no chain, no ticket: tiles are independent here.
+// (Extract's bucket-interleaved order measured 3 % faster for two BF16 versions and 5 % slower with CAST.)
 // ---------------------------------------------------------------------------------------------
 template <int V, bool CAST>
 __global__ __launch_bounds__(kThreads) void mark_kernel(const ExtractArgs a) {
@@ -750,8 +751,9 @@ __global__ __launch_bounds__(kThreads) void mark_kernel(const ExtractArgs a) {
         const uint32_t e = e0 + j * 512;
         if (full || (aligned && e + 8 <= len)) {
             // two versions that are only compared are read once each: non-temporal (2 % faster); with CAST the
-            // parameters are rewritten below and stay on ordinary loads, like extract's snapshot
-            xo[j] = CAST ? load16<false>(po + e) : load16<true>(po + e);
+            // parameters are rewritten below by whole lines, hinted like extract's snapshot, and the master weights
+            // stay on ordinary loads
+            xo[j] = load16<true>(po + e);
             if (CAST) xn[j] = round8_bf16(*reinterpret_cast<const u32x4 *>(pf + e), *reinterpret_cast<const u32x4 *>(pf + e + 4));
             else xn[j] = load16<true>(pn + e);
         } else {
@@ -766,7 +768,7 @@ __global__ __launch_bounds__(kThreads) void mark_kernel(const ExtractArgs a) {
         if (CAST) {                                           // write the cast back where it changed something
             if (full) {
                 const unsigned long long changed = __ballot(m != 0);
-                if ((uint32_t)(changed >> (lane & ~3)) & 0xFu) *reinterpret_cast<u32x4 *>(po + e) = xn[j];
+                if ((uint32_t)(changed >> (lane & ~7)) & 0xFFu) __builtin_nontemporal_store(xn[j], reinterpret_cast<u32x4 *>(po + e));
             } else if (m) {
                 uint32_t mm = m;
                 while (mm) {
