@@ -8,7 +8,11 @@
 //      apply cost, and why they cost the same whatever the store width: the memory side pays per
 //      128-byte line touched);
 //   4. the same sparse blocks updated by an explicit read-modify-write of the whole 64-byte block or 128-byte
-//      line in the kernel (no cheaper than the masked 2-byte store, so the scatter keeps its 2-byte stores).
+//      line in the kernel (no cheaper than the masked 2-byte store, so the scatter keeps its 2-byte stores);
+//   5. what extract's snapshot refresh does now -- both buffers streamed with the non-temporal hint, chosen 128-byte
+//      lines of one of them rewritten whole with the hint -- with the same number of lines chosen one by one or in
+//      runs of 4 .. 256 consecutive lines (how much of the cost goes with the line and how much with the stretch of
+//      memory it lies in).
 // Everything is in bounds by construction; no input, no arguments.
 #include <hip/hip_runtime.h>
 
@@ -92,6 +96,34 @@ __global__ __launch_bounds__(256) void k_rmw(uint16_t *dst, uint32_t keep, uint3
     if (UNIT == 0 && acc == 0x12345u) sink[0] = 1;
 }
 
+// Two hinted read streams over dst and src; the chosen 128-byte lines of dst are rewritten whole (8 lanes x 16 bytes,
+// hinted).  Lines are chosen in runs of G: run r (lines r*G .. r*G+G-1) is chosen when hash(r) % keep == 0.
+// WRITE = false: the two reads only.
+template <int G, bool WRITE>
+__global__ __launch_bounds__(256) void k_lines(uint16_t *dst, const uint16_t *src, uint32_t keep, uint32_t *sink) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const uint64_t tile = (uint64_t)blockIdx.x * 16384;
+    const uint32_t e0 = wave * 4096 + lane * 8;
+    u32x4 xo[8], xn[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) xn[j] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(src + tile + e0 + j * 512));
+#pragma unroll
+    for (int j = 0; j < 8; ++j) xo[j] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(dst + tile + e0 + j * 512));
+    u32x4 acc = {0, 0, 0, 0};
+#pragma unroll
+    for (int j = 0; j < 8; ++j) acc ^= xo[j] ^ xn[j];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+        if (WRITE) {
+            const uint32_t line = (uint32_t)((tile + e0 + j * 512) >> 6);
+            const uint32_t run = line / G;
+            if (((run * 2654435761u) >> 8) % keep == 0)
+                __builtin_nontemporal_store(xn[j], reinterpret_cast<u32x4 *>(dst + tile + e0 + j * 512));
+        }
+    }
+    if ((acc.x ^ acc.y ^ acc.z ^ acc.w) == 0x12345u) sink[0] = 1;
+}
+
 int main() {
     const uint64_t N = 8ull << 30;   // elements per buffer (16 GB)
     const uint32_t nwg = (uint32_t)(N / 16384);
@@ -155,6 +187,25 @@ int main() {
         std::printf("1/%-3u %6.1f M   | %6.3f ms %5.1f ps/line | %6.3f ms %5.1f ps/line | %6.3f ms %5.1f ps/line | %6.3f ms %5.1f ps/line\n",
                     keep, lines / 1e6, t1, t1 * 1e9 / lines, t2, t2 * 1e9 / lines, t3, t3 * 1e9 / lines, t4,
                     t4 * 1e9 / lines);
+    }
+    std::printf("## two hinted read streams (2 x 16 GB) + 1/keep of the 128-byte lines of one of them rewritten whole, hinted,\n");
+    std::printf("## the lines chosen in runs of G consecutive lines; time added to the two reads, per line and per run\n");
+    TIME(hipLaunchKernelGGL((k_lines<1, false>), dim3(nwg), dim3(256), 0, 0, dst, src, 1u, sink));
+    const float t_two = ms;
+    std::printf("the two reads alone: %.3f ms = %.0f GB/s\n", t_two, N * 4 / (t_two * 1e-3) / 1e9);
+    for (uint32_t keep : {2u, 4u, 16u, 64u}) {
+        const double lines = (double)N / 64 / keep;
+        float t[5];
+        TIME(hipLaunchKernelGGL((k_lines<1, true>), dim3(nwg), dim3(256), 0, 0, dst, src, keep, sink)); t[0] = ms - t_two;
+        TIME(hipLaunchKernelGGL((k_lines<4, true>), dim3(nwg), dim3(256), 0, 0, dst, src, keep, sink)); t[1] = ms - t_two;
+        TIME(hipLaunchKernelGGL((k_lines<16, true>), dim3(nwg), dim3(256), 0, 0, dst, src, keep, sink)); t[2] = ms - t_two;
+        TIME(hipLaunchKernelGGL((k_lines<64, true>), dim3(nwg), dim3(256), 0, 0, dst, src, keep, sink)); t[3] = ms - t_two;
+        TIME(hipLaunchKernelGGL((k_lines<256, true>), dim3(nwg), dim3(256), 0, 0, dst, src, keep, sink)); t[4] = ms - t_two;
+        std::printf("1/%-3u %6.1f M lines |", keep, lines / 1e6);
+        const int g[5] = {1, 4, 16, 64, 256};
+        for (int i = 0; i < 5; ++i)
+            std::printf(" G=%-3d +%6.3f ms %5.1f ps/line %6.0f ps/run |", g[i], t[i], t[i] * 1e9 / lines, t[i] * 1e9 / (lines / g[i]));
+        std::printf("\n");
     }
     CK(hipDeviceSynchronize());
     std::printf("done\n");
