@@ -316,7 +316,7 @@ int srs_unpack_dense_multi(srs_ctx *ctx, srs_plan *plan, const srs_tensor *t, co
 
 /*
  * Measurement aid (not part of the method): reads `bytes` bytes from each of a and b with the same
- * 16-byte streaming loads and launch shape as extract and writes one word per workgroup to `sink`
+ * 16-byte streaming loads (non-temporal hint) and launch shape as extract and writes one word per workgroup to `sink`
  * (at least srs_stream_probe_sink_words(bytes) uint32).  Gives the box's achievable two-stream read
  * bandwidth, the practical ceiling for extract.  a, b 16-byte aligned; bytes a multiple of 16.
  */
