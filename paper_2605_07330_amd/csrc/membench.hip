@@ -72,6 +72,25 @@ __global__ __launch_bounds__(256) void k_mix(uint16_t *dst, const uint16_t *src,
     if (READ && (acc.x ^ acc.y ^ acc.z ^ acc.w) == 0x12345u) sink[0] = 1;
 }
 
+// dst <- src, 16 bytes per lane and step, loads and stores with or without the non-temporal hint
+template <bool HINT>
+__global__ __launch_bounds__(256) void k_copy(uint16_t *dst, const uint16_t *src) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const uint64_t tile = (uint64_t)blockIdx.x * 16384;
+    const uint32_t e0 = wave * 4096 + lane * 8;
+    u32x4 x[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+        const u32x4 *p = reinterpret_cast<const u32x4 *>(src + tile + e0 + j * 512);
+        x[j] = HINT ? __builtin_nontemporal_load(p) : *p;
+    }
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+        u32x4 *q = reinterpret_cast<u32x4 *>(dst + tile + e0 + j * 512);
+        if (HINT) __builtin_nontemporal_store(x[j], q); else *q = x[j];
+    }
+}
+
 // UNIT = 4: read, change and rewrite each chosen 64-byte block (4 lanes x 16 bytes); UNIT = 8: each 128-byte
 // line that holds a chosen block; UNIT = 0: only read the chosen blocks.
 template <int UNIT>
@@ -158,6 +177,10 @@ int main() {
     std::printf("write only (dense 16-byte stores): %.3f ms = %.0f GB/s\n", ms, N * 2 / (ms * 1e-3) / 1e9);
     TIME(hipLaunchKernelGGL((k_mix<3, true>), dim3(nwg), dim3(256), 0, 0, dst, src, 1u, sink));
     std::printf("read + dense write: %.3f ms = %.0f GB/s (both directions)\n", ms, N * 4 / (ms * 1e-3) / 1e9);
+    TIME(hipLaunchKernelGGL((k_copy<false>), dim3(nwg), dim3(256), 0, 0, dst, src));
+    std::printf("copy, ordinary loads and stores: %.3f ms = %.0f GB/s (both directions)\n", ms, N * 4 / (ms * 1e-3) / 1e9);
+    TIME(hipLaunchKernelGGL((k_copy<true>), dim3(nwg), dim3(256), 0, 0, dst, src));
+    std::printf("copy, hinted loads and stores: %.3f ms = %.0f GB/s (both directions)\n", ms, N * 4 / (ms * 1e-3) / 1e9);
 
     std::printf("## sparse block writes: 1/keep of the 64-byte blocks of a 16 GB buffer\n");
     std::printf("%-5s %-9s %-10s | %-22s | %-22s | %-26s | %-26s\n", "keep", "blocks", "128B lines", "2B stores alone",
