@@ -8,7 +8,8 @@
 //      apply cost, and why they cost the same whatever the store width: the memory side pays per
 //      128-byte line touched);
 //   4. the same sparse blocks updated by an explicit read-modify-write of the whole 64-byte block or 128-byte
-//      line in the kernel (no cheaper than the masked 2-byte store, so the scatter keeps its 2-byte stores);
+//      line in the kernel, with ordinary or hinted accesses (no cheaper than the masked 2-byte store, so the scatter
+//      keeps its 2-byte stores);
 //   5. what extract's snapshot refresh does now -- both buffers streamed with the non-temporal hint, chosen 128-byte
 //      lines of one of them rewritten whole with the hint -- with the same number of lines chosen one by one or in
 //      runs of 4 .. 256 consecutive lines (how much of the cost goes with the line and how much with the stretch of
@@ -93,7 +94,7 @@ __global__ __launch_bounds__(256) void k_copy(uint16_t *dst, const uint16_t *src
 
 // UNIT = 4: read, change and rewrite each chosen 64-byte block (4 lanes x 16 bytes); UNIT = 8: each 128-byte
 // line that holds a chosen block; UNIT = 0: only read the chosen blocks.
-template <int UNIT>
+template <int UNIT, bool HINT = false>
 __global__ __launch_bounds__(256) void k_rmw(uint16_t *dst, uint32_t keep, uint32_t *sink) {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const uint64_t tile = (uint64_t)blockIdx.x * 16384;
@@ -107,9 +108,9 @@ __global__ __launch_bounds__(256) void k_rmw(uint16_t *dst, uint32_t keep, uint3
         if (UNIT == 8) hit = hit || ((((blk ^ 1u) * 2654435761u) >> 8) % keep == 0);
         if (hit) {
             u32x4 *p = reinterpret_cast<u32x4 *>(dst + tile + e);
-            u32x4 v = *p;
+            u32x4 v = HINT ? __builtin_nontemporal_load(p) : *p;
             if (UNIT == 0) acc ^= v.x ^ v.w;
-            else { v.x ^= blk; *p = v; }
+            else { v.x ^= blk; if (HINT) __builtin_nontemporal_store(v, p); else *p = v; }
         }
     }
     if (UNIT == 0 && acc == 0x12345u) sink[0] = 1;
@@ -198,18 +199,19 @@ int main() {
                     (t3 - t_read) * 1e9 / lines, t4 - t_read, (t4 - t_read) * 1e9 / lines);
     }
     std::printf("## the same sparse blocks by explicit read-modify-write in the kernel (no other traffic)\n");
-    std::printf("%-5s %-10s | %-22s | %-22s | %-22s | %-22s\n", "keep", "128B lines", "2B stores", "RMW of 64B blocks",
-                "RMW of 128B lines", "reads of 64B blocks only");
+    std::printf("%-5s %-10s | %-22s | %-22s | %-22s | %-22s | %-22s\n", "keep", "128B lines", "2B stores", "RMW of 64B blocks",
+                "RMW of 128B lines", "reads of 64B blocks only", "RMW of 128B lines, hinted");
     for (uint32_t keep : {2u, 4u, 8u, 16u}) {
         const double lines = (double)N / 64 * (1.0 - (1.0 - 1.0 / keep) * (1.0 - 1.0 / keep));
-        float t1, t2, t3, t4;
+        float t1, t2, t3, t4, t5;
         TIME(hipLaunchKernelGGL((k_mix<1, false>), dim3(nwg), dim3(256), 0, 0, dst, src, keep, sink)); t1 = ms;
         TIME(hipLaunchKernelGGL((k_rmw<4>), dim3(nwg), dim3(256), 0, 0, dst, keep, sink)); t2 = ms;
         TIME(hipLaunchKernelGGL((k_rmw<8>), dim3(nwg), dim3(256), 0, 0, dst, keep, sink)); t3 = ms;
         TIME(hipLaunchKernelGGL((k_rmw<0>), dim3(nwg), dim3(256), 0, 0, dst, keep, sink)); t4 = ms;
-        std::printf("1/%-3u %6.1f M   | %6.3f ms %5.1f ps/line | %6.3f ms %5.1f ps/line | %6.3f ms %5.1f ps/line | %6.3f ms %5.1f ps/line\n",
+        TIME(hipLaunchKernelGGL((k_rmw<8, true>), dim3(nwg), dim3(256), 0, 0, dst, keep, sink)); t5 = ms;
+        std::printf("1/%-3u %6.1f M   | %6.3f ms %5.1f ps/line | %6.3f ms %5.1f ps/line | %6.3f ms %5.1f ps/line | %6.3f ms %5.1f ps/line | %6.3f ms %5.1f ps/line\n",
                     keep, lines / 1e6, t1, t1 * 1e9 / lines, t2, t2 * 1e9 / lines, t3, t3 * 1e9 / lines, t4,
-                    t4 * 1e9 / lines);
+                    t4 * 1e9 / lines, t5, t5 * 1e9 / lines);
     }
     std::printf("## two hinted read streams (2 x 16 GB) + 1/keep of the 128-byte lines of one of them rewritten whole, hinted,\n");
     std::printf("## the lines chosen in runs of G consecutive lines; time added to the two reads, per line and per run\n");
