@@ -35,6 +35,7 @@ HBM_PEAK_GBS = 8000.0
 # of changed values: the memory side charges a sparse store by the line it touches, and a whole line costs it
 # less than a part of one).
 MEASURED_TRAFFIC_BYTES = {"qwen3-30b-a3b": 153.3e9}
+MEASURED_TRAFFIC_SPLIT = {"qwen3-30b-a3b": (122.4e9, 30.9e9)}     # read, written
 
 
 def log(msg: str) -> None:
@@ -660,7 +661,11 @@ def main() -> int:
         "read_probe_gbs": None if probe_gbs is None else round(probe_gbs, 1),
         "roofline": {"bound": "hbm", "kernel": "extract_kernel", "achieved": round(ach, 1), "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": round(ach / HBM_PEAK_GBS, 4),
-                     "traffic": MEASURED_TRAFFIC_BYTES.get(wl.name) if default_run else None},
+                     "traffic": MEASURED_TRAFFIC_BYTES.get(wl.name) if default_run else None,
+                     # nothing is read twice (2N = 122.1 GB of weights); the excess over the algorithmic bytes is the
+                     # snapshot's changed lines written whole, which is the cheaper way to write them
+                     "traffic_read": MEASURED_TRAFFIC_SPLIT[wl.name][0] if default_run and wl.name in MEASURED_TRAFFIC_SPLIT else None,
+                     "traffic_written": MEASURED_TRAFFIC_SPLIT[wl.name][1] if default_run and wl.name in MEASURED_TRAFFIC_SPLIT else None},
         "cpu_baseline": cpu,
         "rotating_snapshot": rotating,
         "checked": not args.no_check,
