@@ -12,10 +12,11 @@
 //   scan + an LDS combine across the four waves, chains tiles of the same bucket with a
 //   decoupled look-back on one 64-bit {flag, value} status word per tile, stages the
 //   (index, value) pairs of the tile in LDS in rank order and writes them out coalesced
-//   (Alg. 2: V = W[I], I int32 ascending), refreshing the snapshot at the same positions.
+//   (Alg. 2: V = W[I], I int32 ascending).  The snapshot is refreshed in the same pass: every 128-byte line of
+//   it that holds a change is rewritten whole from the new weights the lanes hold (RG = 8), or each changed
+//   element is stored by itself (RG = 0), or nothing is written for callers that rotate buffers (RG = -1).
 //   Template flavours of the same kernel: SRC = FP32 master weights rounded to BF16 on the fly (the
-//   cast-and-copy of Alg. 1 fused with its diff); EB = 1 for one-byte (FP8) patterns; RG = -1 leaves the
-//   snapshot untouched for callers that rotate buffers.
+//   cast-and-copy of Alg. 1 fused with its diff); EB = 1 for one-byte (FP8) patterns.
 // mark_kernel: one optimizer step of Alg. 1's index accumulation, OR-ed into a bitmap.
 // extract_marked_kernel: the payload of the accumulated index set, gathered through the bitmap.
 // apply_kernel: the scatter of Alg. 3, W[I] <- V, one workgroup per (bucket, payload chunk).
