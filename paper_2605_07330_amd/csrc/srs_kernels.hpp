@@ -1030,18 +1030,46 @@ __global__ __launch_bounds__(kThreads) void encode_indices_kernel(const ApplyArg
     const int64_t base = (int64_t)((uint64_t)b * a.base_stride);
     uint32_t gap = 0;
     bool bad = false;
+    uint16_t *const Db = D + (uint64_t)b * a.cap;
+    const uint32_t k0 = threadIdx.x * kApplyPer;
+    static_assert(kApplyPer == 8, "eight consecutive pairs per thread: two 16-byte loads, one 16-byte store");
+    // cap is a multiple of 4 whenever the rows of I are 16-byte aligned for every bucket; checked on the addresses
+    const bool vec = (((uintptr_t)(Ib + start) | (uintptr_t)(Db + start)) & 15u) == 0;       // uniform over the workgroup
+    if (vec && k0 + kApplyPer <= nvalid) {
+        const uint64_t r0 = start + k0;
+        const u32x4 lo = *reinterpret_cast<const u32x4 *>(Ib + r0), hi = *reinterpret_cast<const u32x4 *>(Ib + r0 + 4);
+        const int32_t idx[8] = {(int32_t)lo.x, (int32_t)lo.y, (int32_t)lo.z, (int32_t)lo.w,
+                                (int32_t)hi.x, (int32_t)hi.y, (int32_t)hi.z, (int32_t)hi.w};
+        int64_t prev = r0 ? ((int64_t)Ib[r0 - 1] - base) : 0;
+        uint32_t d16[8];
 #pragma unroll
-    for (int j = 0; j < kApplyPer; ++j) {
-        const uint32_t k = threadIdx.x + j * kThreads;
-        if (k >= nvalid) continue;
-        const uint64_t r = start + k;
-        const int64_t cur = (int64_t)Ib[r] - base;
-        const int64_t prev = r ? ((int64_t)Ib[r - 1] - base) : 0;
-        int64_t dd = cur - prev;
-        if (dd < 0 || cur < 0) { bad = true; dd = 0xFFFFFFFFll; }
-        D[(uint64_t)b * a.cap + r] = (uint16_t)((uint64_t)dd & 0xFFFFu);
-        gap = ((uint64_t)dd > gap) ? (uint32_t)dd : gap;
-        if (k == 0) anchors[(uint64_t)b * a.chunks_per_bucket + (uint32_t)(start / kApplyChunk)] = (int32_t)cur;
+        for (int j = 0; j < 8; ++j) {
+            const int64_t cur = (int64_t)idx[j] - base;
+            int64_t dd = cur - prev;
+            if (dd < 0 || cur < 0) { bad = true; dd = 0xFFFFFFFFll; }
+            d16[j] = (uint32_t)((uint64_t)dd & 0xFFFFu);
+            gap = ((uint64_t)dd > gap) ? (uint32_t)dd : gap;
+            prev = cur;
+        }
+        u32x4 out;
+        out.x = d16[0] | (d16[1] << 16); out.y = d16[2] | (d16[3] << 16);
+        out.z = d16[4] | (d16[5] << 16); out.w = d16[6] | (d16[7] << 16);
+        *reinterpret_cast<u32x4 *>(Db + r0) = out;
+        if (k0 == 0) anchors[(uint64_t)b * a.chunks_per_bucket + (uint32_t)(start / kApplyChunk)] = (int32_t)((int64_t)idx[0] - base);
+    } else {
+#pragma unroll
+        for (int j = 0; j < kApplyPer; ++j) {            // the chunk's ragged end, or rows that are not 16-byte aligned
+            const uint32_t k = vec ? (k0 + j) : (threadIdx.x + j * kThreads);
+            if (k >= nvalid) continue;
+            const uint64_t r = start + k;
+            const int64_t cur = (int64_t)Ib[r] - base;
+            const int64_t prev = r ? ((int64_t)Ib[r - 1] - base) : 0;
+            int64_t dd = cur - prev;
+            if (dd < 0 || cur < 0) { bad = true; dd = 0xFFFFFFFFll; }
+            Db[r] = (uint16_t)((uint64_t)dd & 0xFFFFu);
+            gap = ((uint64_t)dd > gap) ? (uint32_t)dd : gap;
+            if (k == 0) anchors[(uint64_t)b * a.chunks_per_bucket + (uint32_t)(start / kApplyChunk)] = (int32_t)cur;
+        }
     }
     // workgroup maximum: wave maximum by DPP-free shuffles is overkill here; use LDS atomics
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
