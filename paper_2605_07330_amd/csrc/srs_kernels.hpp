@@ -1504,17 +1504,35 @@ __global__ __launch_bounds__(kThreads) void vc_decode_kernel(const ValueCodecArg
         if (v0 < gn) {
             const uint32_t v1 = (v0 + kVcSub < gn) ? (v0 + kVcSub) : gn;  // a chunk holds a multiple of kVcSub unless it is the last
             uint32_t pos = a.sub[(slot0 + kk) * 32 + sb];
-            uint32_t pack = 0;
-            for (uint32_t i = v0; i < v1; ++i) {
+            // one value: the next kVcMaxLen stream bits index the table.  A pattern that is no code of the table has
+            // length 0: the position then stands still and the remaining values of the sub-block come out as that
+            // entry's symbol -- the flag tells the caller that the output means nothing.  (The loop is bound by
+            // instruction issue, so it carries no early exit and, for full sub-blocks, no per-value bookkeeping.)
+            auto next = [&]() -> uint32_t {
                 const uint32_t w = pos >> 5, sh = pos & 31;
                 uint32_t x = 0;
                 if (w < kVcSlotWords) x = (uint32_t)((((unsigned long long)s_words[kk][w + 1] << 32) | s_words[kk][w]) >> sh);
                 const uint32_t e = s_lut[x & ((1u << kVcMaxLen) - 1u)];
-                if ((e & 15u) == 0) { bad = true; break; }                // not a code of this table
+                bad = bad || (e & 15u) == 0;
                 pos += e & 15u;
-                const uint32_t it = i - v0;
-                pack |= (e >> 4) << (8u * (it & 3u));
-                if ((it & 3u) == 3u || i + 1 == v1) { s_sym[(it >> 2) * kSymPitch + s] = pack; pack = 0; }
+                return e >> 4;
+            };
+            if (v1 - v0 == kVcSub) {
+#pragma unroll 4
+                for (uint32_t q = 0; q < kVcSub / 4; ++q) {
+                    uint32_t pack = next();
+                    pack |= next() << 8;
+                    pack |= next() << 16;
+                    pack |= next() << 24;
+                    s_sym[q * kSymPitch + s] = pack;
+                }
+            } else {
+                uint32_t pack = 0;
+                for (uint32_t i = v0; i < v1; ++i) {
+                    const uint32_t it = i - v0;
+                    pack |= next() << (8u * (it & 3u));
+                    if ((it & 3u) == 3u || i + 1 == v1) { s_sym[(it >> 2) * kSymPitch + s] = pack; pack = 0; }
+                }
             }
         }
     }
