@@ -1419,6 +1419,7 @@ __global__ __launch_bounds__(kThreads) void vc_decode_kernel(const ValueCodecArg
     __shared__ uint16_t s_lut[1u << kVcMaxLen];      // symbol << 4 | length
     __shared__ uint32_t s_cnt[kVcMaxLen + 1][kWaves];
     __shared__ uint8_t s_sorted[256];                // symbols in (length, symbol) order
+    __shared__ uint32_t s_first[kVcMaxLen + 2], s_off[kVcMaxLen + 2];   // per length: first code, start in s_sorted
     __shared__ uint32_t s_words[kVcDecodeChunks][kVcSlotWords + 1];
     // decoded high bytes: value q*4 + c of thread t is byte c of word q * kSymPitch + t (the odd pitch keeps both
     // the decoders' stores and the write-out's loads off each other's LDS banks)
@@ -1468,7 +1469,9 @@ __global__ __launch_bounds__(kThreads) void vc_decode_kernel(const ValueCodecArg
     __syncthreads();
     // Per length j: how many symbols have it, the first code of that length and where its symbols start in the
     // list of symbols sorted by (length, symbol) -- every thread keeps the three small tables in registers.
-    uint32_t cnt_j[kVcMaxLen + 1], first_j[kVcMaxLen + 1], off_j[kVcMaxLen + 1];
+    // end_j[j]: one past the last code of length j, left-aligned to kVcMaxLen bits.  The runs of canonical codes of
+    // the lengths 1, 2, ... follow one another in that space, so end_j never decreases.
+    uint32_t off_j[kVcMaxLen + 1], end_j[kVcMaxLen + 1];
     {
         uint32_t code = 0, off = 0;
 #pragma unroll
@@ -1476,23 +1479,27 @@ __global__ __launch_bounds__(kThreads) void vc_decode_kernel(const ValueCodecArg
             uint32_t cj = 0;
 #pragma unroll
             for (int w = 0; w < kWaves; ++w) { cj += s_cnt[j][w]; if (j == l && w < wave) rank += s_cnt[j][w]; }
-            cnt_j[j] = cj; first_j[j] = code; off_j[j] = off;
+            off_j[j] = off; end_j[j] = (code + cj) << (kVcMaxLen - j);
+            if (s == j) { s_first[j] = code; s_off[j] = off; }
             code = (code + cj) << 1; off += cj;
         }
+        if (s == 0) { s_first[kVcMaxLen + 1] = 0; s_off[kVcMaxLen + 1] = 0; }
     }
 #pragma unroll
     for (uint32_t j = 1; j <= kVcMaxLen; ++j)
         if (l == j) s_sorted[off_j[j] + rank] = (uint8_t)s;            // off + rank < 256: each symbol has one length
     __syncthreads();
     // Table entry i: the 12 stream bits i, first bit in bit 0, are a code word's bits most significant first;
-    // the entry's length is the one length j whose first j bits fall inside that length's run of canonical codes.
+    // the entry's length is the first length whose run ends above them (none: not a code of this table, entry 0).
     for (uint32_t i = s; i < (1u << kVcMaxLen); i += kThreads) {
         const uint32_t c12 = __brev(i) >> (32 - kVcMaxLen);
-        uint32_t e = 0;
+        uint32_t len = 1;
 #pragma unroll
-        for (uint32_t j = kVcMaxLen; j >= 1; --j) {                    // descending, so that the shortest match is kept
-            const uint32_t d = (c12 >> (kVcMaxLen - j)) - first_j[j];  // wraps to a huge value below the run
-            if (d < cnt_j[j]) e = ((uint32_t)s_sorted[off_j[j] + d] << 4) | j;
+        for (uint32_t j = 1; j <= kVcMaxLen; ++j) len += (c12 >= end_j[j]) ? 1u : 0u;
+        uint32_t e = 0;
+        if (len <= kVcMaxLen) {
+            const uint32_t d = (c12 >> (kVcMaxLen - len)) - s_first[len];      // below the count of that length
+            e = ((uint32_t)s_sorted[(s_off[len] + d) & 255u] << 4) | len;
         }
         s_lut[i] = (uint16_t)e;
     }
