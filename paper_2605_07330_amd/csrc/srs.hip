@@ -962,7 +962,7 @@ int srs_encode_values(srs_ctx *ctx, const uint16_t *V, const uint32_t *counts, u
     const uint64_t nh = (uint64_t)nbuckets * 256;
     hipLaunchKernelGGL(zero_strided_kernel, dim3((uint32_t)((nh + 255) / 256)), dim3(256), 0, st, a.hist, nh, 1u);
     SRS_HIP(hipGetLastError());
-    const dim3 grid((uint32_t)((uint64_t)nbuckets * nchunk));
+    const dim3 grid((uint32_t)((uint64_t)nbuckets * ((nchunk + kVcEncodeChunks - 1) / kVcEncodeChunks)));
     const dim3 hist_grid((uint32_t)((uint64_t)nbuckets * ((nchunk + kVcHistChunks - 1) / kVcHistChunks)));
     hipLaunchKernelGGL(vc_hist_kernel, hist_grid, dim3(kThreads), 0, st, a);
     SRS_HIP(hipGetLastError());

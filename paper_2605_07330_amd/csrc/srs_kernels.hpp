@@ -1332,80 +1332,94 @@ __global__ __launch_bounds__(kThreads) void vc_build_kernel(const ValueCodecArgs
     a.rcode[(uint64_t)b * 256 + s] = l ? (__brev(c) >> (32 - l)) : 0u;
 }
 
-// per (bucket, chunk): codes of 8 consecutive values per thread, assembled in a 128-bit buffer, placed in
-// the chunk's LDS bit array at the offset a workgroup scan of the bit counts gives, then stored coalesced
+// per (bucket, group of kVcEncodeChunks chunks), chunk after chunk with the bucket's code table loaded once: codes of
+// 8 consecutive values per thread, assembled in a 128-bit buffer, placed in the chunk's LDS bit array at the offset a
+// workgroup scan of the bit counts gives, then stored coalesced
+constexpr uint32_t kVcEncodeChunks = 4;
+
 __global__ __launch_bounds__(kThreads) void vc_encode_kernel(const ValueCodecArgs a) {
-    __shared__ uint32_t s_rcode[256];
-    __shared__ uint8_t s_len[256];
+    __shared__ uint32_t s_code[256];                 // bit-reversed code | length << 16
     __shared__ uint32_t s_words[kVcSlotWords + 4];
     __shared__ uint32_t s_wave[kWaves];
-    const uint32_t b = blockIdx.x / a.nchunk, k = blockIdx.x - b * a.nchunk;
+    const uint32_t groups = (a.nchunk + kVcEncodeChunks - 1) / kVcEncodeChunks;
+    const uint32_t b = blockIdx.x / groups, g = blockIdx.x - b * groups;
     const uint64_t cnt = ((uint64_t)a.counts[b] < a.cap) ? a.counts[b] : a.cap;
-    const uint64_t r0 = (uint64_t)k * kVcChunk;
-    const uint64_t slot = (uint64_t)b * a.nchunk + k;
-    if (r0 >= cnt) { if (threadIdx.x == 0) a.chunk_words[slot] = 0; return; }
-    const uint32_t n = (uint32_t)((cnt - r0 < kVcChunk) ? (cnt - r0) : kVcChunk);
-    s_rcode[threadIdx.x] = a.rcode[(uint64_t)b * 256 + threadIdx.x];
-    s_len[threadIdx.x] = a.lens[(uint64_t)b * 256 + threadIdx.x];
-    for (uint32_t i = threadIdx.x; i < kVcSlotWords + 4; i += kThreads) s_words[i] = 0;
-    __syncthreads();
-    const uint16_t *v = a.V + (uint64_t)b * a.cap + r0;
-    uint8_t *lo = a.low + (uint64_t)b * a.cap + r0;
-    const uint32_t k0 = threadIdx.x * 8;
-    unsigned long long buf0 = 0, buf1 = 0;          // 128-bit bit buffer, stream order = ascending bit index
-    uint32_t nbits = 0;
-    // the thread's 8 values: one 16-byte load and one 8-byte store of the low bytes where the rows allow it
-    uint32_t xs[8];
-    const bool vec = (k0 + 8 <= n) && (((((uintptr_t)(v + k0)) & 15u) | (((uintptr_t)(lo + k0)) & 7u)) == 0);
-    if (vec) {
-        const u32x4 q = *reinterpret_cast<const u32x4 *>(v + k0);
-        xs[0] = q.x & 0xFFFFu; xs[1] = q.x >> 16; xs[2] = q.y & 0xFFFFu; xs[3] = q.y >> 16;
-        xs[4] = q.z & 0xFFFFu; xs[5] = q.z >> 16; xs[6] = q.w & 0xFFFFu; xs[7] = q.w >> 16;
-        uint2 lb;
-        lb.x = (xs[0] & 0xFFu) | ((xs[1] & 0xFFu) << 8) | ((xs[2] & 0xFFu) << 16) | ((xs[3] & 0xFFu) << 24);
-        lb.y = (xs[4] & 0xFFu) | ((xs[5] & 0xFFu) << 8) | ((xs[6] & 0xFFu) << 16) | ((xs[7] & 0xFFu) << 24);
-        *reinterpret_cast<uint2 *>(lo + k0) = lb;
-    } else {
-#pragma unroll
-        for (int j = 0; j < 8; ++j) {
-            xs[j] = (k0 + j < n) ? (uint32_t)v[k0 + j] : 0u;
-            if (k0 + j < n) lo[k0 + j] = (uint8_t)(xs[j] & 0xFFu);
-        }
-    }
-#pragma unroll
-    for (int j = 0; j < 8; ++j) {
-        if (k0 + j < n) {
-            const uint32_t x = xs[j];
-            const uint32_t sym = x >> 8, l = s_len[sym];
-            const unsigned long long rc = s_rcode[sym];
-            if (nbits < 64) { buf0 |= rc << nbits; if (nbits + l > 64) buf1 |= rc >> (64 - nbits); }
-            else buf1 |= rc << (nbits - 64);
-            nbits += l;
-        }
+    const uint32_t k_lo = g * kVcEncodeChunks;
+    const uint32_t k_hi = (k_lo + kVcEncodeChunks < a.nchunk) ? (k_lo + kVcEncodeChunks) : a.nchunk;
+    if ((uint64_t)k_lo * kVcChunk < cnt) {
+        s_code[threadIdx.x] = a.rcode[(uint64_t)b * 256 + threadIdx.x] | ((uint32_t)a.lens[(uint64_t)b * 256 + threadIdx.x] << 16);
+        __syncthreads();
     }
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const uint32_t inc = wave_inclusive_scan(nbits);
-    if (lane == 63) s_wave[wave] = inc;
-    __syncthreads();
-    uint32_t start = inc - nbits, total = 0;
+    for (uint32_t k = k_lo; k < k_hi; ++k) {
+        const uint64_t r0 = (uint64_t)k * kVcChunk;
+        const uint64_t slot = (uint64_t)b * a.nchunk + k;
+        if (r0 >= cnt) {                                 // uniform: a chunk without values
+            if (threadIdx.x == 0) a.chunk_words[slot] = 0;
+            continue;
+        }
+        const uint32_t n = (uint32_t)((cnt - r0 < kVcChunk) ? (cnt - r0) : kVcChunk);
+        const uint16_t *v = a.V + (uint64_t)b * a.cap + r0;
+        uint8_t *lo = a.low + (uint64_t)b * a.cap + r0;
+        const uint32_t k0 = threadIdx.x * 8;
+        // the thread's 8 values: one 16-byte load and one 8-byte store of the low bytes where the rows allow it
+        uint32_t xs[8];
+        const bool vec = (k0 + 8 <= n) && (((((uintptr_t)(v + k0)) & 15u) | (((uintptr_t)(lo + k0)) & 7u)) == 0);
+        if (vec) {
+            const u32x4 q = *reinterpret_cast<const u32x4 *>(v + k0);
+            xs[0] = q.x & 0xFFFFu; xs[1] = q.x >> 16; xs[2] = q.y & 0xFFFFu; xs[3] = q.y >> 16;
+            xs[4] = q.z & 0xFFFFu; xs[5] = q.z >> 16; xs[6] = q.w & 0xFFFFu; xs[7] = q.w >> 16;
+            uint2 lb;
+            lb.x = (xs[0] & 0xFFu) | ((xs[1] & 0xFFu) << 8) | ((xs[2] & 0xFFu) << 16) | ((xs[3] & 0xFFu) << 24);
+            lb.y = (xs[4] & 0xFFu) | ((xs[5] & 0xFFu) << 8) | ((xs[6] & 0xFFu) << 16) | ((xs[7] & 0xFFu) << 24);
+            *reinterpret_cast<uint2 *>(lo + k0) = lb;
+        } else {
 #pragma unroll
-    for (int w = 0; w < kWaves; ++w) { start += (w < wave) ? s_wave[w] : 0u; total += s_wave[w]; }
-    if ((threadIdx.x & 7) == 0 && k0 < n) a.sub[slot * 32 + (threadIdx.x >> 3)] = (uint16_t)start;
-    if (nbits) {
-        const uint32_t w = start >> 5, sh = start & 31;
-        // the thread's bits shifted to their place: up to 96 + 31 bits -> four words
-        const uint32_t p0 = (uint32_t)buf0, p1 = (uint32_t)(buf0 >> 32), p2 = (uint32_t)buf1, p3 = (uint32_t)(buf1 >> 32);
-        atomicOr(&s_words[w], p0 << sh);
-        atomicOr(&s_words[w + 1], sh ? ((p0 >> (32 - sh)) | (p1 << sh)) : p1);
-        atomicOr(&s_words[w + 2], sh ? ((p1 >> (32 - sh)) | (p2 << sh)) : p2);
-        atomicOr(&s_words[w + 3], sh ? ((p2 >> (32 - sh)) | (p3 << sh)) : p3);
-        if (sh && (p3 >> (32 - sh))) atomicOr(&s_words[w + 4], p3 >> (32 - sh));
+            for (int j = 0; j < 8; ++j) {
+                xs[j] = (k0 + j < n) ? (uint32_t)v[k0 + j] : 0u;
+                if (k0 + j < n) lo[k0 + j] = (uint8_t)(xs[j] & 0xFFu);
+            }
+        }
+        // two halves of four codes each (at most 48 bits per half), joined into a 128-bit buffer afterwards;
+        // stream order = ascending bit index
+        unsigned long long half[2] = {0, 0};
+        uint32_t hbits[2] = {0, 0};
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            if (k0 + j < n) {
+                const uint32_t c = s_code[xs[j] >> 8];
+                half[j >> 2] |= (unsigned long long)(c & 0xFFFFu) << hbits[j >> 2];
+                hbits[j >> 2] += c >> 16;
+            }
+        }
+        const uint32_t nbits = hbits[0] + hbits[1];
+        const unsigned long long buf0 = half[0] | (half[1] << hbits[0]);                       // hbits[0] <= 48
+        const unsigned long long buf1 = hbits[0] ? (half[1] >> (64 - hbits[0])) : 0ull;
+        const uint32_t inc = wave_inclusive_scan(nbits);
+        if (lane == 63) s_wave[wave] = inc;
+        __syncthreads();                                // also: every thread is done with the previous chunk's s_words
+        uint32_t start = inc - nbits, total = 0;
+#pragma unroll
+        for (int w = 0; w < kWaves; ++w) { start += (w < wave) ? s_wave[w] : 0u; total += s_wave[w]; }
+        const uint32_t used = (total + 31) / 32;         // at most kVcSlotWords: 2048 codes of at most kVcMaxLen bits
+        for (uint32_t i = threadIdx.x; i < used + 4; i += kThreads) s_words[i] = 0;     // what this chunk can touch
+        __syncthreads();
+        if ((threadIdx.x & 7) == 0 && k0 < n) a.sub[slot * 32 + (threadIdx.x >> 3)] = (uint16_t)start;
+        if (nbits) {
+            const uint32_t w = start >> 5, sh = start & 31;
+            // the thread's bits shifted to their place: up to 96 + 31 bits -> four words
+            const uint32_t p0 = (uint32_t)buf0, p1 = (uint32_t)(buf0 >> 32), p2 = (uint32_t)buf1, p3 = (uint32_t)(buf1 >> 32);
+            atomicOr(&s_words[w], p0 << sh);
+            atomicOr(&s_words[w + 1], sh ? ((p0 >> (32 - sh)) | (p1 << sh)) : p1);
+            atomicOr(&s_words[w + 2], sh ? ((p1 >> (32 - sh)) | (p2 << sh)) : p2);
+            atomicOr(&s_words[w + 3], sh ? ((p2 >> (32 - sh)) | (p3 << sh)) : p3);
+            if (sh && (p3 >> (32 - sh))) atomicOr(&s_words[w + 4], p3 >> (32 - sh));
+        }
+        __syncthreads();
+        uint32_t *out = a.bits + slot * kVcSlotWords;
+        for (uint32_t i = threadIdx.x; i < used; i += kThreads) out[i] = s_words[i];
+        if (threadIdx.x == 0) a.chunk_words[slot] = used;
     }
-    __syncthreads();
-    const uint32_t used = (total + 31) / 32;
-    uint32_t *out = a.bits + slot * kVcSlotWords;
-    for (uint32_t i = threadIdx.x; i < used; i += kThreads) out[i] = s_words[i];
-    if (threadIdx.x == 0) a.chunk_words[slot] = used;
 }
 
 // per (bucket, group of kVcDecodeChunks chunks): rebuild the code from its lengths, fill a 4096-entry table
