@@ -326,6 +326,13 @@ def test_invalid_arguments_are_rejected_before_launch(srs, ctx):
         ctx.plan([1 << 31], 64)
     with pytest.raises(srs.SrsError):
         ctx.set_option(srs.OPT_TILE_ELEMS, 1000)
+    for opt, bad in [(srs.OPT_REFRESH_GROUP, 4), (srs.OPT_REFRESH_GROUP, 16), (srs.OPT_INTERLEAVE, 0), (srs.OPT_INTERLEAVE, 5000),
+                     (srs.OPT_SNAPSHOT, 2), (srs.OPT_SPIN_LIMIT, 0), (99, 1)]:
+        with pytest.raises(srs.SrsError) as e:
+            ctx.set_option(opt, bad)
+        assert e.value.code == srs.ERR_INVALID
+    for opt, good in [(srs.OPT_REFRESH_GROUP, 0), (srs.OPT_REFRESH_GROUP, 8), (srs.OPT_SNAPSHOT, 0)]:
+        ctx.set_option(opt, good)
     # empty inputs are fine and write nothing
     e = torch.empty(0, dtype=torch.bfloat16, device=DEV)
     ctx.extract(e, e.clone(), 64, I, V, counts, 64)
