@@ -48,3 +48,14 @@ def test_host_side_argument_checks_need_no_gpu():
     assert lib.srs_apply(None, None, 8, 8, None, None, None, 8, None) == srs.ERR_INVALID
     assert lib.srs_plan_destroy(None) == srs.ERR_INVALID
     assert lib.srs_stream_probe_sink_words(1 << 20) >= 32
+
+
+def test_a_missing_library_fails_loudly_and_nothing_stands_in_for_it(tmp_path):
+    """The binding has no fallback: without libsrs.so the import itself fails, naming the file and how to build it."""
+    import subprocess
+    import sys
+    env = dict(os.environ, SRS_LIBRARY=str(tmp_path / "no_such_libsrs.so"))
+    r = subprocess.run([sys.executable, "-c", "from paper_2605_07330_amd import srs"], capture_output=True, text=True,
+                       env=env, cwd=os.path.dirname(os.path.dirname(os.path.abspath(__file__))), timeout=300)
+    assert r.returncode != 0
+    assert "no_such_libsrs.so is missing" in r.stderr and "no fallback" in r.stderr
