@@ -163,12 +163,15 @@ def bench_cast(args, torch, srs, synth, wl, dev) -> int:
 def bench_fp8(args, torch, srs, synth, wl, dev) -> int:
     """The same tensor list at FP8 synchronisation precision (Sec. 2.1: 0.0655 % of the elements change):
     srs_extract_multi_u8 + srs_apply_multi_u8 on one-byte patterns, buckets of the same 64 MiB, first with the
-    in-place snapshot refresh, then with the rotating snapshot.  Four sampled buckets of the last step are
-    compared with the oracle."""
+    in-place snapshot refresh, then with the rotating snapshot.  CPU leg (unless --no-cpu-baseline): the oracle is
+    timed on four buckets of the last step and the GPU payload of those buckets is compared with it."""
     import dataclasses
 
     import numpy as np
-    import oracle
+    oracle = None
+    if not args.no_cpu_baseline:
+        import oracle
+    cpu = None
     wl = dataclasses.replace(wl, name=wl.name + "+fp8", bucket_elems=2 * wl.bucket_elems,
                              density=args.density or synth.FP8_DENSITY)
     N, be = wl.numel, wl.bucket_elems
@@ -221,15 +224,29 @@ def bench_fp8(args, torch, srs, synth, wl, dev) -> int:
         ok = ok and (mode == "rotate" or torch.equal(S.flat, last.flat))
         if not ok and not args.no_check:
             raise SystemExit(f"bench self-check failed (fp8, {mode}): flags={flags} counts={total} expected={nchanged}")
-        if not args.no_check:
+        if not args.no_cpu_baseline:                   # the CPU leg: the oracle timed on four buckets, the GPU payload checked against it
             ch = counts.cpu().numpy().view(np.uint32)
+            t_cpu, elems = 0.0, 0
             for b in sorted({0, nb // 3, nb // 2, nb - 1}):
                 lo, hi = b * be, min(N, (b + 1) * be)
-                oI, oV, oc, _ = oracle.extract_u8(prev.flat[lo:hi].cpu().numpy(), last.flat[lo:hi].cpu().numpy(), be, cap=cap)
+                h_old, h_new = prev.flat[lo:hi].cpu().numpy(), last.flat[lo:hi].cpu().numpy()
+                t0 = time.perf_counter()
+                oI, oV, oc, _ = oracle.extract_u8(h_old, h_new, be, cap=cap)
+                t1 = time.perf_counter()
                 c = int(oc[0])
                 if ch[b] != c or not np.array_equal(I[b, :c].cpu().numpy(), oI[0, :c]) \
                         or not np.array_equal(V[b, :c].cpu().numpy(), oV[0, :c]):
                     raise SystemExit(f"bench self-check failed (fp8, {mode}): bucket {b} differs from the oracle")
+                h_roll = prev.flat[lo:hi].cpu().numpy().copy()
+                t2 = time.perf_counter()
+                oracle.apply_u8(h_roll, be, oI, oV, oc)
+                t3 = time.perf_counter()
+                if not np.array_equal(h_roll, last.flat[lo:hi].cpu().numpy()):
+                    raise SystemExit(f"bench self-check failed (fp8, {mode}): oracle apply of bucket {b}")
+                t_cpu += (t1 - t0) + (t3 - t2); elems += hi - lo
+            if mode == "refresh-in-place":
+                cpu = {"value": round(2.0 * elems / t_cpu / 1e9, 3), "unit": "GB/s", "cores": 1, "kind": "oracle",
+                       "sample": f"{elems} one-byte elements (4 of {nb} buckets); oracle extract + apply {t_cpu:.2f}s, compute only"}
         ext = sum(e[0].elapsed_time(e[1]) for e in ev[2:]) / steps
         app = sum(e[1].elapsed_time(e[2]) for e in ev[2:]) / steps
         per_changed = 5.0 if mode == "rotate" else 6.0         # I (4) + V (1) [+ snapshot (1)]
@@ -251,7 +268,7 @@ def bench_fp8(args, torch, srs, synth, wl, dev) -> int:
            "extract_ms": m["extract_ms"], "apply_ms": m["apply_ms"],
            "roofline": {"bound": "hbm", "kernel": "extract_kernel<u8>", "achieved": m["achieved"], "peak": HBM_PEAK_GBS,
                         "unit": "GB/s", "frac": m["frac"], "traffic": None},
-           "rotating_snapshot": out_modes["rotate"], "cpu_baseline": None, "checked": not args.no_check}
+           "rotating_snapshot": out_modes["rotate"], "cpu_baseline": cpu, "checked": not args.no_check}
     print(json.dumps(out), flush=True)
     return 0
 
