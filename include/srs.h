@@ -80,7 +80,8 @@ typedef enum {
                                   1 leave it untouched: the caller rotates buffers instead, i.e. new_w IS the
                                   snapshot of the next call and the Trainer's next cast writes into the buffer
                                   that held old_snapshot (same two resident BF16 copies, no scattered stores
-                                  into the weights; Alg. 1's W_prev without the clone).  Payload identical. */
+                                  into the weights; Alg. 1's W_prev without the clone).  Payload identical.
+                                  This mode measures best with SRS_OPT_INTERLEAVE = 256. */
 
 typedef struct srs_ctx srs_ctx;    /* per-stream scratch: tile status words, per-bucket ticket counters, flag word */
 typedef struct srs_plan srs_plan;  /* immutable bucket / segment / tile tables of one tensor list */
