@@ -29,21 +29,6 @@ def build_lib(verbose: bool = False) -> str:
     return LIB
 
 
-MEMBENCH = os.path.join(HERE, "membench")
-
-
-def build_membench(verbose: bool = False) -> str:
-    """The memory-system microbenchmark (measurement aid; a plain executable, no Python)."""
-    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    cmd = [hipcc, "--offload-arch=gfx950", "-O3", "-std=c++17", "-Xclang", "-target-feature", "-Xclang",
-           "-packed-fp32-ops", "-Wno-unused-command-line-argument", os.path.join(HERE, "csrc", "membench.hip"),
-           "-o", MEMBENCH]
-    if verbose:
-        print(" ".join(cmd), flush=True)
-    subprocess.check_call(cmd)
-    return MEMBENCH
-
-
 C_CONSUMER_SRC = os.path.join(ROOT, "tests", "c_abi", "roundtrip.c")
 C_CONSUMER = os.path.join(ROOT, "tests", "c_abi", "roundtrip")
 
@@ -70,6 +55,5 @@ def is_stale() -> bool:
 
 if __name__ == "__main__":
     build_lib(verbose=True)
-    build_membench(verbose=True)
     build_c_consumer(verbose=True)
     print(LIB)

@@ -1,6 +1,7 @@
 // Host side of libsrs.so: argument checks, bucket / segment / tile tables, launches.
 // The operations and their conventions are documented in include/srs.h.
 #include "srs.h"
+#include "device_guard.hpp"
 #include "srs_kernels.hpp"
 
 #include <hip/hip_runtime.h>
@@ -23,19 +24,12 @@ constexpr uint64_t kMaxIndexable = 0x7fffffffull;   // int32 indices (Sec. 3.2: 
     } while (0)
 
 // Makes `device` current for the rest of the enclosing scope and puts the caller's device back afterwards.
-struct DeviceGuard {
-    int prev = -1, target;
-    bool ok;
-    explicit DeviceGuard(int device) : target(device) {
-        ok = hipGetDevice(&prev) == hipSuccess && (prev == device || hipSetDevice(device) == hipSuccess);
-        if (!ok) (void)hipGetLastError();
-    }
-    ~DeviceGuard() {
-        if (ok && prev != target) DeviceGuard device_guard_(prev);
-    }
-    DeviceGuard(const DeviceGuard &) = delete;
-    DeviceGuard &operator=(const DeviceGuard &) = delete;
+struct HipDeviceApi {
+    static bool get_device(int *out) { return hipGetDevice(out) == hipSuccess; }
+    static bool set_device(int device) { return hipSetDevice(device) == hipSuccess; }
+    static void clear_error() { (void)hipGetLastError(); }
 };
+typedef srs::BasicDeviceGuard<HipDeviceApi> DeviceGuard;
 
 #define SRS_ON_DEVICE(device)            \
     DeviceGuard device_guard_(device);   \
