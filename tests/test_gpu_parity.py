@@ -461,3 +461,104 @@ def test_two_contexts_on_two_streams_run_concurrently(srs):
     finally:
         for c in ctxs:
             c.close()
+
+
+# ---------------------------------------------------------------------------------------------------------------
+# More than 65,536 buckets: the per-bucket ticket counters are then packed 4 bytes apart instead of 256, and the
+# extract, apply, encode and encoded-apply grids all exceed 65,536 workgroups with one-element tiles.
+# ---------------------------------------------------------------------------------------------------------------
+def _encoded_host(D, mg, an):
+    return D.cpu().numpy().view(np.uint16), mg.cpu().numpy().view(np.uint32), an.cpu().numpy()
+
+
+def _check_encoded(got, want):
+    gD, gm, ga = got
+    wD, wm, wa = want
+    assert np.array_equal(gm, wm), "max_gap"
+    assert np.array_equal(gD, wD), "differences (including untouched slots)"
+    assert np.array_equal(ga.reshape(-1)[:wa.size].reshape(wa.shape), wa), "anchors"
+
+
+@pytest.mark.parametrize("n,be,density", [(70_001, 1, 0.3), (140_003, 2, 0.4)])
+def test_single_tensor_more_than_65536_buckets(srs, ctx, n, be, density):
+    print(f"case many buckets single n={n} be={be}", flush=True)
+    nb = (n + be - 1) // be
+    assert nb > 65536
+    old_h, new_h = make_pair(n, density, seed=n + be)
+    wI, wV, wc, _ = oracle.extract(old_h.copy(), new_h, be)
+    got, snap, roll, flags = run_single(srs, ctx, old_h, new_h, be)
+    assert flags == 0
+    assert_payload_equal(got, (wI, wV, wc), "many buckets, single")
+    assert np.array_equal(snap, new_h) and np.array_equal(roll, new_h)
+    # index coding of the same payload and the encoded apply
+    want = oracle.encode_indices(wI, wc, base_stride=be)
+    d_old, d_new, d_roll = from_u16(old_h, DEV), from_u16(new_h, DEV), from_u16(old_h, DEV)
+    I, V, counts = srs.alloc_payload(nb, be, DEV)
+    D, mg, an = srs.alloc_encoded(nb, be, DEV)
+    ctx.extract(d_old, d_new, be, I, V, counts, be)
+    ctx.encode_indices(I, counts, nb, be, be, D, mg, an)
+    assert ctx.status() == 0
+    _check_encoded(_encoded_host(D, mg, an), want)
+    I_wide = I.clone()
+    I_wide[mg.to(torch.int64) < 32768] = -4242          # the receiver has I only for wide buckets (none here)
+    ctx.apply_encoded(d_roll, be, D, I_wide, V, counts, mg, an, be)
+    assert ctx.status() == 0
+    assert np.array_equal(u16(d_roll), new_h)
+
+
+def test_tensor_list_more_than_65536_buckets(srs, ctx):
+    numels = [50_001, 3, 0, 90_001]                        # odd sizes: tensors straddle the two-element buckets
+    be = 2
+    total = sum(numels)
+    nb = (total + be - 1) // be
+    assert nb > 65536
+    print(f"case many buckets list numels={numels} be={be}", flush=True)
+    pairs = [make_pair(max(k, 1), 0.35, seed=900 + i) for i, k in enumerate(numels)]
+    olds = [p[0][:k].copy() for p, k in zip(pairs, numels)]
+    news = [p[1][:k].copy() for p, k in zip(pairs, numels)]
+    wI, wV, wc, _ = oracle.extract_multi([o.copy() for o in olds], news, numels, be)
+    want = oracle.encode_indices(wI, wc)
+    d_old = [from_u16(o, DEV) for o in olds]
+    d_new = [from_u16(x, DEV) for x in news]
+    d_roll = [from_u16(o, DEV) for o in olds]
+    d_roll2 = [from_u16(o, DEV) for o in olds]
+    plan = ctx.plan(numels, be)
+    assert plan.nbuckets == nb
+    I, V, counts = srs.alloc_payload(nb, be, DEV)
+    D, mg, an = srs.alloc_encoded(nb, be, DEV)
+    ctx.extract_multi(plan, d_old, d_new, I, V, counts, be)
+    ctx.apply_multi(plan, d_roll, I, V, counts, be)
+    ctx.encode_indices(I, counts, nb, be, 0, D, mg, an)
+    assert ctx.status() == 0
+    assert_payload_equal(payload_to_host(I, V, counts), (wI, wV, wc), "many buckets, list")
+    _check_encoded(_encoded_host(D, mg, an), want)
+    I_wide = I.clone()
+    I_wide[mg.to(torch.int64) < 32768] = -4242
+    ctx.apply_multi_encoded(plan, d_roll2, D, I_wide, V, counts, mg, an, be)
+    assert ctx.status() == 0
+    plan.close()
+    for k in range(len(numels)):
+        if numels[k]:
+            assert np.array_equal(u16(d_old[k]), news[k]), f"snapshot of tensor {k}"
+            assert np.array_equal(u16(d_roll[k]), news[k]), f"reconstruction of tensor {k}"
+            assert np.array_equal(u16(d_roll2[k]), news[k]), f"encoded reconstruction of tensor {k}"
+
+
+def test_one_byte_elements_more_than_65536_buckets(srs, ctx):
+    n, be = 70_001, 1
+    nb = n
+    print(f"case many buckets u8 n={n} be={be}", flush=True)
+    rng = np.random.default_rng(4711)
+    old_h = rng.integers(0, 256, size=n, dtype=np.uint8)
+    new_h = old_h.copy()
+    pos = np.flatnonzero(rng.random(n) < 0.3)
+    new_h[pos] = ((old_h[pos].astype(np.uint32) + rng.integers(1, 256, size=pos.size, dtype=np.uint32)) & 0xFF).astype(np.uint8)
+    wI, wV, wc, _ = oracle.extract_u8(old_h.copy(), new_h, be)
+    d_old, d_new, d_roll = (torch.from_numpy(x.copy()).to(DEV) for x in (old_h, new_h, old_h))
+    I, V, counts = srs.alloc_payload_u8(nb, be, DEV)
+    ctx.extract_u8(d_old, d_new, be, I, V, counts, be)
+    ctx.apply_u8(d_roll, be, I, V, counts, be)
+    assert ctx.status() == 0
+    assert np.array_equal(counts.cpu().numpy().view(np.uint32), wc)
+    assert np.array_equal(I.cpu().numpy(), wI) and np.array_equal(V.cpu().numpy(), wV)
+    assert np.array_equal(d_old.cpu().numpy(), new_h) and np.array_equal(d_roll.cpu().numpy(), new_h)
