@@ -55,7 +55,8 @@ typedef enum {
     SRS_ERR_INVALID = -1,     /* null pointer, zero bucket size or capacity, size beyond int32 indexing */
     SRS_ERR_HIP = -2,         /* a HIP runtime call failed (allocation, copy, launch) */
     SRS_ERR_NOMEM = -3,       /* host allocation failed */
-    SRS_ERR_NO_DEVICE = -4    /* no usable GPU / wrong architecture */
+    SRS_ERR_NO_DEVICE = -4,   /* no usable GPU / wrong architecture */
+    SRS_ERR_TOO_LARGE = -5    /* srs_extract_noalloc: the input needs more scratch than the library's static array holds */
 } srs_error;
 
 /* device flags reported by srs_status() */
@@ -108,6 +109,20 @@ int srs_status(srs_ctx *ctx, uint32_t *flags, void *stream);
  */
 int srs_extract(srs_ctx *ctx, void *old_snapshot, const void *new_w, uint64_t n, uint64_t bucket_elems,
                 int32_t *I, uint16_t *V, uint32_t *counts, uint64_t cap, void *stream);
+
+/*
+ * srs_extract for callers that cannot allocate: code under HIP graph capture, tight serving loops, harnesses
+ * that forbid hipMalloc.  Same arguments, same payload, same snapshot refresh, same flags as srs_extract, but the
+ * tile status words and ticket counters live in a static device array of the library (9 MiB per GPU, held until
+ * the process ends) instead of the context's growable scratch, so the call never allocates, frees or
+ * synchronises, whatever its size.  Limits: at most 2^20 tiles (a bucket has ceil(bucket_elems / SRS_OPT_TILE_ELEMS)
+ * tiles: with buckets of at least one default tile of 32768 elements every n below 2^31 fits) and at most 2^18 buckets; beyond either the call returns
+ * SRS_ERR_TOO_LARGE and launches nothing.  Every context on one GPU shares that GPU's array: two such calls that
+ * overlap in time on one GPU (different streams or different contexts) race; order them on one stream.  The
+ * array keeps the previous call's contents; a small kernel at the head of each call clears what the call uses.
+ */
+int srs_extract_noalloc(srs_ctx *ctx, void *old_snapshot, const void *new_w, uint64_t n, uint64_t bucket_elems,
+                        int32_t *I, uint16_t *V, uint32_t *counts, uint64_t cap, void *stream);
 
 /*
  * Single tensor scatter (Alg. 3): weights[I[b*cap+r]] <- V[b*cap+r] for r < min(counts[b], cap).

@@ -37,8 +37,20 @@ typedef srs::BasicDeviceGuard<HipDeviceApi> DeviceGuard;
 
 }  // namespace
 
+// Scratch of the entry point that may not allocate (srs_extract_noalloc): tile status words, then ticket counters.
+// One copy per GPU, held until the process ends.  In host code `scratch` is only a handle for
+// hipGetSymbolAddress: srs_create resolves it once per context, with the context's device current, and everything
+// else (kernel arguments included) goes through the pointer kept in the context.
+namespace {
+constexpr uint64_t kStaticTiles = 1ull << 20;          // status words: 8 MiB
+constexpr uint64_t kStaticTicketWords = 1ull << 18;    // ticket counters: 1 MiB
+constexpr uint64_t kStaticScratchBytes = kStaticTiles * sizeof(unsigned long long) + kStaticTicketWords * sizeof(uint32_t);
+}  // namespace
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
 struct srs_ctx {
     int device = 0;
+    unsigned char *static_scratch = nullptr;   // this device's address of `scratch`
     unsigned long long *status = nullptr;   // tile status words
     uint64_t status_cap = 0;
     uint32_t *tickets = nullptr;            // per-bucket ticket counters
@@ -102,6 +114,23 @@ int prepare_extract(srs_ctx *ctx, uint64_t ntiles, uint64_t nb, hipStream_t st, 
     const uint32_t threads = 256;
     hipLaunchKernelGGL(prepare_extract_kernel, dim3((uint32_t)((n + threads - 1) / threads)), dim3(threads), 0, st,
                        ctx->tickets, nb, *stride, ctx->status, ntiles);
+    SRS_HIP(hipGetLastError());
+    return SRS_OK;
+}
+
+// The same on the static scratch: nothing is allocated, sizes beyond the array are refused.  Ticket counters sit
+// 256 bytes apart while they fit, 4 bytes apart above that.
+int prepare_extract_static(srs_ctx *ctx, uint64_t ntiles, uint64_t nb, hipStream_t st, uint32_t *stride,
+                           unsigned long long **status, uint32_t **tickets) {
+    if (!ctx->static_scratch) return SRS_ERR_HIP;
+    if (ntiles > kStaticTiles || nb > kStaticTicketWords) return SRS_ERR_TOO_LARGE;
+    *stride = (nb * 64u <= kStaticTicketWords) ? 64u : 1u;
+    *status = reinterpret_cast<unsigned long long *>(ctx->static_scratch);
+    *tickets = reinterpret_cast<uint32_t *>(ctx->static_scratch + kStaticTiles * sizeof(unsigned long long));
+    const uint64_t n = ntiles > nb ? ntiles : nb;
+    const uint32_t threads = 256;
+    hipLaunchKernelGGL(prepare_extract_kernel, dim3((uint32_t)((n + threads - 1) / threads)), dim3(threads), 0, st,
+                       *tickets, nb, *stride, *status, ntiles);
     SRS_HIP(hipGetLastError());
     return SRS_OK;
 }
@@ -324,7 +353,8 @@ bool encoded_args_ok(const uint16_t *D, const int32_t *I_wide, const uint16_t *V
 
 namespace {
 int extract_single(srs_ctx *ctx, void *old_snapshot, const void *new_w, uint64_t n, uint64_t bucket_elems,
-                   int32_t *I, void *V, uint32_t *counts, uint64_t cap, void *stream, bool cast, int eb = 2) {
+                   int32_t *I, void *V, uint32_t *counts, uint64_t cap, void *stream, bool cast, int eb = 2,
+                   bool static_scratch = false) {
     if (!ctx || bucket_elems == 0 || cap == 0 || n > kMaxIndexable || bucket_elems > kMaxIndexable) return SRS_ERR_INVALID;
     if (n == 0) return SRS_OK;
     if (!old_snapshot || !new_w || !I || !V || !counts) return SRS_ERR_INVALID;
@@ -348,14 +378,16 @@ int extract_single(srs_ctx *ctx, void *old_snapshot, const void *new_w, uint64_t
 
     ExtractArgs a;
     std::memset(&a, 0, sizeof(a));
-    int rc = prepare_extract(ctx, ntiles, nb, st, &a.ticket_stride);
+    int rc = static_scratch ? prepare_extract_static(ctx, ntiles, nb, st, &a.ticket_stride, &a.status, &a.tickets)
+                            : prepare_extract(ctx, ntiles, nb, st, &a.ticket_stride);
     if (rc != SRS_OK) return rc;
+    if (!static_scratch) { a.status = ctx->status; a.tickets = ctx->tickets; }
     a.old_w = (uint16_t *)old_snapshot; a.new_w = new_w; a.n = n;
     a.be = (uint32_t)bucket_elems; a.tiles_per_bucket = (uint32_t)tpb;
     a.nb = (uint32_t)nb; a.last_tiles = (uint32_t)((last_len + T - 1) / T); a.group = (uint32_t)group;
     a.ntiles = (uint32_t)ntiles;
     a.I = I; a.V = (uint16_t *)V; a.counts = counts; a.cap = cap;
-    a.status = ctx->status; a.tickets = ctx->tickets; a.flags = ctx->flags;
+    a.flags = ctx->flags;
     a.spin_limit = ctx->spin_limit;
     return launch_extract<false>(ctx, ctx->tile_elems, a, st, cast ? kSrcFp32 : kSrcBf16, eb);
 }
@@ -405,6 +437,7 @@ const char *srs_strerror(int err) {
         case SRS_ERR_HIP: return "HIP runtime call failed";
         case SRS_ERR_NOMEM: return "out of host memory";
         case SRS_ERR_NO_DEVICE: return "no usable GPU";
+        case SRS_ERR_TOO_LARGE: return "input needs more scratch than the no-allocation entry point holds";
         default: return "unknown error";
     }
 }
@@ -425,6 +458,12 @@ int srs_create(srs_ctx **out, int device) {
     if (hipMemset(ctx->flags, 0, 256) != hipSuccess || hipDeviceSynchronize() != hipSuccess) {
         (void)hipGetLastError(); (void)hipFree(ctx->flags); delete ctx; return SRS_ERR_HIP;
     }
+    // this device's copy of the static scratch array (each GPU has its own, at its own address)
+    void *sp = nullptr;
+    if (hipGetSymbolAddress(&sp, HIP_SYMBOL(scratch)) != hipSuccess || !sp || ((uintptr_t)sp & 255u)) {
+        (void)hipGetLastError(); (void)hipFree(ctx->flags); delete ctx; return SRS_ERR_HIP;
+    }
+    ctx->static_scratch = static_cast<unsigned char *>(sp);
     *out = ctx;
     return SRS_OK;
 }
@@ -482,6 +521,11 @@ int srs_status(srs_ctx *ctx, uint32_t *flags, void *stream) {
 int srs_extract(srs_ctx *ctx, void *old_snapshot, const void *new_w, uint64_t n, uint64_t bucket_elems,
                 int32_t *I, uint16_t *V, uint32_t *counts, uint64_t cap, void *stream) {
     return extract_single(ctx, old_snapshot, new_w, n, bucket_elems, I, V, counts, cap, stream, false);
+}
+
+int srs_extract_noalloc(srs_ctx *ctx, void *old_snapshot, const void *new_w, uint64_t n, uint64_t bucket_elems,
+                        int32_t *I, uint16_t *V, uint32_t *counts, uint64_t cap, void *stream) {
+    return extract_single(ctx, old_snapshot, new_w, n, bucket_elems, I, V, counts, cap, stream, false, 2, true);
 }
 
 int srs_extract_cast(srs_ctx *ctx, void *weights, const float *master, uint64_t n, uint64_t bucket_elems,

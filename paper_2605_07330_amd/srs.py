@@ -24,7 +24,7 @@ if not os.path.exists(LIB_PATH):
 
 _lib = C.CDLL(LIB_PATH)
 
-OK, ERR_INVALID, ERR_HIP, ERR_NOMEM, ERR_NO_DEVICE = 0, -1, -2, -3, -4
+OK, ERR_INVALID, ERR_HIP, ERR_NOMEM, ERR_NO_DEVICE, ERR_TOO_LARGE = 0, -1, -2, -3, -4, -5
 FLAG_OVERFLOW, FLAG_BAD_INDEX, FLAG_TIMEOUT = 1, 2, 4
 OPT_SPIN_LIMIT, OPT_TILE_ELEMS, OPT_REFRESH_GROUP, OPT_INTERLEAVE, OPT_SNAPSHOT = 1, 2, 3, 4, 5
 SNAPSHOT_REFRESH, SNAPSHOT_ROTATE = 0, 1
@@ -39,6 +39,7 @@ EXPORTS = [
     "srs_bitmap_words", "srs_mark_multi", "srs_cast_mark_multi", "srs_extract_marked_multi",
     "srs_value_chunks", "srs_encode_values", "srs_decode_values",
     "srs_extract_u8", "srs_apply_u8", "srs_extract_multi_u8", "srs_apply_multi_u8", "srs_tensor_indices",
+    "srs_extract_noalloc",
 ]
 
 
@@ -60,6 +61,7 @@ _lib.srs_version.argtypes = []
 _lib.srs_status.argtypes = [_vp, _u32p, _vp]
 _lib.srs_extract.argtypes = [_vp, _vp, _vp, _u64, _u64, _vp, _vp, _vp, _u64, _vp]
 _lib.srs_apply.argtypes = [_vp, _vp, _u64, _u64, _vp, _vp, _vp, _u64, _vp]
+_lib.srs_extract_noalloc.argtypes = _lib.srs_extract.argtypes
 _lib.srs_plan_create.argtypes = [_vp, C.POINTER(_u64), C.c_uint32, _u64, C.POINTER(_vp)]
 _lib.srs_plan_info.argtypes = [_vp, C.POINTER(_u64), _u32p, _u32p, _u32p]
 _lib.srs_plan_destroy.argtypes = [_vp]
@@ -240,6 +242,20 @@ class Context:
             _payload_ok(I, V, counts, (n + bucket_elems - 1) // bucket_elems, cap)
         _check(_lib.srs_extract(self._h, old.data_ptr(), new.data_ptr(), n, bucket_elems, I.data_ptr(), V.data_ptr(),
                                 counts.data_ptr(), cap, _stream_ptr(stream)), "srs_extract")
+
+    def extract_noalloc(self, old: torch.Tensor, new: torch.Tensor, bucket_elems: int, I: torch.Tensor,
+                        V: torch.Tensor, counts: torch.Tensor, cap: int,
+                        stream: Optional[torch.cuda.Stream] = None) -> None:
+        """srs_extract on the library's static scratch array: never allocates (see the header for its limits)."""
+        _dev16(old, "old"), _dev16(new, "new")
+        n = old.numel()
+        if new.numel() != n:
+            raise ValueError("old/new size mismatch")
+        if bucket_elems > 0 and cap > 0:
+            _payload_ok(I, V, counts, (n + bucket_elems - 1) // bucket_elems, cap)
+        _check(_lib.srs_extract_noalloc(self._h, old.data_ptr(), new.data_ptr(), n, bucket_elems, I.data_ptr(),
+                                        V.data_ptr(), counts.data_ptr(), cap, _stream_ptr(stream)),
+               "srs_extract_noalloc")
 
     def apply(self, weights: torch.Tensor, bucket_elems: int, I: torch.Tensor, V: torch.Tensor, counts: torch.Tensor,
               cap: int, stream: Optional[torch.cuda.Stream] = None) -> None:
