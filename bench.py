@@ -28,14 +28,40 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0
 
-# HBM traffic per extract launch measured with rocprofv3 --pmc (FETCH_SIZE x 2.00 + WRITE_SIZE x 1.00, the
-# factors from a 61.06 GB copy in the same runs): profiles/extract_apply_qwen3-30b-a3b.md.  Only the workload
-# that was profiled has a figure.  122.4 GB read (old + new once, tile tables, status words) + 30.9 GB written:
-# 1.83 GB of payload and the 224 M lines of the snapshot that hold a change, rewritten whole (28.7 GB for 0.61 GB
-# of changed values: the memory side charges a sparse store by the line it touches, and a whole line costs it
-# less than a part of one).
-MEASURED_TRAFFIC_BYTES = {"qwen3-30b-a3b": 153.3e9}
-MEASURED_TRAFFIC_SPLIT = {"qwen3-30b-a3b": (122.4e9, 30.9e9)}     # read, written
+# HBM traffic per launch comes from a tracked rocprofv3 summary (FETCH_SIZE / WRITE_SIZE runs of this very command,
+# scaled by what the same counters read for a device copy of known size).  The summary names the command and the
+# commit it was taken at and carries a hash of the kernel sources; when the sources have changed since, the
+# figures are withheld (null) rather than reported as if measured.
+TRAFFIC_SUMMARY = os.path.join(ROOT, "profiles", "traffic_extract_apply_qwen3-30b-a3b.txt")
+KERNEL_SOURCES = [os.path.join(ROOT, "paper_2605_07330_amd", "csrc", f)
+                  for f in ("srs_kernels.hpp", "srs.hip", "device_guard.hpp")]
+
+
+def kernel_source_hash() -> str:
+    import hashlib
+    h = hashlib.sha256()
+    for f in KERNEL_SOURCES:
+        with open(f, "rb") as fh:
+            h.update(fh.read())
+    return h.hexdigest()
+
+
+def measured_traffic(workload: str):
+    """{"extract": (read, written), "apply": (read, written)} in bytes per launch, or None when there is no
+    summary for this workload or the kernel sources are not the ones it was measured with."""
+    try:
+        kv = {}
+        with open(TRAFFIC_SUMMARY) as fh:
+            for line in fh:
+                if "=" in line and not line.lstrip().startswith("#"):
+                    k, v = line.split("=", 1)
+                    kv[k.strip()] = v.strip()
+        if kv.get("workload") != workload or kv.get("sources_sha256") != kernel_source_hash():
+            return None
+        return {"extract": (float(kv["extract_read_bytes"]), float(kv["extract_written_bytes"])),
+                "apply": (float(kv["apply_read_bytes"]), float(kv["apply_written_bytes"]))}
+    except (OSError, KeyError, ValueError):
+        return None
 
 
 def log(msg: str) -> None:
@@ -91,6 +117,103 @@ def cpu_baseline_and_check(torch, np, oracle, wl, old_ws, new_ws, payload, bucke
             log(f"oracle: {done} of {len(starts)} groups of {buckets_per_group} buckets done (last [{b_lo},{b_hi})): "
                 f"extract {t_extract:.2f}s apply {t_apply:.2f}s so far, GPU payload matches")
     return t_extract, t_apply, elems, len(starts) * buckets_per_group
+
+
+def cpu_all_cores(torch, np, oracle, wl, old_ws, new_ws, cores, buckets_per_thread):
+    """The same unmodified oracle on `cores` host threads at once, each on its own disjoint bucket range
+    (ctypes releases the interpreter lock during the call).  Host copies are made first; only the concurrent
+    oracle calls are timed (wall clock of the whole pool)."""
+    from concurrent.futures import ThreadPoolExecutor
+    be, numels = wl.bucket_elems, [t.numel for t in wl.tensors]
+    nb = wl.num_buckets
+    cores = max(1, min(cores, nb // buckets_per_thread))
+    stride = nb // cores
+    cap = int(1.5 * wl.density * be) + 8192
+    jobs = []
+    for c in range(cores):
+        b_lo = c * stride
+        b_hi = min(nb, b_lo + buckets_per_thread)
+        ks = overlapping_tensors(numels, be, b_lo, b_hi)
+        olds = [None] * len(numels); news = [None] * len(numels); rolls = [None] * len(numels)
+        for k in ks:
+            olds[k] = old_ws.tensors[k].view(torch.int16).cpu().numpy().view(np.uint16)
+            news[k] = new_ws.tensors[k].view(torch.int16).cpu().numpy().view(np.uint16)
+            rolls[k] = olds[k].copy()
+        jobs.append((b_lo, b_hi, olds, news, rolls))
+
+    def work(job):
+        b_lo, b_hi, olds, news, rolls = job
+        oI, oV, oc, _ = oracle.extract_multi(olds, news, numels, be, cap=cap, b_lo=b_lo, b_hi=b_hi)
+        oracle.apply_multi(rolls, numels, be, oI, oV, oc, b_lo=b_lo, b_hi=b_hi)
+        return int(oc.sum())
+
+    t0 = time.perf_counter()
+    with ThreadPoolExecutor(max_workers=cores) as pool:
+        changed = sum(pool.map(work, jobs))
+    wall = time.perf_counter() - t0
+    elems = sum(min(wl.numel, b_hi * be) - b_lo * be for b_lo, b_hi, *_ in jobs)
+    return wall, elems, cores, changed
+
+
+def measure_other_config(args, torch, srs, synth, cfg, densities, steps, dev):
+    """Extract + apply on another workload of the same family, three resident weight sets (snapshot, new weights,
+    rollout copy): the new weights are rebuilt, untimed, from the refreshed snapshot before every step.  Library
+    defaults; every step is checked (flags, total count against the generator's, snapshot and rollout copy
+    bit-identical to the new weights).  Returns {label: figures}."""
+    out = {}
+    wl0 = synth.workload(cfg)
+    S = synth.WeightSet(wl0, dev); W1 = synth.WeightSet(wl0, dev); R = synth.WeightSet(wl0, dev)
+    synth.fill_base(S, args.seed)
+    R.copy_from(S)
+    ctx = srs.Context(0)
+    plan = ctx.plan(S.numels, wl0.bucket_elems)
+    N = wl0.numel
+    update_no = 0
+    for dens in densities:
+        wl = synth.workload(cfg, density=dens)
+        S.wl = W1.wl = R.wl = wl              # the sets keep their storage; only the update recipe (density) changes
+        cap = (synth.payload_capacity(wl) + 7) // 8 * 8
+        I = torch.empty((plan.nbuckets, cap), dtype=torch.int32, device=dev)
+        V = torch.empty((plan.nbuckets, cap), dtype=torch.int16, device=dev)
+        counts = torch.zeros(plan.nbuckets, dtype=torch.int32, device=dev)
+        pairs = ctx.bind_pairs(plan, S.tensors, W1.tensors)
+        rolls = ctx.bind_weights(plan, R.tensors)
+        ext, app, rho = [], [], 0.0
+        for i in range(1 + steps):                       # the first step is the warm-up
+            update_no += 1
+            nchanged, _ = synth.make_update(W1, S, args.seed, step=update_no)
+            rho = nchanged / N
+            e = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+            e[0].record()
+            ctx.extract_multi(plan, None, None, I, V, counts, cap, pairs=pairs)
+            e[1].record()
+            ctx.apply_multi(plan, None, I, V, counts, cap, tensors=rolls)
+            e[2].record()
+            torch.cuda.synchronize()
+            flags = ctx.status()
+            total = int(counts.to(torch.int64).sum().item())
+            ok = flags == 0 and total == nchanged and torch.equal(S.flat.view(torch.int16), W1.flat.view(torch.int16)) \
+                and torch.equal(R.flat.view(torch.int16), W1.flat.view(torch.int16))
+            if not ok and not args.no_check:
+                raise SystemExit(f"bench self-check failed ({wl.name}, density {dens}): flags={flags} counts={total} "
+                                 f"expected={nchanged}")
+            if i > 0:
+                ext.append(e[0].elapsed_time(e[1])); app.append(e[1].elapsed_time(e[2]))
+        e_ms, a_ms = sum(ext) / len(ext), sum(app) / len(app)
+        b_e, b_a = (4.0 + 8.0 * rho) * N, 8.0 * rho * N
+        label = wl.name if len(densities) == 1 else f"{wl.name}@{dens:g}"
+        out[label] = {"elements": N, "buckets": plan.nbuckets, "changed_fraction": round(rho, 6),
+                      "extract_ms": round(e_ms, 4), "apply_ms": round(a_ms, 4), "sync_ms": round(e_ms + a_ms, 4),
+                      "frac": round(b_e / (e_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+                      "frac_combined": round((b_e + b_a) / ((e_ms + a_ms) * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+                      "dense_gbs_scanned": round(4.0 * N / ((e_ms + a_ms) * 1e-3) / 1e9, 1), "steps": steps}
+        log(f"{label}: rho {rho:.5f}, extract {e_ms:.3f} ms = {100 * out[label]['frac']:.1f}% of peak on (4 + 8 rho) N, "
+            f"apply {a_ms:.3f} ms, combined {100 * out[label]['frac_combined']:.1f}%")
+        del I, V, counts
+    plan.close(); ctx.close()
+    del S, W1, R
+    torch.cuda.empty_cache()
+    return out
 
 
 def bench_cast(args, torch, srs, synth, wl, dev) -> int:
@@ -400,6 +523,13 @@ def main() -> int:
     ap.add_argument("--cpu-groups", type=int, default=36,
                     help="oracle sample: groups of 16 buckets spread over the set (36 groups = 63 %% of the default "
                          "workload, about 12 s of single-thread oracle work)")
+    ap.add_argument("--cpu-cores", type=int, default=0,
+                    help="threads of the all-cores oracle leg (0 = the host's cores, at most 16: a one-GPU box's share)")
+    ap.add_argument("--no-other-configs", action="store_true",
+                    help="skip the other workloads (Qwen3-8B-shaped, skewed 30B-A3B, Qwen3-32B-shaped at three "
+                         "densities) that the default run times after the headline")
+    ap.add_argument("--print-source-hash", action="store_true",
+                    help="print the hash of the kernel sources that a traffic summary under profiles/ must carry, and exit")
     ap.add_argument("--probe", action="store_true", help="also time the two-stream read probe")
     ap.add_argument("--no-check", action="store_true", help="skip the result checks (kernel experiments only)")
     ap.add_argument("--index-coding", action="store_true",
@@ -428,6 +558,9 @@ def main() -> int:
                          "fit otherwise; step time is then the sum of the per-step event times")
     args = ap.parse_args()
 
+    if args.print_source_hash:
+        print(kernel_source_hash())
+        return 0
     if args.gpus != 1:
         print("bench.py: this build measures one GPU only (the path has no cross-GPU step); run with --gpus 1",
               file=sys.stderr)
@@ -586,6 +719,7 @@ def main() -> int:
     if not ok and not args.no_check:
         raise SystemExit(f"bench self-check failed: flags={flags} counts={total_counts} expected={nchanged}")
 
+    nbuckets = plan.nbuckets
     ext_ms = [e[0].elapsed_time(e[1]) for e in events]
     app_ms = [e[1].elapsed_time(e[2]) for e in events]
     ext_avg, app_avg = sum(ext_ms) / len(ext_ms), sum(app_ms) / len(app_ms)
@@ -611,6 +745,7 @@ def main() -> int:
             f"value stream {wire / 1e9:.3f} GB against {2 * nchanged / 1e9:.3f} GB raw: alpha = {wire / (2 * nchanged):.4f}")
 
     probe_gbs = None
+    a = b = sink = old_ws = new_ws = None
     if args.probe or not (args.regen or args.tiny):     # context for the roofline: what two plain read streams reach here
         nbytes = min(2 * N, 16 << 30) // 32768 * 32768
         sink = torch.empty(srs.stream_probe_sink_words(nbytes), dtype=torch.int32, device=dev)
@@ -632,7 +767,7 @@ def main() -> int:
         rotating = rotating_leg(args, torch, srs, wl, versions, R, (I, V, counts), cap, args.warmup + args.steps,
                                 nchanged, rho, N)
 
-    cpu = None
+    cpu = cpu_mt = None
     if not args.no_cpu_baseline and not args.regen:
         import oracle
         # one more (untimed) step in a known direction, then the oracle on a sample of its buckets
@@ -647,9 +782,46 @@ def main() -> int:
         cpu = {"value": round(4.0 * elems / (te + ta) / 1e9, 3), "unit": "GB/s", "cores": 1, "kind": "oracle",
                "sample": f"{elems} elements ({elems / N * 100:.1f}% of the workload) in groups of {bpg} buckets spread "
                          f"over the set; oracle extract {te:.2f}s + apply {ta:.2f}s, compute only"}
+        # the same oracle on all host cores at once, disjoint bucket ranges (a one-GPU machine's share is 16 cores)
+        ncpu = os.cpu_count() or 1
+        cores = args.cpu_cores or min(ncpu, 16)
+        if not args.tiny and cores > 1:
+            wall, elems_mt, used, changed_mt = cpu_all_cores(torch, np, oracle, wl, old_ws, new_ws, cores, min(6, plan.nbuckets))
+            cpu_mt = {"value": round(4.0 * elems_mt / wall / 1e9, 3), "unit": "GB/s", "cores": used, "kind": "oracle",
+                      "host_cpus": ncpu,
+                      "sample": f"{elems_mt} elements ({elems_mt / N * 100:.1f}% of the workload): {used} threads, each the "
+                                f"unmodified oracle (extract + apply) on its own run of buckets; wall {wall:.2f}s, "
+                                f"{changed_mt} changed elements found"}
+            log(f"oracle on {used} threads (host reports {ncpu} CPUs): {cpu_mt['value']} GB/s of dense bytes scanned "
+                f"against {cpu['value']} on one")
 
     default_run = not (args.tiny or args.density or args.tile or args.interleave or args.refresh_group >= 0
-                       or args.index_coding or args.value_coding or args.rotate_snapshot)
+                       or args.index_coding or args.value_coding or args.rotate_snapshot or args.regen or args.config != 2)
+    traffic = measured_traffic(wl.name) if default_run else None
+    tr_e = traffic["extract"] if traffic else None
+    tr_a = traffic["apply"] if traffic else None
+    ach_a = bytes_apply / (app_avg * 1e-3) / 1e9
+
+    # the other workloads of the family, each with the library defaults (the headline's buffers are released first)
+    others = None
+    if default_run and not args.no_other_configs:
+        for pl in plans:
+            pl.close()
+        ctx.close()
+        plans, ctx = [], None
+        # every name that still holds (a view of) the headline's buffers
+        W0 = W1 = S = R = I = V = counts = versions = pairs = rolls = plan = last_new = None
+        a = b = sink = old_ws = new_ws = None
+        import gc
+        gc.collect()
+        torch.cuda.empty_cache()
+        free_b, total_b = torch.cuda.mem_get_info()
+        log(f"headline buffers released: {free_b / 2**30:.0f} of {total_b / 2**30:.0f} GiB free")
+        others = {}
+        others.update(measure_other_config(args, torch, srs, synth, 1, [0.01], 3, dev))
+        others.update(measure_other_config(args, torch, srs, synth, 3, [None], 2, dev))
+        others.update(measure_other_config(args, torch, srs, synth, 4, [0.001, 0.01, 0.1], 3, dev))
+
     out = {
         "metric": "extract+apply dense GB/s scanned",
         "value": round(value, 1),
@@ -663,7 +835,7 @@ def main() -> int:
         "vs_baseline": None,
         "dtype": "u16",
         "data": "synthetic",
-        "config": {"workload": wl.name, "elements": N, "buckets": plan.nbuckets, "bucket_elems": wl.bucket_elems,
+        "config": {"workload": wl.name, "elements": N, "buckets": nbuckets, "bucket_elems": wl.bucket_elems,
                    "changed_fraction": round(rho, 6), "payload_cap": cap, "tile_elems": args.tile or 32768,
                    "index_coding": bool(args.index_coding),
                    "snapshot": "rotate" if args.rotate_snapshot else "refresh-in-place"},
@@ -672,25 +844,35 @@ def main() -> int:
         "apply_ms": round(app_avg, 4),
         "pct_hbm_peak_combined": round(100 * combined / HBM_PEAK_GBS, 2),
         "pct_hbm_peak_extract": round(100 * ach / HBM_PEAK_GBS, 2),
-        "apply_strict_gbs": round(bytes_apply / (app_avg * 1e-3) / 1e9, 1),
-        # line model for iid changes: payload read + read-modify-write of every 128-byte line that holds a change
-        "apply_line_model_gbs": round((6.0 * rho * N + 2 * 128.0 * (N / 64.0) * (1.0 - (1.0 - rho) ** 64)) / (app_avg * 1e-3) / 1e9, 1),
         "read_probe_gbs": None if probe_gbs is None else round(probe_gbs, 1),
+        # dominant kernel.  achieved = algorithmic bytes (4 + 8 rho) N per launch / HIP-event time of the launch;
+        # traffic = L2 <-> fabric bytes per launch from the tracked counter summary (nothing is read twice; the
+        # excess is the snapshot's changed lines written whole, the cheaper way to write them)
         "roofline": {"bound": "hbm", "kernel": "extract_kernel", "achieved": round(ach, 1), "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": round(ach / HBM_PEAK_GBS, 4),
-                     "traffic": MEASURED_TRAFFIC_BYTES.get(wl.name) if default_run else None,
-                     # nothing is read twice (2N = 122.1 GB of weights); the excess over the algorithmic bytes is the
-                     # snapshot's changed lines written whole, which is the cheaper way to write them
-                     "traffic_read": MEASURED_TRAFFIC_SPLIT[wl.name][0] if default_run and wl.name in MEASURED_TRAFFIC_SPLIT else None,
-                     "traffic_written": MEASURED_TRAFFIC_SPLIT[wl.name][1] if default_run and wl.name in MEASURED_TRAFFIC_SPLIT else None},
+                     "traffic": None if tr_e is None else tr_e[0] + tr_e[1],
+                     "traffic_read": None if tr_e is None else tr_e[0],
+                     "traffic_written": None if tr_e is None else tr_e[1]},
+        # the scatter: algorithmic bytes 8 rho N (payload read + 2 bytes written per pair); `traffic` as above.
+        # line_model_gbs prices what the memory side has to do for iid changes -- payload read + read-modify-write
+        # of every 128-byte line that holds a change -- and is a model, not a measurement
+        "roofline_apply": {"bound": "hbm", "kernel": "apply_kernel", "achieved": round(ach_a, 1), "peak": HBM_PEAK_GBS,
+                           "unit": "GB/s", "frac": round(ach_a / HBM_PEAK_GBS, 4),
+                           "traffic": None if tr_a is None else tr_a[0] + tr_a[1],
+                           "traffic_read": None if tr_a is None else tr_a[0],
+                           "traffic_written": None if tr_a is None else tr_a[1],
+                           "line_model_gbs": round((6.0 * rho * N + 2 * 128.0 * (N / 64.0) * (1.0 - (1.0 - rho) ** 64)) / (app_avg * 1e-3) / 1e9, 1)},
         "cpu_baseline": cpu,
+        "cpu_baseline_all_cores": cpu_mt,
         "rotating_snapshot": rotating,
+        "other_configs": others,
         "checked": not args.no_check,
     }
     print(json.dumps(out), flush=True)
     for pl in plans:
         pl.close()
-    ctx.close()
+    if ctx is not None:
+        ctx.close()
     return 0
 
 

@@ -27,9 +27,12 @@
  *     the snapshot is refreshed all the same, and the caller sends that bucket as a dense copy of
  *     the new weights (the full-copy route of Sec. 3.4 for dense parameters).  Slots at and beyond
  *     counts[b] are left untouched.
- *   - Return value: SRS_OK (0) or a negative srs_error.  Nothing is launched when an error is
- *     returned.  Device-side conditions (overflow, bad index, look-back time-out) are reported
- *     through srs_status().
+ *   - Return value: SRS_OK (0) or a negative srs_error.  Argument errors (SRS_ERR_INVALID,
+ *     SRS_ERR_TOO_LARGE) are found before anything is launched or copied.  SRS_ERR_HIP reports a
+ *     failed runtime call (allocation, copy, launch); calls that issue several kernels (the encoded
+ *     applies, the value coder, every extract with its clearing kernel) may then have launched the
+ *     earlier ones, so the outputs of such a call are undefined.  Device-side conditions (overflow,
+ *     bad index, look-back time-out) are reported through srs_status().
  *   - A context serialises its own scratch memory: use one context per stream, and do not run
  *     two calls on the same context concurrently.  A plan caches the device copy of the last pointer
  *     arrays it was called with (one for extract-side pairs, one for apply-side weights) and is

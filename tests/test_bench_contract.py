@@ -38,3 +38,27 @@ def test_tiny_run_prints_one_json_line_with_the_agreed_keys():
     cpu = out["cpu_baseline"]
     assert cpu["kind"] == "oracle" and cpu["cores"] == 1 and cpu["value"] > 0 and cpu["unit"] == "GB/s" and cpu["sample"]
     assert out["checked"] is True
+    ra = out["roofline_apply"]
+    assert ra["bound"] == "hbm" and ra["kernel"] == "apply_kernel" and abs(ra["frac"] - ra["achieved"] / ra["peak"]) < 1e-3
+    assert "traffic" in ra and ra["line_model_gbs"] > 0
+    for key in ("cpu_baseline_all_cores", "other_configs", "rotating_snapshot"):
+        assert key in out, key
+
+
+def test_traffic_figures_follow_the_kernel_sources(tmp_path, monkeypatch):
+    """The HBM-traffic figures of the JSON line come from a tracked counter summary and are withheld as soon as
+    the kernel sources differ from the ones the summary was measured with."""
+    sys.path.insert(0, ROOT)
+    import bench
+    good = tmp_path / "traffic.txt"
+    good.write_text("# comment\nworkload = w\nsources_sha256 = %s\nextract_read_bytes = 10\nextract_written_bytes = 3\n"
+                    "apply_read_bytes = 2\napply_written_bytes = 9\n" % bench.kernel_source_hash())
+    monkeypatch.setattr(bench, "TRAFFIC_SUMMARY", str(good))
+    assert bench.measured_traffic("w") == {"extract": (10.0, 3.0), "apply": (2.0, 9.0)}
+    assert bench.measured_traffic("another workload") is None
+    stale = tmp_path / "stale.txt"
+    stale.write_text(good.read_text().replace(bench.kernel_source_hash(), "0" * 64))
+    monkeypatch.setattr(bench, "TRAFFIC_SUMMARY", str(stale))
+    assert bench.measured_traffic("w") is None
+    monkeypatch.setattr(bench, "TRAFFIC_SUMMARY", str(tmp_path / "missing.txt"))
+    assert bench.measured_traffic("w") is None
