@@ -35,13 +35,22 @@ def build(force: bool = False) -> str:
     return _LIB
 
 
+def build_sanitized(out: str) -> str:
+    """The same source under AddressSanitizer and UndefinedBehaviorSanitizer (gcc), for a run of the CPU tests with
+    SRS_ORACLE_LIBRARY pointing at it and gcc's libasan.so preloaded into the interpreter."""
+    subprocess.check_call(["gcc", "-O1", "-g", "-fno-omit-frame-pointer", "-fsanitize=address,undefined",
+                           "-fno-sanitize-recover=undefined", "-Wall", "-Wextra", "-shared", "-fPIC", "-o", out, _SRC])
+    return out
+
+
 _lib = None
 
 
 def _load():
     global _lib
     if _lib is None:
-        lib = C.CDLL(build())
+        # SRS_ORACLE_LIBRARY: another build of the same srs_oracle.c (e.g. with -fsanitize=address,undefined)
+        lib = C.CDLL(os.environ.get("SRS_ORACLE_LIBRARY") or build())
         u16p, i32p, u32p, u64p = (C.POINTER(C.c_uint16), C.POINTER(C.c_int32),
                                   C.POINTER(C.c_uint32), C.POINTER(C.c_uint64))
         lib.srs_oracle_extract.restype = C.c_int

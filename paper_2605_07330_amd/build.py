@@ -29,6 +29,24 @@ def build_lib(verbose: bool = False) -> str:
     return LIB
 
 
+def build_lib_host_sanitized(out: str, verbose: bool = False) -> str:
+    """libsrs.so with its HOST code under AddressSanitizer and UndefinedBehaviorSanitizer (device code as usual),
+    for CPU-only runs of the host-side tests (bucket / segment / tile tables, argument checks) with SRS_LIBRARY
+    pointing at it and clang's ASan runtime preloaded.  Never meant for a GPU machine."""
+    cmd = hipcc_command(out, extra=["-g", "-Xarch_host", "-fsanitize=address", "-Xarch_host", "-fsanitize=undefined",
+                                    "-Xarch_host", "-fno-sanitize-recover=undefined", "-Xarch_host", "-shared-libsan"])
+    if verbose:
+        print(" ".join(cmd), flush=True)
+    subprocess.check_call(cmd)
+    return out
+
+
+def clang_asan_runtime() -> str:
+    import glob
+    hits = sorted(glob.glob("/opt/rocm/lib/llvm/lib/clang/*/lib/linux/libclang_rt.asan-x86_64.so"))
+    return hits[-1] if hits else ""
+
+
 C_CONSUMER_SRC = os.path.join(ROOT, "tests", "c_abi", "roundtrip.c")
 C_CONSUMER = os.path.join(ROOT, "tests", "c_abi", "roundtrip")
 
