@@ -81,3 +81,40 @@ def test_noalloc_refuses_sizes_beyond_its_static_array():
         assert ctx.status() == 0 and int(counts.sum()) == 0
     finally:
         ctx.close()
+
+
+def test_noalloc_first_call_under_graph_capture_then_replays():
+    """What the entry point is for: a fresh context whose very first extract of this size is recorded into a HIP
+    graph (where the runtime forbids allocation and synchronisation), followed by the scatter; every replay, with the
+    program's own eager work in between, must equal the oracle on the data of that replay."""
+    from paper_2605_07330_amd import srs
+    n, be = 1_200_003, 400_001
+    nb = (n + be - 1) // be
+    cap = be
+    ctx = srs.Context(0)
+    try:
+        base_h, _ = _pair(n, 0.0, 30)
+        d_base = from_u16(base_h, DEV)
+        d_old = d_base.clone(); d_new = d_base.clone(); d_roll = d_base.clone()
+        I, V, counts = srs.alloc_payload(nb, cap, DEV)
+        torch.cuda.synchronize()
+        g = torch.cuda.CUDAGraph()
+        print("capturing srs_extract_noalloc + srs_apply", flush=True)
+        with torch.cuda.graph(g):
+            ctx.extract_noalloc(d_old, d_new, be, I, V, counts, cap)
+            ctx.apply(d_roll, be, I, V, counts, cap)
+        for rep in range(4):
+            _, new_h = _pair(n, 0.01 * (rep + 1), 30)           # same old values (same seed), denser update every time
+            d_old.copy_(d_base); d_roll.copy_(d_base); d_new.copy_(from_u16(new_h, DEV))
+            I.fill_(-1); V.fill_(-1); counts.zero_()
+            torch.cuda.synchronize()
+            print(f"replay {rep}", flush=True)
+            g.replay()
+            torch.cuda.synchronize()
+            assert ctx.status() == 0
+            wI, wV, wc, _ = oracle.extract(base_h.copy(), new_h, be, cap=cap)
+            gI, gV, gc = payload_to_host(I, V, counts)
+            assert np.array_equal(gc, wc) and np.array_equal(gI, wI) and np.array_equal(gV, wV), f"replay {rep}"
+            assert np.array_equal(u16(d_old), new_h) and np.array_equal(u16(d_roll), new_h), f"replay {rep}: weights"
+    finally:
+        ctx.close()
