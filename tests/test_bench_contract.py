@@ -62,3 +62,30 @@ def test_traffic_figures_follow_the_kernel_sources(tmp_path, monkeypatch):
     assert bench.measured_traffic("w") is None
     monkeypatch.setattr(bench, "TRAFFIC_SUMMARY", str(tmp_path / "missing.txt"))
     assert bench.measured_traffic("w") is None
+
+
+def test_all_cores_oracle_leg_runs_disjoint_bucket_runs_on_host_threads():
+    """bench.py's all-cores CPU leg: the unmodified oracle on several host threads, each on its own run of buckets.
+    On a tiny workload held in host memory the changed elements it finds must be exactly those of the buckets it
+    covered (taken from a single-threaded oracle run over the whole set)."""
+    sys.path.insert(0, ROOT)
+    import numpy as np
+    import torch
+
+    import bench
+    import oracle
+    from paper_2605_07330_amd import synth
+    wl = synth.workload(2, tiny=True)
+    a = synth.WeightSet(wl, "cpu", slab=False); b = synth.WeightSet(wl, "cpu", slab=False)
+    synth.fill_base(a, 5)
+    synth.make_update(b, a, 5)
+    numels, be, nb = a.numels, wl.bucket_elems, wl.num_buckets
+    _, _, counts, _ = oracle.extract_multi(a.to_numpy_u16(), b.to_numpy_u16(), numels, be)
+    wall, elems, used, changed = bench.cpu_all_cores(torch, np, oracle, wl, a, b, cores=3, buckets_per_thread=2)
+    assert used == min(3, nb // 2) and wall > 0
+    stride = nb // used
+    covered = [bk for c in range(used) for bk in range(c * stride, min(nb, c * stride + 2))]
+    assert len(set(covered)) == len(covered), "the threads' bucket runs must not overlap"
+    assert changed == int(counts[covered].astype(np.int64).sum())
+    assert elems == sum(min(wl.numel, (bk + 1) * be) - bk * be for bk in covered)
+    assert a.equal(a) and not a.equal(b), "the weight sets themselves are left alone (host copies are refreshed)"
