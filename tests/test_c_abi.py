@@ -32,9 +32,9 @@ def test_c_consumer_is_built_and_links_against_the_library():
 
 
 @pytest.mark.gpu
-@pytest.mark.parametrize("n,be,cap,density", [(1_000_003, 300_000, 300_000, 0.01), (70_001, 70_001, 512, 0.02),
-                                              (4096, 1000, 1000, 1.0)])
-def test_c_program_round_trip_matches_oracle(tmp_path, n, be, cap, density):
+@pytest.mark.parametrize("n,be,cap,density,mode", [(1_000_003, 300_000, 300_000, 0.01, ""), (70_001, 70_001, 512, 0.02, ""),
+                                                   (4096, 1000, 1000, 1.0, ""), (1_000_003, 300_000, 300_000, 0.01, "noalloc")])
+def test_c_program_round_trip_matches_oracle(tmp_path, n, be, cap, density, mode):
     assert os.path.exists(CONSUMER), "run __graft_entry__.build() first"
     rng = np.random.default_rng(n)
     old = rng.integers(0, 1 << 16, size=n, dtype=np.uint16)
@@ -43,9 +43,9 @@ def test_c_program_round_trip_matches_oracle(tmp_path, n, be, cap, density):
     new[pos] ^= rng.integers(1, 1 << 16, size=pos.size, dtype=np.uint16)
     (tmp_path / "old.u16").write_bytes(old.tobytes()); (tmp_path / "new.u16").write_bytes(new.tobytes())
     out = tmp_path / "out.bin"
-    print(f"c consumer: n={n} be={be} cap={cap} density={density}", flush=True)
+    print(f"c consumer: n={n} be={be} cap={cap} density={density} {mode}", flush=True)
     r = subprocess.run([CONSUMER, str(tmp_path / "old.u16"), str(tmp_path / "new.u16"), str(n), str(be), str(cap),
-                        str(out)], capture_output=True, text=True, timeout=100)
+                        str(out)] + ([mode] if mode else []), capture_output=True, text=True, timeout=100)
     assert r.returncode == 0, r.stdout + r.stderr
     nb = -(-n // be)
     raw = np.fromfile(out, dtype=np.uint8)
