@@ -155,6 +155,9 @@ def cpu_all_cores(torch, np, oracle, wl, old_ws, new_ws, cores, buckets_per_thre
     return wall, elems, cores, changed
 
 
+SECOND_PASS_BELOW = 0.002    # other_configs also time SRS_OPT_SNAPSHOT = 2 where at most this fraction changes
+
+
 def measure_other_config(args, torch, srs, synth, cfg, densities, steps, dev):
     """Extract + apply on another workload of the same family, three resident weight sets (snapshot, new weights,
     rollout copy): the new weights are rebuilt, untimed, from the refreshed snapshot before every step.  Library
@@ -202,11 +205,39 @@ def measure_other_config(args, torch, srs, synth, cfg, densities, steps, dev):
         e_ms, a_ms = sum(ext) / len(ext), sum(app) / len(app)
         b_e, b_a = (4.0 + 8.0 * rho) * N, 8.0 * rho * N
         label = wl.name if len(densities) == 1 else f"{wl.name}@{dens:g}"
+        sp_ms = None
+        if dens is not None and dens <= SECOND_PASS_BELOW:       # same steps with SRS_OPT_SNAPSHOT = 2
+            ctx2 = srs.Context(0)
+            ctx2.set_option(srs.OPT_SNAPSHOT, srs.SNAPSHOT_SECOND_PASS)
+            ctx2.set_option(srs.OPT_INTERLEAVE, 256)
+            plan2 = ctx2.plan(S.numels, wl0.bucket_elems)
+            pairs2 = ctx2.bind_pairs(plan2, S.tensors, W1.tensors)
+            sp = []
+            for i in range(1 + steps):
+                update_no += 1
+                nchanged, _ = synth.make_update(W1, S, args.seed, step=update_no)
+                e = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+                e[0].record()
+                ctx2.extract_multi(plan2, None, None, I, V, counts, cap, pairs=pairs2)
+                e[1].record()
+                torch.cuda.synchronize()
+                ok = ctx2.status() == 0 and int(counts.to(torch.int64).sum().item()) == nchanged \
+                    and torch.equal(S.flat.view(torch.int16), W1.flat.view(torch.int16))
+                if not ok and not args.no_check:
+                    raise SystemExit(f"bench self-check failed ({wl.name}, density {dens}, second-pass refresh)")
+                if i > 0:
+                    sp.append(e[0].elapsed_time(e[1]))
+            sp_ms = sum(sp) / len(sp)
+            R.copy_from(S)                               # the rollout copy follows for the next density
+            plan2.close(); ctx2.close()
+            log(f"{label}: extract with the snapshot refreshed in a second pass {sp_ms:.3f} ms against {e_ms:.3f} ms fused")
         out[label] = {"elements": N, "buckets": plan.nbuckets, "changed_fraction": round(rho, 6),
                       "extract_ms": round(e_ms, 4), "apply_ms": round(a_ms, 4), "sync_ms": round(e_ms + a_ms, 4),
                       "frac": round(b_e / (e_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
                       "frac_combined": round((b_e + b_a) / ((e_ms + a_ms) * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
                       "dense_gbs_scanned": round(4.0 * N / ((e_ms + a_ms) * 1e-3) / 1e9, 1), "steps": steps}
+        if sp_ms is not None:
+            out[label]["extract_second_pass_ms"] = round(sp_ms, 4)
         log(f"{label}: rho {rho:.5f}, extract {e_ms:.3f} ms = {100 * out[label]['frac']:.1f}% of peak on (4 + 8 rho) N, "
             f"apply {a_ms:.3f} ms, combined {100 * out[label]['frac_combined']:.1f}%")
         del I, V, counts
@@ -308,7 +339,7 @@ def bench_fp8(args, torch, srs, synth, wl, dev) -> int:
     versions = [W1, W0]
     cap = (synth.payload_capacity(wl) + 15) // 16 * 16
     out_modes = {}
-    for mode in ("refresh-in-place", "rotate"):
+    for mode in ("refresh-in-place", "rotate", "refresh-second-pass"):
         ctx = srs.Context(0)
         if args.tile:
             ctx.set_option(srs.OPT_TILE_ELEMS, args.tile)
@@ -316,8 +347,8 @@ def bench_fp8(args, torch, srs, synth, wl, dev) -> int:
             ctx.set_option(srs.OPT_INTERLEAVE, args.interleave)
         if args.refresh_group >= 0:
             ctx.set_option(srs.OPT_REFRESH_GROUP, args.refresh_group)
-        if mode == "rotate":
-            ctx.set_option(srs.OPT_SNAPSHOT, srs.SNAPSHOT_ROTATE)
+        if mode != "refresh-in-place":
+            ctx.set_option(srs.OPT_SNAPSHOT, srs.SNAPSHOT_ROTATE if mode == "rotate" else srs.SNAPSHOT_SECOND_PASS)
             if not args.interleave:
                 ctx.set_option(srs.OPT_INTERLEAVE, 256)
         plans = [ctx.plan(S.numels, be) for _ in (0, 1)]
@@ -383,6 +414,8 @@ def bench_fp8(args, torch, srs, synth, wl, dev) -> int:
         ctx.close()
     m = out_modes["refresh-in-place"]
     step_ms = m["extract_ms"] + m["apply_ms"]
+    log(f"fp8: snapshot refreshed in a second pass (SRS_OPT_SNAPSHOT = 2): extract "
+        f"{out_modes['refresh-second-pass']['extract_ms']:.3f} ms against {m['extract_ms']:.3f} ms fused")
     out = {"metric": "extract+apply dense GB/s scanned (one-byte elements)", "value": round(2.0 * N / (step_ms * 1e-3) / 1e9, 1),
            "unit": "GB/s", "n_gpus": 1, "steps": steps, "warmup": 2, "ms_per_step": round(step_ms, 4),
            "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "u8", "data": "synthetic",
@@ -391,7 +424,8 @@ def bench_fp8(args, torch, srs, synth, wl, dev) -> int:
            "extract_ms": m["extract_ms"], "apply_ms": m["apply_ms"],
            "roofline": {"bound": "hbm", "kernel": "extract_kernel<u8>", "achieved": m["achieved"], "peak": HBM_PEAK_GBS,
                         "unit": "GB/s", "frac": m["frac"], "traffic": None},
-           "rotating_snapshot": out_modes["rotate"], "cpu_baseline": cpu, "checked": not args.no_check}
+           "rotating_snapshot": out_modes["rotate"], "second_pass_snapshot": out_modes["refresh-second-pass"],
+           "cpu_baseline": cpu, "checked": not args.no_check}
     print(json.dumps(out), flush=True)
     return 0
 
@@ -552,6 +586,10 @@ def main() -> int:
                     help="SRS_OPT_SNAPSHOT = 1: extract leaves the snapshot alone and the two resident BF16 versions "
                          "swap roles every step (the new weights of one step are the snapshot of the next) -- "
                          "not the headline contract, which refreshes the snapshot in place")
+    ap.add_argument("--second-pass", action="store_true",
+                    help="SRS_OPT_SNAPSHOT = 2: the scan leaves the snapshot alone and the same call then scatters the "
+                         "payload into it (same contract as the headline; pays when few elements change) -- not the "
+                         "headline mode")
     ap.add_argument("--regen", action="store_true",
                     help="keep one new-weights version and rebuild it (untimed) before every step instead of "
                          "alternating two resident versions: 3 weight sets instead of 4, for workloads that do not "
@@ -589,6 +627,9 @@ def main() -> int:
     if args.fp8:
         return bench_fp8(args, torch, srs, synth, wl, dev)
 
+    if args.rotate_snapshot and args.second_pass:
+        print("bench.py: --rotate-snapshot and --second-pass are two values of one option", file=sys.stderr)
+        return 2
     if args.rotate_snapshot and args.regen:
         print("bench.py: --rotate-snapshot alternates two resident versions; it cannot be combined with --regen",
               file=sys.stderr)
@@ -627,6 +668,9 @@ def main() -> int:
         # with no stores into the weights this mode measures best with more buckets in flight than the in-place one
         if args.tile:
             ctx.set_option(srs.OPT_TILE_ELEMS, args.tile)
+        ctx.set_option(srs.OPT_INTERLEAVE, args.interleave or 256)
+    if args.second_pass:
+        ctx.set_option(srs.OPT_SNAPSHOT, srs.SNAPSHOT_SECOND_PASS)
         ctx.set_option(srs.OPT_INTERLEAVE, args.interleave or 256)
     # one plan per direction: each keeps its own device copy of the pointer table, so alternating the
     # `new` version does not re-upload it every step
@@ -763,7 +807,7 @@ def main() -> int:
     # the same workload under the rotating-snapshot contract (SRS_OPT_SNAPSHOT = 1), reported beside the
     # headline: an even number of steps, so that the rollout copy ends where it started
     rotating = None
-    if not (args.regen or args.rotate_snapshot or args.index_coding or args.value_coding or args.tiny):
+    if not (args.regen or args.rotate_snapshot or args.second_pass or args.index_coding or args.value_coding or args.tiny):
         rotating = rotating_leg(args, torch, srs, wl, versions, R, (I, V, counts), cap, args.warmup + args.steps,
                                 nchanged, rho, N)
 
@@ -796,7 +840,8 @@ def main() -> int:
                 f"against {cpu['value']} on one")
 
     default_run = not (args.tiny or args.density or args.tile or args.interleave or args.refresh_group >= 0
-                       or args.index_coding or args.value_coding or args.rotate_snapshot or args.regen or args.config != 2)
+                       or args.index_coding or args.value_coding or args.rotate_snapshot or args.second_pass or args.regen
+                       or args.config != 2)
     traffic = measured_traffic(wl.name) if default_run else None
     tr_e = traffic["extract"] if traffic else None
     tr_a = traffic["apply"] if traffic else None
@@ -838,7 +883,8 @@ def main() -> int:
         "config": {"workload": wl.name, "elements": N, "buckets": nbuckets, "bucket_elems": wl.bucket_elems,
                    "changed_fraction": round(rho, 6), "payload_cap": cap, "tile_elems": args.tile or 32768,
                    "index_coding": bool(args.index_coding),
-                   "snapshot": "rotate" if args.rotate_snapshot else "refresh-in-place"},
+                   "snapshot": "rotate" if args.rotate_snapshot else "refresh-second-pass" if args.second_pass
+                               else "refresh-in-place"},
         "sync_ms": round(ms_per_step, 4),
         "extract_ms": round(ext_avg, 4),
         "apply_ms": round(app_avg, 4),

@@ -6,6 +6,7 @@
 
 #include <hip/hip_runtime.h>
 
+#include <cstddef>
 #include <cstdlib>
 #include <cstring>
 #include <new>
@@ -62,7 +63,8 @@ struct srs_ctx {
     uint32_t tile_elems = 32768;
     uint32_t group = 64;                    // buckets whose tiles are interleaved over consecutive workgroups
     uint32_t refresh_group = 8;             // 8: snapshot refreshed by whole 128-byte lines (full, aligned tiles); 0: element by element
-    bool rotate_snapshot = false;           // true: extract leaves the snapshot alone, the caller swaps buffers
+    uint32_t snapshot_mode = 0;             // 0: refreshed inside the scan; 1: left alone, the caller swaps buffers;
+                                            // 2: left alone by the scan, then refreshed from the payload (second pass)
 };
 
 struct srs_plan {
@@ -143,7 +145,7 @@ int launch_extract_u8(const srs_ctx *ctx, uint32_t tile_elems, const ExtractArgs
     const dim3 grid(a.ntiles), block(kThreads);
 #define SRS_LAUNCH8(VV)                                                                                               \
     do {                                                                                                              \
-        if (ctx->rotate_snapshot) hipLaunchKernelGGL((extract_kernel<VV, MULTI, -1, kSrcBf16, 1>), grid, block, 0, st, a); \
+        if (ctx->snapshot_mode != 0) hipLaunchKernelGGL((extract_kernel<VV, MULTI, -1, kSrcBf16, 1>), grid, block, 0, st, a); \
         else if (ctx->refresh_group == 8) hipLaunchKernelGGL((extract_kernel<VV, MULTI, 8, kSrcBf16, 1>), grid, block, 0, st, a); \
         else hipLaunchKernelGGL((extract_kernel<VV, MULTI, 0, kSrcBf16, 1>), grid, block, 0, st, a);                   \
     } while (0)
@@ -179,7 +181,7 @@ int launch_extract(const srs_ctx *ctx, uint32_t tile_elems, const ExtractArgs &a
         if (src == kSrcFp32) {                                                                                        \
             if (ctx->refresh_group == 8) hipLaunchKernelGGL((extract_kernel<VV, MULTI, 8, kSrcFp32>), grid, block, 0, st, a); \
             else hipLaunchKernelGGL((extract_kernel<VV, MULTI, 0, kSrcFp32>), grid, block, 0, st, a);                 \
-        } else if (ctx->rotate_snapshot) hipLaunchKernelGGL((extract_kernel<VV, MULTI, -1>), grid, block, 0, st, a);  \
+        } else if (ctx->snapshot_mode != 0) hipLaunchKernelGGL((extract_kernel<VV, MULTI, -1>), grid, block, 0, st, a); \
         else if (ctx->refresh_group == 8) hipLaunchKernelGGL((extract_kernel<VV, MULTI, 8>), grid, block, 0, st, a);  \
         else hipLaunchKernelGGL((extract_kernel<VV, MULTI, 0>), grid, block, 0, st, a);                               \
     } while (0)
@@ -352,6 +354,45 @@ bool encoded_args_ok(const uint16_t *D, const int32_t *I_wide, const uint16_t *V
 
 
 namespace {
+// Second-pass snapshot refresh (SRS_OPT_SNAPSHOT = 2), queued behind an extract that left the snapshot alone: the
+// payload is scattered into the snapshot, and buckets whose payload was cut at cap are copied whole.  `a` is the
+// extract's own argument block; for a list the scatter reads the snapshot pointers from the extract-side table.
+uint64_t apply_chunks_per_bucket(uint64_t cap, uint64_t be) {
+    const uint64_t slots = cap < be ? cap : be;           // a bucket never holds more pairs than elements
+    return (slots + kApplyChunk - 1) / kApplyChunk;
+}
+
+bool second_pass_fits(uint64_t nb, uint64_t cap, uint64_t be) {
+    return nb * apply_chunks_per_bucket(cap, be) <= 0x7fffffffull && nb * kOverflowSplit <= 0x7fffffffull;
+}
+
+template <bool MULTI>
+int launch_second_pass(const srs_ctx *ctx, const srs_plan *plan, const ExtractArgs &a, uint64_t be, uint32_t tile_elems,
+                       int eb, hipStream_t st) {
+    const uint64_t cpb = apply_chunks_per_bucket(a.cap, be);
+    ApplyArgs s;
+    std::memset(&s, 0, sizeof(s));
+    if (MULTI) {
+        s.segs = plan->d_segs; s.seg_begin = plan->d_seg_begin; s.total = plan->total;
+        s.wptrs = reinterpret_cast<uint16_t *const *>(plan->d_pairs); s.wptr_skip = 1;
+        static_assert(sizeof(PtrPair) == 2 * sizeof(uint16_t *) && offsetof(PtrPair, old_w) == 0, "old_w of entry k is pointer 2k");
+    } else {
+        s.w = a.old_w; s.n = a.n;
+    }
+    s.be = (uint32_t)be; s.nb = a.nb; s.chunks_per_bucket = (uint32_t)cpb;
+    s.I = a.I; s.V = a.V; s.counts = a.counts; s.cap = a.cap; s.flags = ctx->flags;
+    const dim3 grid((uint32_t)((uint64_t)a.nb * cpb)), ogrid(a.nb * kOverflowSplit), block(kThreads);
+    if (eb == 1) {
+        hipLaunchKernelGGL((apply_kernel<MULTI, 1>), grid, block, 0, st, s);
+        hipLaunchKernelGGL((refresh_overflow_kernel<MULTI, 1>), ogrid, block, 0, st, a, tile_elems);
+    } else {
+        hipLaunchKernelGGL((apply_kernel<MULTI, 2>), grid, block, 0, st, s);
+        hipLaunchKernelGGL((refresh_overflow_kernel<MULTI, 2>), ogrid, block, 0, st, a, tile_elems);
+    }
+    SRS_HIP(hipGetLastError());
+    return SRS_OK;
+}
+
 int extract_single(srs_ctx *ctx, void *old_snapshot, const void *new_w, uint64_t n, uint64_t bucket_elems,
                    int32_t *I, void *V, uint32_t *counts, uint64_t cap, void *stream, bool cast, int eb = 2,
                    bool static_scratch = false) {
@@ -374,6 +415,8 @@ int extract_single(srs_ctx *ctx, void *old_snapshot, const void *new_w, uint64_t
     if (ntiles > 0x7fffffffull) return SRS_ERR_INVALID;
 
     if (nb > 0x7fffffffull) return SRS_ERR_INVALID;
+    const bool second_pass = !cast && ctx->snapshot_mode == 2;
+    if (second_pass && !second_pass_fits(nb, cap, bucket_elems)) return SRS_ERR_INVALID;
     const uint64_t group = ctx->group < nb ? ctx->group : nb;     // group * tpb <= ntiles + tpb
 
     ExtractArgs a;
@@ -389,7 +432,9 @@ int extract_single(srs_ctx *ctx, void *old_snapshot, const void *new_w, uint64_t
     a.I = I; a.V = (uint16_t *)V; a.counts = counts; a.cap = cap;
     a.flags = ctx->flags;
     a.spin_limit = ctx->spin_limit;
-    return launch_extract<false>(ctx, ctx->tile_elems, a, st, cast ? kSrcFp32 : kSrcBf16, eb);
+    rc = launch_extract<false>(ctx, ctx->tile_elems, a, st, cast ? kSrcFp32 : kSrcBf16, eb);
+    if (rc != SRS_OK || !second_pass) return rc;
+    return launch_second_pass<false>(ctx, nullptr, a, bucket_elems, ctx->tile_elems, eb, st);
 }
 }  // namespace
 
@@ -406,6 +451,8 @@ int extract_multi(srs_ctx *ctx, srs_plan *plan, const srs_tensor_pair *t,
     if (((uintptr_t)V & amask) || (((uintptr_t)I | (uintptr_t)counts) & 3u)) return SRS_ERR_INVALID;
     if (eb == 1 && plan->tile_elems < 8192) return SRS_ERR_INVALID;
     if (!pair_pointers_ok(plan, t, amask, cast ? 3u : amask, src != kSrcBitmap)) return SRS_ERR_INVALID;
+    const bool second_pass = src == kSrcBf16 && ctx->snapshot_mode == 2;
+    if (second_pass && !second_pass_fits(plan->nbuckets, cap, plan->be)) return SRS_ERR_INVALID;
     hipStream_t st = (hipStream_t)stream;
     SRS_ON_DEVICE(ctx->device);
 
@@ -422,7 +469,9 @@ int extract_multi(srs_ctx *ctx, srs_plan *plan, const srs_tensor_pair *t,
     a.status = ctx->status; a.tickets = ctx->tickets; a.flags = ctx->flags;
     a.spin_limit = ctx->spin_limit;
     a.bitmap = const_cast<uint32_t *>(bitmap); a.bitmap_words = (plan->total + 31) / 32; a.tensor_base = plan->d_tensor_base;
-    return launch_extract<true>(ctx, plan->tile_elems, a, st, src, eb);
+    rc = launch_extract<true>(ctx, plan->tile_elems, a, st, src, eb);
+    if (rc != SRS_OK || !second_pass) return rc;
+    return launch_second_pass<true>(ctx, plan, a, plan->be, plan->tile_elems, eb, st);
 }
 }  // namespace
 
@@ -496,8 +545,8 @@ int srs_set_option(srs_ctx *ctx, int option, uint64_t value) {
             if (value == 0 || value > 4096) return SRS_ERR_INVALID;
             ctx->group = (uint32_t)value; return SRS_OK;
         case SRS_OPT_SNAPSHOT:
-            if (value > 1) return SRS_ERR_INVALID;
-            ctx->rotate_snapshot = value == 1; return SRS_OK;
+            if (value > 2) return SRS_ERR_INVALID;
+            ctx->snapshot_mode = (uint32_t)value; return SRS_OK;
         default: return SRS_ERR_INVALID;
     }
 }

@@ -104,6 +104,9 @@ struct ApplyArgs {
     uint32_t be; uint32_t nb; uint32_t chunks_per_bucket;
     const int32_t *I; const uint16_t *V; const uint32_t *counts; uint64_t cap;
     uint32_t *flags;
+    // pointers to skip between two entries of wptrs: 0 for the apply-side table, 1 when wptrs is the extract-side
+    // table of PtrPair read through its old_w members (the second-pass snapshot refresh)
+    uint32_t wptr_skip;
     // 16-bit index coding (null / 0 when the payload carries 32-bit indices only)
     const uint16_t *D; const uint32_t *max_gap; const int32_t *anchors; uint64_t base_stride;
 };
@@ -884,7 +887,8 @@ __device__ __forceinline__ void scatter_pairs(const ApplyArgs &a, ApplyShared &s
                 const SegDesc d = a.segs[s_lo + s];
                 sh.off[s] = d.bucket_off;
                 // byte address of the element at bucket position 0 of this segment's tensor run
-                sh.base[s] = (unsigned long long)(uintptr_t)a.wptrs[d.tensor] + (unsigned long long)EB * d.tensor_off -
+                sh.base[s] = (unsigned long long)(uintptr_t)a.wptrs[(uint64_t)d.tensor * (1u + a.wptr_skip)] +
+                             (unsigned long long)EB * d.tensor_off -
                              (unsigned long long)EB * d.bucket_off;
             }
             if (threadIdx.x == 0) sh.off[nseg] = blen;
@@ -916,7 +920,8 @@ __device__ __forceinline__ void scatter_pairs(const ApplyArgs &a, ApplyShared &s
                 const SegDesc d = a.segs[lo];
                 const uint32_t off = i - d.bucket_off;
                 if (off >= d.len) { bad = true; continue; }     // cannot happen for a well-formed plan
-                __builtin_nontemporal_store((T)val[j], (gptr<T>)a.wptrs[d.tensor] + ((uint64_t)d.tensor_off + off));
+                __builtin_nontemporal_store((T)val[j], (gptr<T>)a.wptrs[(uint64_t)d.tensor * (1u + a.wptr_skip)] +
+                                                           ((uint64_t)d.tensor_off + off));
             }
         }
     } else {
@@ -1202,6 +1207,51 @@ __global__ __launch_bounds__(kThreads) void dense_copy_kernel(const DenseCopyArg
         for (uint32_t e = nvec * 8 + threadIdx.x; e < d.len; e += kThreads) dst[e] = src[e];
     } else {
         for (uint32_t e = threadIdx.x; e < d.len; e += kThreads) dst[e] = src[e];
+    }
+}
+
+// Second-pass snapshot refresh (Alg. 1's W_prev <- W done after the scan instead of inside it): the payload is
+// scattered into the snapshot by apply_kernel, which cannot bring a bucket up to date whose payload was cut at cap.
+// Those buckets are copied whole here.  kOverflowSplit workgroups per bucket walk its tiles (the plan's for a list,
+// runs of tile_elems for a single tensor); a bucket that did not overflow costs one load of its count.
+constexpr uint32_t kOverflowSplit = 16;
+
+template <bool MULTI, int EB>
+__global__ __launch_bounds__(kThreads) void refresh_overflow_kernel(const ExtractArgs a, uint32_t tile_elems) {
+    typedef typename Elem<EB>::type T;
+    constexpr uint32_t VE = 16u / EB;
+    const uint32_t b = blockIdx.x / kOverflowSplit, s = blockIdx.x - b * kOverflowSplit;
+    if (b >= a.nb || (uint64_t)a.counts[b] <= a.cap) return;           // uniform over the workgroup
+    uint64_t b0 = 0; uint32_t blen = 0, first = 0, nt;
+    if (MULTI) {
+        first = a.bucket_first[b];
+        nt = a.bucket_first[b + 1] - first;
+    } else {
+        b0 = (uint64_t)b * a.be;
+        blen = (uint32_t)((a.n - b0 < a.be) ? (a.n - b0) : a.be);
+        nt = (blen + tile_elems - 1) / tile_elems;
+    }
+    for (uint32_t j = s; j < nt; j += kOverflowSplit) {
+        gptr<T> dst; gptr<const T> src; uint32_t len;
+        if (MULTI) {
+            const TileDesc d = a.tiles[first + j];
+            const PtrPair p = a.ptrs[d.tensor];
+            dst = (gptr<T>)p.old_w + d.tensor_off;
+            src = (gptr<const T>)as_global(p.new_w) + d.tensor_off;
+            len = d.len;
+        } else {
+            const uint32_t off = j * tile_elems;
+            len = (blen - off < tile_elems) ? (blen - off) : tile_elems;
+            dst = (gptr<T>)a.old_w + b0 + off;
+            src = (gptr<const T>)as_global(a.new_w) + b0 + off;
+        }
+        uint32_t done = 0;
+        if (((((uintptr_t)dst) | ((uintptr_t)src)) & 15u) == 0) {
+            const uint32_t nvec = len / VE;
+            for (uint32_t v = threadIdx.x; v < nvec; v += kThreads) ((gptr<u32x4>)dst)[v] = ((gptr<const u32x4>)src)[v];
+            done = nvec * VE;
+        }
+        for (uint32_t e = done + threadIdx.x; e < len; e += kThreads) dst[e] = src[e];
     }
 }
 

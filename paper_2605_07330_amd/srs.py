@@ -27,7 +27,7 @@ _lib = C.CDLL(LIB_PATH)
 OK, ERR_INVALID, ERR_HIP, ERR_NOMEM, ERR_NO_DEVICE, ERR_TOO_LARGE = 0, -1, -2, -3, -4, -5
 FLAG_OVERFLOW, FLAG_BAD_INDEX, FLAG_TIMEOUT = 1, 2, 4
 OPT_SPIN_LIMIT, OPT_TILE_ELEMS, OPT_REFRESH_GROUP, OPT_INTERLEAVE, OPT_SNAPSHOT = 1, 2, 3, 4, 5
-SNAPSHOT_REFRESH, SNAPSHOT_ROTATE = 0, 1
+SNAPSHOT_REFRESH, SNAPSHOT_ROTATE, SNAPSHOT_SECOND_PASS = 0, 1, 2
 
 EXPORTS = [
     "srs_create", "srs_destroy", "srs_set_option", "srs_strerror", "srs_version", "srs_status",

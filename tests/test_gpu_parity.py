@@ -327,7 +327,7 @@ def test_invalid_arguments_are_rejected_before_launch(srs, ctx):
     with pytest.raises(srs.SrsError):
         ctx.set_option(srs.OPT_TILE_ELEMS, 1000)
     for opt, bad in [(srs.OPT_REFRESH_GROUP, 4), (srs.OPT_REFRESH_GROUP, 16), (srs.OPT_INTERLEAVE, 0), (srs.OPT_INTERLEAVE, 5000),
-                     (srs.OPT_SNAPSHOT, 2), (srs.OPT_SPIN_LIMIT, 0), (99, 1)]:
+                     (srs.OPT_SNAPSHOT, 3), (srs.OPT_SPIN_LIMIT, 0), (99, 1)]:
         with pytest.raises(srs.SrsError) as e:
             ctx.set_option(opt, bad)
         assert e.value.code == srs.ERR_INVALID

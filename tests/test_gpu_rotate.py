@@ -109,7 +109,7 @@ def test_option_range(srs):
     ctx = srs.Context(0)
     try:
         with pytest.raises(srs.SrsError):
-            ctx.set_option(srs.OPT_SNAPSHOT, 2)
+            ctx.set_option(srs.OPT_SNAPSHOT, 3)
         ctx.set_option(srs.OPT_SNAPSHOT, srs.SNAPSHOT_REFRESH)
     finally:
         ctx.close()
