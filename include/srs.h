@@ -90,8 +90,8 @@ typedef enum {
                                   same call scatters the payload into it (and copies a bucket whole whose payload
                                   overflowed cap), so that old_snapshot == new_w afterwards exactly as under 0.
                                   Payload, counts and flags identical.  Keeping the stores out of the read stream
-                                  pays when few elements change (at one-byte width and 0.07 % changed: 10.3 against
-                                  12.2 ms on a 30.5 G-element list; at 16 bits and 0.1 %: 3.5 % faster; from 0.3 %
+                                  pays when few elements change (at one-byte width and 0.07 % changed: 10.4 against
+                                  11.8 ms on a 30.5 G-element list, both with SRS_OPT_INTERLEAVE = 256; at 16 bits and 0.1 %: 3.5 % faster; from 0.3 %
                                   up the default is faster).  Ignored, like 1, by the fused-cast and cumulative calls. */
 
 typedef struct srs_ctx srs_ctx;    /* per-stream scratch: tile status words, per-bucket ticket counters, flag word */
