@@ -13,13 +13,15 @@ pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
 
 
-def test_graph_replays_match_eager_and_oracle():
+@pytest.mark.parametrize("snapshot_mode", [0, 2])      # refreshed inside the scan / by a second pass of the same call
+def test_graph_replays_match_eager_and_oracle(snapshot_mode):
     from paper_2605_07330_amd import srs
     wl = synth.workload(2, tiny=True)
     base = synth.WeightSet(wl, DEV); S = synth.WeightSet(wl, DEV); R = synth.WeightSet(wl, DEV); new = synth.WeightSet(wl, DEV)
     synth.fill_base(base, 91)
     ctx = srs.Context(0)
     try:
+        ctx.set_option(srs.OPT_SNAPSHOT, snapshot_mode)
         plan = ctx.plan(base.numels, wl.bucket_elems)
         cap = wl.bucket_elems
         I, V, counts = srs.alloc_payload(plan.nbuckets, cap, DEV)
