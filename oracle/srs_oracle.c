@@ -54,7 +54,9 @@
  * functions (tests/test_oracle_u8.py), plus agreement with the 16-bit functions
  * on byte patterns widened to 16 bits.
  * parity unpinned: only the BF16 pattern a NaN master weight rounds to (0x7FC0
- * here) -- the paper is silent and library casts disagree on it.
+ * here) -- the paper is silent and library casts disagree on it (no CPU pin;
+ * a GPU test compares this value with the framework's device cast, which gives
+ * the same).
  */
 #include <stdint.h>
 #include <stddef.h>

@@ -90,3 +90,35 @@ def test_tensor_lists_cast(srs, cfg, slab):
     assert int(got[2].sum()) == nchanged
     assert a.equal(b), "model parameters are not the rounded master weights"
     assert r.equal(b), "rollout reconstruction differs"
+
+
+def test_rounding_equals_the_frameworks_device_cast_nan_included(srs):
+    """The Trainer's cast runs on the GPU (Alg. 1, Sec. 3.4: the optimizer's FP32 -> BF16 copy of the training
+    stack).  On this platform PyTorch's device cast is that routine: it must give what the oracle's rounding and the
+    fused kernel give on every class of binary32 pattern -- including the NaN patterns, where the paper is silent and
+    CPU library casts differ (all of them map to the quiet NaN 0x7FC0 here)."""
+    rng = np.random.default_rng(11)
+    special = np.array([0x7FC00000, 0xFFC00000, 0x7F800001, 0xFF800001, 0x7FFFFFFF, 0xFFFFFFFF, 0x7FA00000, 0x7F80FFFF,
+                        0xFF812345, 0x7F800000, 0xFF800000, 0x00000000, 0x80000000, 0x00000001, 0x807FFFFF,
+                        0x3F808000, 0x3F818000, 0x3F807FFF, 0x3F808001, 0x7F7FFFFF, 0xFF7F8000], dtype=np.uint32)
+    nan_hi = (0x7F800001 + rng.integers(0, 0x7FFFFF, size=50000, dtype=np.uint32)) | (rng.integers(0, 2, size=50000, dtype=np.uint32) << 31)
+    m_h = np.concatenate([special, nan_hi, rng.integers(0, 1 << 32, size=400000, dtype=np.uint64).astype(np.uint32)])
+    n = m_h.size
+    d_m = torch.from_numpy(m_h.view(np.int32).copy()).to(DEV).view(torch.float32)
+    framework = u16(d_m.to(torch.bfloat16))
+    assert np.array_equal(oracle.round_bf16(m_h.view(np.float32)), framework), "oracle rounding differs from the device cast"
+    is_nan = (m_h & 0x7FFFFFFF) > 0x7F800000
+    assert is_nan.sum() > 50000 and np.all(framework[is_nan] == 0x7FC0)
+    # the fused kernel: parameters that differ from the rounded master everywhere, so that every element is emitted
+    w_h = (~framework).astype(np.uint16)
+    d_w = from_u16(w_h, DEV)
+    c = srs.Context(0)
+    try:
+        I, V, counts = srs.alloc_payload(1, n, DEV)
+        c.extract_cast(d_w, d_m, n, I, V, counts, n)
+        assert c.status() == 0
+        assert int(counts[0].item()) == n
+        assert np.array_equal(V[0].cpu().numpy().view(np.uint16), framework)
+        assert np.array_equal(u16(d_w), framework)
+    finally:
+        c.close()
