@@ -354,18 +354,20 @@ bool encoded_args_ok(const uint16_t *D, const int32_t *I_wide, const uint16_t *V
 
 
 namespace {
-// Second-pass snapshot refresh (SRS_OPT_SNAPSHOT = 2), queued behind an extract that left the snapshot alone: the
-// payload is scattered into the snapshot, and buckets whose payload was cut at cap are copied whole.  `a` is the
-// extract's own argument block; for a list the scatter reads the snapshot pointers from the extract-side table.
+// workgroups apply_kernel needs per bucket: one per chunk of kApplyChunk payload slots
 uint64_t apply_chunks_per_bucket(uint64_t cap, uint64_t be) {
     const uint64_t slots = cap < be ? cap : be;           // a bucket never holds more pairs than elements
     return (slots + kApplyChunk - 1) / kApplyChunk;
 }
 
+// do the grids of the second-pass snapshot refresh fit a launch?  (checked before anything is launched)
 bool second_pass_fits(uint64_t nb, uint64_t cap, uint64_t be) {
     return nb * apply_chunks_per_bucket(cap, be) <= 0x7fffffffull && nb * kOverflowSplit <= 0x7fffffffull;
 }
 
+// Second-pass snapshot refresh (SRS_OPT_SNAPSHOT = 2), queued behind an extract that left the snapshot alone: the
+// payload is scattered into the snapshot, and buckets whose payload was cut at cap are copied whole.  `a` is the
+// extract's own argument block; for a list the scatter reads the snapshot pointers from the extract-side table.
 template <bool MULTI>
 int launch_second_pass(const srs_ctx *ctx, const srs_plan *plan, const ExtractArgs &a, uint64_t be, uint32_t tile_elems,
                        int eb, hipStream_t st) {

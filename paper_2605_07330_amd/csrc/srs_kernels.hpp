@@ -20,6 +20,8 @@
 // mark_kernel: one optimizer step of Alg. 1's index accumulation, OR-ed into a bitmap.
 // extract_marked_kernel: the payload of the accumulated index set, gathered through the bitmap.
 // apply_kernel: the scatter of Alg. 3, W[I] <- V, one workgroup per (bucket, payload chunk).
+// refresh_overflow_kernel: whole-bucket copy for buckets whose payload overflowed, when the snapshot is refreshed
+// by scattering the payload into it after the scan (apply_kernel on the snapshot) instead of inside extract_kernel.
 // apply_encoded_kernel / encode_indices_kernel: the 16-bit index delta coding of Sec. 3.3.
 // route_kernel / dense_copy_kernel: the per-bucket sparse / dense routing of Sec. 3.4 and its full-copy route.
 //
