@@ -3,7 +3,7 @@
  * It shows that the boundary is what the header says (device pointers and sizes) and gives the GPU tests
  * one caller that is not the ctypes binding.
  *
- *   roundtrip <old.u16> <new.u16> <n> <bucket_elems> <cap> <out.bin> [noalloc]
+ *   roundtrip <old.u16> <new.u16> <n> <bucket_elems> <cap> <out.bin> [noalloc|secondpass]
  *
  * old / new: n 16-bit patterns each (host byte order).  The program extracts the difference on the GPU
  * (Alg. 1-2: indices and values of the changed elements, per bucket; the snapshot is refreshed), applies the
@@ -11,7 +11,8 @@
  *   counts[nb] (u32), I[nb*cap] (i32), V[nb*cap] (u16), snapshot[n] (u16), patched[n] (u16), flags (u32)
  * to out.bin.  Payload slots are pre-filled with -1 / 0xFFFF so that untouched slots can be checked.
  * With the trailing word `noalloc` the extraction goes through srs_extract_noalloc (static scratch) instead of
- * srs_extract; the output is the same.  Exit status 0 when every call returned SRS_OK.
+ * srs_extract; with `secondpass` the context is first given SRS_OPT_SNAPSHOT = 2 (snapshot refreshed by a scatter
+ * of the payload after the scan).  The output is the same in all three.  Exit status 0 when every call returned SRS_OK.
  */
 #define __HIP_PLATFORM_AMD__ 1
 #include <hip/hip_runtime_api.h>
@@ -50,11 +51,12 @@ static int read_file(const char *path, void *dst, size_t bytes) {
 }
 
 int main(int argc, char **argv) {
-    if (argc != 7 && !(argc == 8 && strcmp(argv[7], "noalloc") == 0)) {
-        fprintf(stderr, "usage: %s old.u16 new.u16 n bucket_elems cap out.bin [noalloc]\n", argv[0]);
+    if (argc != 7 && !(argc == 8 && (strcmp(argv[7], "noalloc") == 0 || strcmp(argv[7], "secondpass") == 0))) {
+        fprintf(stderr, "usage: %s old.u16 new.u16 n bucket_elems cap out.bin [noalloc|secondpass]\n", argv[0]);
         return 1;
     }
-    const int noalloc = argc == 8;
+    const int noalloc = argc == 8 && strcmp(argv[7], "noalloc") == 0;
+    const int secondpass = argc == 8 && strcmp(argv[7], "secondpass") == 0;
     const uint64_t n = strtoull(argv[3], NULL, 10), be = strtoull(argv[4], NULL, 10), cap = strtoull(argv[5], NULL, 10);
     if (n == 0 || be == 0 || cap == 0) return 1;
     const uint64_t nb = (n + be - 1) / be;
@@ -85,6 +87,7 @@ int main(int argc, char **argv) {
     CHECK_HIP(hipStreamCreate(&stream));
     srs_ctx *ctx = NULL;
     CHECK_SRS(srs_create(&ctx, 0));
+    if (secondpass) CHECK_SRS(srs_set_option(ctx, SRS_OPT_SNAPSHOT, 2));
     if (noalloc)
         CHECK_SRS(srs_extract_noalloc(ctx, d_snap, d_new, n, be, (int32_t *)d_I, (uint16_t *)d_V, (uint32_t *)d_counts, cap,
                                       stream));

@@ -33,7 +33,9 @@ def test_c_consumer_is_built_and_links_against_the_library():
 
 @pytest.mark.gpu
 @pytest.mark.parametrize("n,be,cap,density,mode", [(1_000_003, 300_000, 300_000, 0.01, ""), (70_001, 70_001, 512, 0.02, ""),
-                                                   (4096, 1000, 1000, 1.0, ""), (1_000_003, 300_000, 300_000, 0.01, "noalloc")])
+                                                   (4096, 1000, 1000, 1.0, ""), (1_000_003, 300_000, 300_000, 0.01, "noalloc"),
+                                                   (1_000_003, 300_000, 300_000, 0.01, "secondpass"),
+                                                   (500_001, 70_001, 512, 0.02, "secondpass")])
 def test_c_program_round_trip_matches_oracle(tmp_path, n, be, cap, density, mode):
     assert os.path.exists(CONSUMER), "run __graft_entry__.build() first"
     rng = np.random.default_rng(n)
